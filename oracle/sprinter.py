@@ -1,0 +1,165 @@
+"""The SPRINTER decode loop over a batch of independent rows, on the CPU.
+
+Test infrastructure only (see oracle/__init__.py).
+
+Per row and per generated position t (Alg. 2, the detailed listing in the
+appendix; Alg. 1 is its short form):
+  1. the draft model reads the committed prefix and yields the final hidden
+     state hf and next-token logits            (Alg. 2: q_r ~ M_q(Prefix))
+  2. a draft token is drawn from them           (Alg. 2: x ~ q_r)
+  3. the verifier scores hf; the token is accepted iff score >= tau
+                                                (Alg. 2: "if V(s(x, Prefix)) >= tau")
+  4. accepted: the draft token is committed and drafting continues
+  5. rejected: the target model is run once for that position and its sample
+     replaces the draft token                   (Alg. 2: "Run M_p Once"; Fig. 2(a)
+     caption: the target is used only to replace the rejected token)
+
+Readings of points the paper leaves open (also listed in the design notes):
+  * equality score == tau accepts (Alg. 2; Alg. 1 prints the opposite comparison).
+  * on a rejection the replacement is a fresh draw from the target distribution
+    (REPLACE); the accept-with-probability-p/q coin and the residual
+    distribution of Eq. (1) are not part of this path.
+  * the target's distribution is the one for the rejected position; the rejected
+    token is never fed to the target.
+  * target context: OWN_HISTORY = the prompt (all but its last token) plus one
+    entry per earlier target call on that row, each carrying its true position
+    id, so every target call is a single-token forward (the cost model of
+    Sec. 3.1(c) charges one F_t per rejection).  FULL_PREFIX = the target first
+    consumes every committed token it has not seen.
+  * the verifier input s(x, prefix) is the draft's final (post-norm) hidden
+    state, the vector that also feeds the LM head.
+  * a fixed number of tokens is generated; there is no end-of-sequence handling.
+
+`forced` switches the loop to replay mode: it still computes its own draft
+token, score, decision and (where the forced history has a rejection) target
+sample for every step, but commits the forced decisions and tokens, so that a
+second implementation can be compared decision by decision on identical history.
+"""
+from __future__ import annotations
+import numpy as np
+from . import philox
+
+CTX_OWN_HISTORY, CTX_FULL_PREFIX = 0, 1
+
+
+def top2_margin(y32: np.ndarray) -> float:
+    if y32.shape[0] < 2:
+        return float("inf")
+    part = np.partition(y32.astype(np.float64), -2)
+    return float(part[-1] - part[-2])
+
+
+def compact_rejected(accept_row) -> list:
+    """Ascending list of the rows whose flag is 0."""
+    return [b for b in range(len(accept_row)) if not accept_row[b]]
+
+
+def prefill(model, prompts, prompt_len):
+    """Caches holding positions 0 .. P_b-2 of every row's prompt."""
+    caches = []
+    for b in range(len(prompt_len)):
+        c = model.new_cache()
+        for j in range(int(prompt_len[b]) - 1):
+            model.step([prompts[b][j]], [j], [c], want_logits=False)
+        caches.append(c)
+    return caches
+
+
+def generate(draft, target, verifier, prompts, prompt_len, n_gen, tau, temperature, seed,
+             ctx_mode=CTX_OWN_HISTORY, forced=None, rows=None, keep_logits=False,
+             draft_caches=None, target_caches=None):
+    """Run n_gen lock-step decode steps.
+
+    draft / target : objects with new_cache() and step(tokens, positions, caches) -> (hf, logits)
+    verifier       : callable hf [M, d] -> float32 scores [M]
+    rows           : the original batch indices of the given rows (they select the
+                     random streams); default 0 .. B-1
+    forced         : None or dict(tok [B, G], accept [B, G]) for replay mode
+    Returns a dict of per-step records (see the end of the function).
+    """
+    B = len(prompt_len)
+    rows = list(range(B)) if rows is None else list(rows)
+    tau32 = np.float32(tau)
+    if draft_caches is None:
+        draft_caches = prefill(draft, prompts, prompt_len)
+    if target_caches is None:
+        target_caches = prefill(target, prompts, prompt_len)
+    seq = [list(map(int, prompts[b][:int(prompt_len[b])])) for b in range(B)]
+
+    G = n_gen
+    rec = dict(draft_tok=np.zeros((B, G), np.int32), score=np.zeros((B, G), np.float32),
+               accept=np.zeros((B, G), np.uint8), tok=np.zeros((B, G), np.int32),
+               target_tok=np.full((B, G), -1, np.int32),
+               draft_margin=np.zeros((B, G)), target_margin=np.full((B, G), np.inf),
+               rejected=[], target_positions=[[] for _ in range(B)],
+               n_target_calls=np.zeros(B, np.int64))
+    if keep_logits:
+        rec.update(draft_logits=[], draft_hidden=[], target_logits=[], target_hidden=[])
+
+    for g in range(G):
+        t = [len(seq[b]) for b in range(B)]                 # position being generated
+        # 1. draft forward on the last committed token of every row
+        hf, lq = draft.step([seq[b][-1] for b in range(B)], [t[b] - 1 for b in range(B)],
+                            draft_caches)
+        # 2. draft sample, 3. verifier decision
+        s = verifier(hf)
+        own_accept = np.zeros(B, np.uint8)
+        for b in range(B):
+            x, y32 = philox.sample(lq[b], temperature, seed, philox.STREAM_DRAFT, rows[b], t[b])
+            rec["draft_tok"][b, g] = x
+            rec["draft_margin"][b, g] = top2_margin(y32)
+            rec["score"][b, g] = s[b]
+            own_accept[b] = 1 if s[b] >= tau32 else 0
+        rec["accept"][:, g] = own_accept
+        decide = own_accept if forced is None else np.asarray(forced["accept"])[:, g]
+        rej = compact_rejected(decide)
+        rec["rejected"].append(rej)
+        # 5. the target runs once, on the rejected rows only
+        if rej:
+            if ctx_mode == CTX_FULL_PREFIX:                 # catch up on unseen committed tokens
+                for b in rej:
+                    for j in range(len(target_caches[b]), t[b] - 1):
+                        target.step([seq[b][j]], [j], [target_caches[b]], want_logits=False)
+            hp, lp = target.step([seq[b][-1] for b in rej], [t[b] - 1 for b in rej],
+                                 [target_caches[b] for b in rej])
+            for i, b in enumerate(rej):
+                yb, y32 = philox.sample(lp[i], temperature, seed, philox.STREAM_TARGET, rows[b], t[b])
+                rec["target_tok"][b, g] = yb
+                rec["target_margin"][b, g] = top2_margin(y32)
+                rec["target_positions"][b].append(t[b])
+                rec["n_target_calls"][b] += 1
+        # 4./5. commit
+        for b in range(B):
+            if forced is not None:
+                c = int(np.asarray(forced["tok"])[b, g])
+            else:
+                c = int(rec["draft_tok"][b, g]) if decide[b] else int(rec["target_tok"][b, g])
+            rec["tok"][b, g] = c
+            seq[b].append(c)
+        if keep_logits:
+            rec["draft_logits"].append(lq.copy())
+            rec["draft_hidden"].append(hf.copy())
+            rec["target_logits"].append(lp.copy() if rej else None)
+            rec["target_hidden"].append(hp.copy() if rej else None)
+
+    rec["len_q"] = np.array([len(c) for c in draft_caches])
+    rec["len_p"] = np.array([len(c) for c in target_caches])
+    rec["seq"] = seq
+    rec["draft_caches"], rec["target_caches"] = draft_caches, target_caches
+    return rec
+
+
+def pure_decode(model, prompts, prompt_len, n_gen, temperature, seed, stream, rows=None):
+    """Ordinary autoregressive sampling from one model (used to pin tau = 0 and tau > 1).
+    Written on the uncached route on purpose: the whole sequence is re-run per token."""
+    B = len(prompt_len)
+    rows = list(range(B)) if rows is None else list(rows)
+    out = np.zeros((B, n_gen), np.int32)
+    for b in range(B):
+        s = list(map(int, prompts[b][:int(prompt_len[b])]))
+        for g in range(n_gen):
+            _, logits = model.forward_full(s)
+            x, _ = philox.sample(logits[-1], temperature, seed, stream, rows[b], len(s))
+            out[b, g] = x
+            s.append(x)
+    return out
