@@ -1,0 +1,191 @@
+/*
+ * sprinter.h - C ABI of the batched SPRINTER decode step for one MI355X (gfx950).
+ *
+ * SPRINTER ("Speeding up Speculative Decoding via Sequential Approximate
+ * Verification", Sec. 3 "Algorithm", Alg. 1; detailed listing: Alg. 2 in the
+ * appendix "Full SPRINTER Algorithm") decodes with three models: a small draft
+ * LM M_q, a large target LM M_p and a tiny verifier classifier V.  Per token the
+ * draft samples x ~ q(.|prefix); the verifier scores a latent feature of the
+ * draft; if the score clears the threshold tau the token is kept, otherwise the
+ * target is run once for that position and its sample replaces the draft token
+ * (Fig. 2(a)).  This library runs that loop for B independent rows in lock step:
+ *
+ *   draft single-token forward (B rows) -> fused LM head + Gumbel-max sample
+ *   -> verifier MLP + sigmoid + threshold -> stable compaction of rejected rows
+ *   -> target single-token forward on the R rejected rows -> LM head + sample
+ *   -> scatter the replacements back, advance per-row state.
+ *
+ * Everything is enqueued on the caller's HIP stream; nothing in a step
+ * synchronises with the host (R stays on the device).  The library never
+ * allocates device memory: the caller hands over one workspace.
+ *
+ * Conventions
+ *   - "dev" pointers are device memory, "host" pointers host memory.
+ *   - every call returns 0 (SPRINTER_OK) or a negative SPRINTER_E_* code; the
+ *     text of the last error is available from sprinter_last_error().  A call
+ *     that fails validation enqueues no device work.
+ *   - matrices are row-major [out, in] ("y = W x"), in the element type chosen
+ *     by sprinter_cfg.dtype; every 1-D parameter (bias, norm gain/offset) and
+ *     the whole verifier are float32.
+ */
+#ifndef SPRINTER_H
+#define SPRINTER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SPRINTER_OK = 0,
+  SPRINTER_E_NULL = -1,      /* a required pointer is NULL */
+  SPRINTER_E_CONFIG = -2,    /* unsupported or inconsistent configuration */
+  SPRINTER_E_WORKSPACE = -3, /* workspace too small or misaligned */
+  SPRINTER_E_WEIGHTS = -4,   /* unknown name, wrong shape, or weights missing */
+  SPRINTER_E_RANGE = -5,     /* batch / length outside the configured maxima */
+  SPRINTER_E_STATE = -6,     /* call order violated (e.g. generate before prefill) */
+  SPRINTER_E_HIP = -7        /* a HIP runtime call failed */
+};
+
+enum { SPRINTER_ARCH_GPT = 0, SPRINTER_ARCH_LLAMA = 1 };
+enum { SPRINTER_F32 = 0, SPRINTER_BF16 = 1 };
+enum { SPRINTER_DRAFT = 0, SPRINTER_TARGET = 1, SPRINTER_VERIFIER = 2 };
+
+/* One decoder-only transformer.
+ *   arch 0 (GPT family)  : pre-LN LayerNorm, biases on all linear maps, tanh-GELU
+ *                          two-matrix FFN, learned absolute positions, LM head tied
+ *                          to the token embedding.
+ *   arch 1 (LLaMA family): RMSNorm, no biases, rotary positions on pairs
+ *                          (i, i + d_head/2), SwiGLU three-matrix FFN, grouped-query
+ *                          attention (n_kv_head divides n_head), separate LM head.
+ * d_head = d_model / n_head must be 64 or 128; d_model and d_ff multiples of 8. */
+typedef struct {
+  int32_t arch, n_layer, d_model, n_head, n_kv_head, d_ff, vocab, max_pos;
+  float norm_eps, rope_theta;
+} sprinter_model_cfg;
+
+/* The triple (M_q, M_p, V) and the sampling parameters (inputs of Alg. 1/2:
+ * "M_p, M_q, V, Prefix, prediction threshold tau").
+ *   ver_d_hidden  0: V = sigmoid(w2 . hf + b2), the single layer of Sec. 3.2;
+ *                >0: V = sigmoid(w2 . relu(W1 hf + b1) + b2).
+ *   hf is the draft's final hidden state after the last norm (the LM-head input).
+ *   accept <=> V >= tau (the comparison of Alg. 2), taken in float32.
+ *   temperature 0 selects greedy decoding; otherwise tokens are drawn by
+ *   Gumbel-max with Philox4x32-10 noise keyed by (seed; vocab index, position,
+ *   row, stream), so a run is reproducible from (seed, prompts) alone.
+ *   target_ctx_mode 0: the target's cache holds the prompt plus one entry per
+ *   earlier target call of that row (each with its true position id).  Other
+ *   values are rejected. */
+typedef struct {
+  sprinter_model_cfg draft, target;
+  int32_t ver_d_in, ver_d_hidden;
+  int32_t dtype;
+  int32_t max_batch, max_seq;
+  float tau, temperature;
+  uint64_t seed;
+  int32_t target_ctx_mode;
+  int32_t reserved;
+} sprinter_cfg;
+
+/* Optional per-step outputs of sprinter_step; every field is a device pointer
+ * or NULL.  B = batch of the last prefill, R = number of rejected rows.
+ *   draft_tok[B]      token sampled from the draft (Alg. 2 "x ~ q_r")
+ *   score[B]          verifier output in (0,1)
+ *   accept[B]         1 iff score >= tau
+ *   rej_idx[B]        first R entries: rejected rows in ascending order
+ *   n_rej[1]          R
+ *   committed_tok[B]  token appended to the row (draft token or target sample)
+ *   draft_logits[B,V] draft_hidden[B,d_q]   float32, before noise / after last norm
+ *   target_logits[B,V] target_hidden[B,d_p] rows 0..R-1 in rej_idx order */
+typedef struct {
+  int32_t* draft_tok;
+  float* score;
+  uint8_t* accept;
+  int32_t* rej_idx;
+  int32_t* n_rej;
+  int32_t* committed_tok;
+  float* draft_logits;
+  float* draft_hidden;
+  float* target_logits;
+  float* target_hidden;
+} sprinter_step_out;
+
+/* Counters since the last prefill (the paper's "Avg Tokens" and the number of
+ * target invocations follow from them). */
+typedef struct {
+  int64_t steps;              /* decode steps executed */
+  int64_t steps_with_target;  /* steps in which at least one row was rejected */
+  int64_t sum_rejected;       /* total target row-invocations = sum over steps of R */
+  int32_t batch;
+  int32_t reserved;
+} sprinter_stats;
+
+typedef struct sprinter_ctx sprinter_ctx;
+
+/* Bytes of device workspace sprinter_create needs for cfg (KV caches of both
+ * models for max_batch x max_seq, tile-packed weight copies, activations, state). */
+int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes);
+
+/* Creates a context on the current device.  dev_workspace (256-byte aligned, at
+ * least sprinter_workspace_bytes) stays owned by the caller and must outlive the
+ * context; hip_stream is a hipStream_t (NULL = the default stream) on which all
+ * later work is enqueued.  Errors: NULL pointers, unsupported cfg (see field
+ * comments), workspace too small. */
+int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes,
+                    void* hip_stream, sprinter_ctx** out_ctx);
+
+/* Hands over the parameters of one model.  which: SPRINTER_DRAFT, _TARGET or
+ * _VERIFIER.  names[i] / dev_ptrs[i] / shapes[4*i..4*i+3] (unused dims 0) describe
+ * tensor i.  Names: "tok_emb" [V,d], "pos_emb" [max_pos,d] (GPT), "lm_head" [V,d]
+ * (LLaMA), "normf.g" [d], "normf.b" [d] (GPT) and per layer i "l<i>.norm1.g",
+ * "l<i>.norm1.b"*, "l<i>.wqkv" [(H+2KVH)d_h, d] (rows: Q heads, K heads, V heads),
+ * "l<i>.bqkv"*, "l<i>.wo" [d, H d_h], "l<i>.bo"*, "l<i>.norm2.g", "l<i>.norm2.b"*,
+ * GPT: "l<i>.w1" [ff,d], "l<i>.b1", "l<i>.w2" [d,ff], "l<i>.b2";
+ * LLaMA: "l<i>.wg" [ff,d], "l<i>.wu" [ff,d], "l<i>.w2" [d,ff]   (* = GPT only).
+ * Verifier: "v.w1" [h,d_in], "v.b1" [h] (h > 0 only), "v.w2" [h or d_in], "v.b2" [1].
+ * In bf16 mode matrices are copied into a tile-packed layout inside the workspace
+ * (enqueued on the stream; the originals may be freed once the stream has passed
+ * this point), except the embedding tables, which are read in place; every other
+ * tensor is BORROWED and must stay valid for the life of the context.  The call
+ * fails if a name is unknown, a shape is wrong, or a tensor of the model is absent. */
+int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names,
+                          const void* const* dev_ptrs, const int64_t* shapes, int n);
+
+/* Starts B rows: resets state and counters and fills both KV caches with
+ * positions 0 .. P_b-2 of each prompt; the first decode step then feeds the last
+ * prompt token at position P_b-1.  dev_prompt is [B, max_prompt] int32 (padding
+ * is never read), host_prompt_len[B] has 1 <= P_b <= max_prompt.  Errors:
+ * B > max_batch, P_b out of range, max_prompt > max_seq (or > max_pos), weights
+ * not loaded. */
+int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t* host_prompt_len,
+                     int B, int max_prompt);
+
+/* One decode step for all rows (the steps listed at the top).  out may be NULL.
+ * Error if no prefill was done or a row would exceed max_seq / max_pos. */
+int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out);
+
+/* n_tokens decode steps back to back without host synchronisation.  Outputs are
+ * [B, n_tokens] row-major device arrays; any of them may be NULL:
+ * committed tokens, accept flags, verifier scores, draft tokens. */
+int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uint8_t* dev_out_accept,
+                      float* dev_out_score, int32_t* dev_out_draft_tok);
+
+/* Replaces the threshold tau (takes effect for steps enqueued afterwards). */
+int sprinter_set_tau(sprinter_ctx* ctx, float tau);
+
+/* Waits for the stream and copies the counters to the host.
+ * host_target_calls, if not NULL, receives the per-row number of target calls [B]. */
+int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* host_target_calls);
+
+void sprinter_destroy(sprinter_ctx* ctx);
+
+/* Text of the last error on ctx (or of the last failed sprinter_create /
+ * sprinter_workspace_bytes in this thread when ctx is NULL).  Never NULL. */
+const char* sprinter_last_error(const sprinter_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPRINTER_H */

@@ -1,0 +1,569 @@
+// C-ABI layer of the SPRINTER decode library: validation, workspace carving,
+// weight intake and the launch sequence of prefill / step / generate.
+// All device work is issued through the launchers in kernels.hip.
+#include "../../include/sprinter.h"
+#include "internal.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+using namespace sprinter;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+struct Bump {   // 256-byte aligned bump allocator; base == nullptr only measures
+  char* base; size_t off;
+  explicit Bump(void* b) : base((char*)b), off(0) {}
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+struct Expected {      // one tensor the model needs
+  std::string name;
+  int64_t rows, cols;  // cols == 0: 1-D
+  bool pack;           // bf16 matrix that is repacked into operand tiles
+  const void** slot;   // where the usable device pointer is stored
+  void* packed;        // destination of the packed copy
+  const void** slot2;  // second consumer (tied LM head)
+  void* packed2;
+  bool seen;
+};
+
+struct Model {
+  sprinter_model_cfg cfg;
+  ModelDims md;
+  const void *tok_emb = nullptr, *pos_emb = nullptr, *lm_head = nullptr;
+  const void *normf_g = nullptr, *normf_b = nullptr;
+  std::vector<LayerW> layers;
+  std::vector<Expected> expected;
+  std::unordered_map<std::string, int> index;
+  void *kcache = nullptr, *vcache = nullptr;
+  size_t layer_stride = 0;   // elements per layer in a cache
+  ModelScratch sc;
+  int *rd_n = nullptr, *rd_b = nullptr, *rd_tok = nullptr, *rd_pos = nullptr, *rd_slot = nullptr;
+  bool loaded = false;
+  RowDesc rd() const { return RowDesc{rd_n, rd_b, rd_tok, rd_pos, rd_slot}; }
+};
+
+}  // namespace
+
+struct sprinter_ctx {
+  sprinter_cfg cfg;
+  hipStream_t stream;
+  Model draft, target;
+  // verifier
+  const void *v_w1 = nullptr, *v_b1 = nullptr, *v_w2 = nullptr, *v_b2 = nullptr;
+  std::vector<Expected> v_expected;
+  std::unordered_map<std::string, int> v_index;
+  bool v_loaded = false;
+  float* ver_part = nullptr;
+  int ver_chunks = 1;
+  // state
+  State st;
+  float* tau_dev = nullptr;
+  int *draft_tok = nullptr, *rej_idx = nullptr, *n_rej = nullptr, *committed = nullptr;
+  float* score = nullptr;
+  unsigned char* accept = nullptr;
+  int rows_alloc = 0;
+  // host bookkeeping
+  int B = 0, max_prompt_len = 0;
+  long long steps_done = 0;
+  bool prefilled = false;
+  char err[512];
+};
+
+namespace {
+
+int fail(sprinter_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) snprintf(ctx->err, sizeof ctx->err, "%s", buf);
+  snprintf(g_err, sizeof g_err, "%s", buf);
+  return code;
+}
+
+int rows_alloc_for(int max_batch) {
+  if (max_batch <= 16) return 16;
+  if (max_batch <= 32) return 32;
+  if (max_batch <= 64) return 64;
+  return round_up(max_batch, 128);
+}
+
+size_t esize(int dtype) { return dtype == SPRINTER_F32 ? 4 : 2; }
+// elements of an activation buffer [rows, K] in the activation layout
+size_t act_plane(int dtype, int rows, int K) { return (size_t)rows * (dtype == SPRINTER_F32 ? K : round_up(K, 32)); }
+// bf16 mode keeps every activation as hi + lo in two planes
+size_t act_elems(int dtype, int rows, int K) { return act_plane(dtype, rows, K) * (dtype == SPRINTER_F32 ? 1 : 2); }
+size_t packed_elems(int N, int K) { return (size_t)round_up(N, 16) * round_up(K, 32); }
+
+const char* check_model(const sprinter_model_cfg& m, const char* who, char* buf, size_t n) {
+#define BAD(...) do { snprintf(buf, n, __VA_ARGS__); return buf; } while (0)
+  if (m.arch != SPRINTER_ARCH_GPT && m.arch != SPRINTER_ARCH_LLAMA) BAD("%s: unknown arch %d", who, m.arch);
+  if (m.n_layer < 1 || m.d_model < 8 || m.n_head < 1 || m.n_kv_head < 1 || m.d_ff < 8 || m.vocab < 2 || m.max_pos < 2)
+    BAD("%s: non-positive dimension", who);
+  if (m.d_model % m.n_head) BAD("%s: d_model %d not divisible by n_head %d", who, m.d_model, m.n_head);
+  int dh = m.d_model / m.n_head;
+  if (dh != 64 && dh != 128) BAD("%s: head dimension %d is not 64 or 128", who, dh);
+  if (m.n_head % m.n_kv_head) BAD("%s: n_head %d not divisible by n_kv_head %d", who, m.n_head, m.n_kv_head);
+  int G = m.n_head / m.n_kv_head;
+  if (G != 1 && G != 2 && G != 4 && G != 8) BAD("%s: %d query heads per KV head unsupported (1, 2, 4, 8)", who, G);
+  if (m.d_model % 8 || m.d_ff % 8) BAD("%s: d_model and d_ff must be multiples of 8", who);
+  if (m.d_model > 8192) BAD("%s: d_model %d > 8192", who, m.d_model);
+  if (!(m.norm_eps >= 0.f)) BAD("%s: norm_eps", who);
+  if (m.arch == SPRINTER_ARCH_LLAMA && !(m.rope_theta > 1.f)) BAD("%s: rope_theta", who);
+  return nullptr;
+#undef BAD
+}
+
+int validate_cfg(const sprinter_cfg* c, char* buf, size_t n) {
+  const char* e;
+  if ((e = check_model(c->draft, "draft", buf, n))) return SPRINTER_E_CONFIG;
+  if ((e = check_model(c->target, "target", buf, n))) return SPRINTER_E_CONFIG;
+#define BAD(...) do { snprintf(buf, n, __VA_ARGS__); return SPRINTER_E_CONFIG; } while (0)
+  if (c->draft.vocab != c->target.vocab) BAD("draft and target vocabularies differ (%d vs %d)", c->draft.vocab, c->target.vocab);
+  if (c->ver_d_in != c->draft.d_model) BAD("verifier input width %d != draft d_model %d", c->ver_d_in, c->draft.d_model);
+  if (c->ver_d_hidden < 0 || c->ver_d_hidden > 65536) BAD("verifier hidden width %d", c->ver_d_hidden);
+  if (c->dtype != SPRINTER_F32 && c->dtype != SPRINTER_BF16) BAD("unknown dtype %d", c->dtype);
+  if (c->max_batch < 1 || c->max_batch > 1024) BAD("max_batch %d outside [1, 1024]", c->max_batch);
+  if (c->max_seq < 2) BAD("max_seq %d < 2", c->max_seq);
+  if (c->draft.arch == SPRINTER_ARCH_GPT && c->max_seq > c->draft.max_pos) BAD("max_seq %d > draft max_pos %d", c->max_seq, c->draft.max_pos);
+  if (c->target.arch == SPRINTER_ARCH_GPT && c->max_seq > c->target.max_pos) BAD("max_seq %d > target max_pos %d", c->max_seq, c->target.max_pos);
+  if (!(c->temperature >= 0.f)) BAD("temperature must be >= 0");
+  if (!(c->tau == c->tau)) BAD("tau is NaN");
+  if (c->target_ctx_mode != 0) BAD("target_ctx_mode %d is not supported (only 0, own history)", c->target_ctx_mode);
+  for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
+    int dh = m->d_model / m->n_head, G = m->n_head / m->n_kv_head;
+    size_t lds = (size_t)(G * dh + 2 * dh + 4 * G * dh + G * c->max_seq) * 4;
+    if (lds > 64 * 1024) BAD("attention needs %zu bytes of LDS for max_seq %d (limit 65536)", lds, c->max_seq);
+  }
+  return SPRINTER_OK;
+#undef BAD
+}
+
+ModelDims dims_of(const sprinter_model_cfg& m) {
+  ModelDims d;
+  d.arch = m.arch; d.n_layer = m.n_layer; d.d = m.d_model; d.H = m.n_head; d.KVH = m.n_kv_head;
+  d.dh = m.d_model / m.n_head; d.ff = m.d_ff; d.V = m.vocab; d.max_pos = m.max_pos;
+  d.dqkv = (m.n_head + 2 * m.n_kv_head) * d.dh; d.eps = m.norm_eps; d.theta = m.rope_theta;
+  return d;
+}
+
+// Lays one model out in the workspace (or only measures when bump.base == nullptr).
+void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc, Model* m, int rows) {
+  ModelDims md = dims_of(mc);
+  const size_t es = esize(c.dtype);
+  const bool bf = c.dtype == SPRINTER_BF16;
+  size_t layer_stride = (size_t)c.max_batch * md.KVH * c.max_seq * md.dh;
+  void* kc = bump.take(layer_stride * md.n_layer * es);
+  void* vc = bump.take(layer_stride * md.n_layer * es);
+  ModelScratch sc;
+  sc.h = (float*)bump.take((size_t)rows * md.d * 4);
+  sc.xn = bump.take(act_elems(c.dtype, rows, md.d) * es);
+  sc.y = (float*)bump.take((size_t)rows * md.dqkv * 4);
+  sc.ao = bump.take(act_elems(c.dtype, rows, md.H * md.dh) * es);
+  sc.mid = bump.take(act_elems(c.dtype, rows, md.ff) * es);
+  sc.hf = (float*)bump.take((size_t)rows * md.d * 4);
+  sc.hfn = bump.take(act_elems(c.dtype, rows, md.d) * es);
+  sc.rope = (float*)bump.take((size_t)rows * md.dh * 4);
+  sc.n_lm_wg = lmhead_num_wg(c.dtype, md.V);
+  sc.am_part = (unsigned long long*)bump.take((size_t)sc.n_lm_wg * rows * 8);
+  int* rd_n = (int*)bump.take(4);
+  int* rd_b = (int*)bump.take((size_t)rows * 4);
+  int* rd_tok = (int*)bump.take((size_t)rows * 4);
+  int* rd_pos = (int*)bump.take((size_t)rows * 4);
+  int* rd_slot = (int*)bump.take((size_t)rows * 4);
+  if (m) {
+    m->cfg = mc; m->md = md; m->kcache = kc; m->vcache = vc; m->layer_stride = layer_stride; m->sc = sc;
+    m->rd_n = rd_n; m->rd_b = rd_b; m->rd_tok = rd_tok; m->rd_pos = rd_pos; m->rd_slot = rd_slot;
+    m->layers.assign(md.n_layer, LayerW{});
+    m->expected.clear();
+  }
+  auto want = [&](const std::string& name, int64_t r, int64_t cl, bool is_matrix, bool gathered, const void** slot,
+                  const void** slot2 = nullptr) {
+    bool pack = bf && is_matrix && !gathered;
+    void* dst = pack ? bump.take(packed_elems((int)r, (int)cl) * 2) : nullptr;
+    void* dst2 = (bf && slot2) ? bump.take(packed_elems((int)r, (int)cl) * 2) : nullptr;
+    if (m) m->expected.push_back(Expected{name, r, cl, pack, slot, dst, slot2, dst2, false});
+  };
+  const int d = md.d, ff = md.ff, V = md.V;
+  const bool gpt = md.arch == SPRINTER_ARCH_GPT;
+  Model dummy;
+  Model* t = m ? m : &dummy;
+  if (!m) dummy.layers.assign(md.n_layer, LayerW{});
+  want("tok_emb", V, d, true, true, &t->tok_emb, gpt ? &t->lm_head : nullptr);
+  if (gpt) want("pos_emb", md.max_pos, d, true, true, &t->pos_emb);
+  for (int i = 0; i < md.n_layer; ++i) {
+    std::string p = "l" + std::to_string(i) + ".";
+    LayerW& L = t->layers[i];
+    want(p + "norm1.g", d, 0, false, false, (const void**)&L.n1g);
+    if (gpt) want(p + "norm1.b", d, 0, false, false, (const void**)&L.n1b);
+    want(p + "wqkv", md.dqkv, d, true, false, &L.wqkv);
+    if (gpt) want(p + "bqkv", md.dqkv, 0, false, false, (const void**)&L.bqkv);
+    want(p + "wo", d, md.H * md.dh, true, false, &L.wo);
+    if (gpt) want(p + "bo", d, 0, false, false, (const void**)&L.bo);
+    want(p + "norm2.g", d, 0, false, false, (const void**)&L.n2g);
+    if (gpt) {
+      want(p + "norm2.b", d, 0, false, false, (const void**)&L.n2b);
+      want(p + "w1", ff, d, true, false, &L.w1);
+      want(p + "b1", ff, 0, false, false, (const void**)&L.b1);
+      want(p + "w2", d, ff, true, false, &L.w2);
+      want(p + "b2", d, 0, false, false, (const void**)&L.b2);
+    } else {
+      want(p + "wg", ff, d, true, false, &L.wg);
+      want(p + "wu", ff, d, true, false, &L.wu);
+      want(p + "w2", d, ff, true, false, &L.w2);
+    }
+  }
+  want("normf.g", d, 0, false, false, &t->normf_g);
+  if (gpt) want("normf.b", d, 0, false, false, &t->normf_b);
+  else want("lm_head", V, d, true, false, &t->lm_head);
+  if (m) {
+    m->index.clear();
+    for (size_t i = 0; i < m->expected.size(); ++i) m->index[m->expected[i].name] = (int)i;
+  }
+}
+
+// Lays the whole workspace out; ctx == nullptr only measures.  Returns total bytes.
+size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scratch_begin, size_t* scratch_end) {
+  Bump bump(base);
+  const int rows = rows_alloc_for(c.max_batch);
+  carve_model(bump, c, c.draft, ctx ? &ctx->draft : nullptr, rows);
+  carve_model(bump, c, c.target, ctx ? &ctx->target : nullptr, rows);
+  int chunks = verifier_num_chunks(c.ver_d_hidden);
+  float* ver_part = (float*)bump.take((size_t)chunks * c.max_batch * 4);
+  State st;
+  st.last_tok = (int*)bump.take((size_t)c.max_batch * 4);
+  st.len_q = (int*)bump.take((size_t)c.max_batch * 4);
+  st.len_p = (int*)bump.take((size_t)c.max_batch * 4);
+  st.prompt_len = (int*)bump.take((size_t)c.max_batch * 4);
+  st.n_target_calls = (long long*)bump.take((size_t)c.max_batch * 8);
+  st.counters = (long long*)bump.take(4 * 8);
+  float* tau = (float*)bump.take(4);
+  int* draft_tok = (int*)bump.take((size_t)c.max_batch * 4);
+  float* score = (float*)bump.take((size_t)c.max_batch * 4);
+  unsigned char* accept = (unsigned char*)bump.take((size_t)c.max_batch);
+  int* rej_idx = (int*)bump.take((size_t)c.max_batch * 4);
+  int* n_rej = (int*)bump.take(4);
+  int* committed = (int*)bump.take((size_t)c.max_batch * 4);
+  size_t total = (bump.off + 255) & ~(size_t)255;
+  if (ctx) {
+    ctx->ver_part = ver_part; ctx->ver_chunks = chunks; ctx->st = st; ctx->tau_dev = tau;
+    ctx->draft_tok = draft_tok; ctx->score = score; ctx->accept = accept; ctx->rej_idx = rej_idx;
+    ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows;
+  }
+  (void)scratch_begin; (void)scratch_end;
+  return total;
+}
+
+// One model forward over the rows described by rd (device-side count).
+void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool want_head, unsigned stream_id,
+             float* logits_out) {
+  const int dt = ctx->cfg.dtype;
+  const ModelDims& md = m.md;
+  hipStream_t s = ctx->stream;
+  ModelScratch& sc = m.sc;
+  const int rows = ctx->rows_alloc;
+  const size_t pl_d = act_plane(dt, rows, md.d), pl_a = act_plane(dt, rows, md.H * md.dh), pl_f = act_plane(dt, rows, md.ff);
+  launch_embed(dt, md, m.tok_emb, m.pos_emb, rd, sc.h, sc.rope, max_rows, s);
+  for (int i = 0; i < md.n_layer; ++i) {
+    const LayerW& L = m.layers[i];
+    launch_norm(dt, md.arch, sc.h, L.n1g, L.n1b, md.eps, md.d, rd.n_rows, sc.xn, pl_d, nullptr, max_rows, s);
+    launch_gemm(dt, EPI_F32, L.wqkv, nullptr, sc.xn, pl_d, rd.n_rows, md.dqkv, md.d, L.bqkv, sc.y, md.dqkv, nullptr, 0,
+                0, max_rows, s);
+    launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+                     ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
+    launch_gemm(dt, EPI_RESID, L.wo, nullptr, sc.ao, pl_a, rd.n_rows, md.d, md.H * md.dh, L.bo, sc.h, md.d, nullptr, 0,
+                0, max_rows, s);
+    launch_norm(dt, md.arch, sc.h, L.n2g, L.n2b, md.eps, md.d, rd.n_rows, sc.xn, pl_d, nullptr, max_rows, s);
+    if (md.arch == SPRINTER_ARCH_GPT)
+      launch_gemm(dt, EPI_GELU, L.w1, nullptr, sc.xn, pl_d, rd.n_rows, md.ff, md.d, L.b1, nullptr, 0, sc.mid, md.ff,
+                  pl_f, max_rows, s);
+    else
+      launch_gemm(dt, EPI_SWIGLU, L.wg, L.wu, sc.xn, pl_d, rd.n_rows, md.ff, md.d, nullptr, nullptr, 0, sc.mid, md.ff,
+                  pl_f, max_rows, s);
+    launch_gemm(dt, EPI_RESID, L.w2, nullptr, sc.mid, pl_f, rd.n_rows, md.d, md.ff, L.b2, sc.h, md.d, nullptr, 0, 0,
+                max_rows, s);
+  }
+  if (!want_head) return;
+  launch_norm(dt, md.arch, sc.h, (const float*)m.normf_g, (const float*)m.normf_b, md.eps, md.d, rd.n_rows, sc.hfn,
+              pl_d, sc.hf, max_rows, s);
+  SamplerArgs sa;
+  sa.seed_lo = (unsigned)(ctx->cfg.seed & 0xFFFFFFFFull);
+  sa.seed_hi = (unsigned)(ctx->cfg.seed >> 32);
+  sa.stream = stream_id;
+  sa.inv_temperature = ctx->cfg.temperature > 0.f ? 1.0f / ctx->cfg.temperature : 0.f;
+  launch_lmhead(dt, m.lm_head, sc.hfn, pl_d, rd, md.V, md.d, sa, sc.am_part, sc.n_lm_wg, ctx->rows_alloc, logits_out,
+                max_rows, s);
+}
+
+int check_ready(sprinter_ctx* ctx) {
+  if (!ctx->draft.loaded || !ctx->target.loaded || !ctx->v_loaded)
+    return fail(ctx, SPRINTER_E_WEIGHTS, "weights not loaded (draft %d, target %d, verifier %d)", (int)ctx->draft.loaded,
+                (int)ctx->target.loaded, (int)ctx->v_loaded);
+  return SPRINTER_OK;
+}
+
+int check_room(sprinter_ctx* ctx, long long extra_steps) {
+  if (!ctx->prefilled) return fail(ctx, SPRINTER_E_STATE, "no prefill has been done");
+  long long last_slot = (long long)ctx->max_prompt_len - 1 + ctx->steps_done + extra_steps - 1;
+  if (last_slot > ctx->cfg.max_seq - 1)
+    return fail(ctx, SPRINTER_E_RANGE, "prompt length %d + %lld generated tokens exceeds max_seq %d",
+                ctx->max_prompt_len, ctx->steps_done + extra_steps, ctx->cfg.max_seq);
+  return SPRINTER_OK;
+}
+
+void enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, int32_t* g_tok, uint8_t* g_accept,
+                  float* g_score, int32_t* g_draft_tok) {
+  hipStream_t s = ctx->stream;
+  const int B = ctx->B;
+  Model &dq = ctx->draft, &tp = ctx->target;
+  forward(ctx, dq, dq.rd(), B, true, 0u, out ? out->draft_logits : nullptr);
+  if (out && out->draft_hidden) launch_copy_f32(dq.sc.hf, out->draft_hidden, dq.rd_n, dq.md.d, B, s);
+  launch_verifier_part(dq.sc.hf, dq.md.d, ctx->cfg.ver_d_hidden, (const float*)ctx->v_w1, (const float*)ctx->v_b1,
+                       (const float*)ctx->v_w2, dq.rd_n, ctx->ver_part, B, s);
+  DecideArgs da;
+  da.am_part = dq.sc.am_part; da.n_lm_wg = dq.sc.n_lm_wg; da.Mpad = ctx->rows_alloc;
+  da.ver_part = ctx->ver_part; da.n_chunks = ctx->ver_chunks; da.b2 = (const float*)ctx->v_b2; da.tau_ptr = ctx->tau_dev;
+  da.B = B; da.st = ctx->st;
+  da.draft_tok = ctx->draft_tok; da.score = ctx->score; da.accept = ctx->accept; da.rej_idx = ctx->rej_idx;
+  da.n_rej = ctx->n_rej; da.committed = ctx->committed;
+  da.t_n_rows = tp.rd_n; da.t_b = tp.rd_b; da.t_tok = tp.rd_tok; da.t_pos = tp.rd_pos; da.t_slot = tp.rd_slot;
+  da.o_draft_tok = out ? out->draft_tok : nullptr; da.o_score = out ? out->score : nullptr;
+  da.o_accept = out ? out->accept : nullptr; da.o_rej_idx = out ? out->rej_idx : nullptr;
+  da.o_n_rej = out ? out->n_rej : nullptr;
+  launch_draft_decide(da, s);
+  forward(ctx, tp, tp.rd(), B, true, 1u, out ? out->target_logits : nullptr);
+  if (out && out->target_hidden) launch_copy_f32(tp.sc.hf, out->target_hidden, tp.rd_n, tp.md.d, B, s);
+  FinishArgs fa;
+  fa.am_part = tp.sc.am_part; fa.n_lm_wg = tp.sc.n_lm_wg; fa.Mpad = ctx->rows_alloc; fa.B = B; fa.st = ctx->st;
+  fa.draft_tok = ctx->draft_tok; fa.score = ctx->score; fa.accept = ctx->accept; fa.rej_idx = ctx->rej_idx;
+  fa.n_rej = ctx->n_rej; fa.committed = ctx->committed;
+  fa.d_n_rows = dq.rd_n; fa.d_b = dq.rd_b; fa.d_tok = dq.rd_tok; fa.d_pos = dq.rd_pos; fa.d_slot = dq.rd_slot;
+  fa.o_committed = out ? out->committed_tok : nullptr;
+  fa.n_tokens = n_tokens; fa.g_tok = g_tok; fa.g_accept = g_accept; fa.g_score = g_score; fa.g_draft_tok = g_draft_tok;
+  launch_step_finish(fa, s);
+}
+
+int hip_status(sprinter_ctx* ctx, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "%s: %s", what, hipGetErrorString(e));
+  return SPRINTER_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes) {
+  if (!cfg || !out_bytes) return fail(nullptr, SPRINTER_E_NULL, "sprinter_workspace_bytes: NULL argument");
+  char buf[256];
+  int rc = validate_cfg(cfg, buf, sizeof buf);
+  if (rc) return fail(nullptr, rc, "%s", buf);
+  *out_bytes = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
+  return SPRINTER_OK;
+}
+
+int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes, void* hip_stream,
+                    sprinter_ctx** out_ctx) {
+  if (!cfg || !dev_workspace || !out_ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_create: NULL argument");
+  *out_ctx = nullptr;
+  char buf[256];
+  int rc = validate_cfg(cfg, buf, sizeof buf);
+  if (rc) return fail(nullptr, rc, "%s", buf);
+  if (((uintptr_t)dev_workspace) & 255) return fail(nullptr, SPRINTER_E_WORKSPACE, "workspace is not 256-byte aligned");
+  size_t need = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
+  if (workspace_bytes < need)
+    return fail(nullptr, SPRINTER_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  sprinter_ctx* ctx = new sprinter_ctx();
+  ctx->cfg = *cfg;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->err[0] = 0;
+  carve(*cfg, dev_workspace, ctx, nullptr, nullptr);
+  // verifier tensors
+  auto vwant = [&](const char* name, int64_t r, int64_t c, const void** slot) {
+    ctx->v_expected.push_back(Expected{name, r, c, false, slot, nullptr, nullptr, nullptr, false});
+  };
+  if (cfg->ver_d_hidden > 0) {
+    vwant("v.w1", cfg->ver_d_hidden, cfg->ver_d_in, &ctx->v_w1);
+    vwant("v.b1", cfg->ver_d_hidden, 0, &ctx->v_b1);
+    vwant("v.w2", cfg->ver_d_hidden, 0, &ctx->v_w2);
+  } else {
+    vwant("v.w2", cfg->ver_d_in, 0, &ctx->v_w2);
+  }
+  vwant("v.b2", 1, 0, &ctx->v_b2);
+  for (size_t i = 0; i < ctx->v_expected.size(); ++i) ctx->v_index[ctx->v_expected[i].name] = (int)i;
+  // activation scratch must start at zero (padding lanes of operand tiles are never written)
+  for (Model* m : {&ctx->draft, &ctx->target}) {
+    const int rows = ctx->rows_alloc;
+    const size_t es = esize(cfg->dtype);
+    launch_fill_zero(m->sc.xn, act_elems(cfg->dtype, rows, m->md.d) * es, ctx->stream);
+    launch_fill_zero(m->sc.ao, act_elems(cfg->dtype, rows, m->md.H * m->md.dh) * es, ctx->stream);
+    launch_fill_zero(m->sc.mid, act_elems(cfg->dtype, rows, m->md.ff) * es, ctx->stream);
+    launch_fill_zero(m->sc.hfn, act_elems(cfg->dtype, rows, m->md.d) * es, ctx->stream);
+  }
+  launch_set_f32(ctx->tau_dev, cfg->tau, ctx->stream);
+  rc = hip_status(ctx, "sprinter_create");
+  if (rc) { delete ctx; return rc; }
+  *out_ctx = ctx;
+  return SPRINTER_OK;
+}
+
+int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names, const void* const* dev_ptrs,
+                          const int64_t* shapes, int n) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_load_weights: NULL context");
+  if (!names || !dev_ptrs || !shapes || n < 0) return fail(ctx, SPRINTER_E_NULL, "sprinter_load_weights: NULL argument");
+  std::vector<Expected>* exp;
+  std::unordered_map<std::string, int>* idx;
+  const char* who;
+  if (which == SPRINTER_DRAFT) { exp = &ctx->draft.expected; idx = &ctx->draft.index; who = "draft"; }
+  else if (which == SPRINTER_TARGET) { exp = &ctx->target.expected; idx = &ctx->target.index; who = "target"; }
+  else if (which == SPRINTER_VERIFIER) { exp = &ctx->v_expected; idx = &ctx->v_index; who = "verifier"; }
+  else return fail(ctx, SPRINTER_E_WEIGHTS, "unknown model selector %d", which);
+  // validate everything before touching the device
+  std::vector<int> hit(n, -1);
+  std::vector<char> seen(exp->size(), 0);
+  for (int i = 0; i < n; ++i) {
+    if (!names[i] || !dev_ptrs[i]) return fail(ctx, SPRINTER_E_NULL, "%s tensor %d: NULL name or pointer", who, i);
+    auto it = idx->find(names[i]);
+    if (it == idx->end()) return fail(ctx, SPRINTER_E_WEIGHTS, "%s: unknown tensor name '%s'", who, names[i]);
+    const Expected& e = (*exp)[it->second];
+    const int64_t* sh = shapes + 4 * i;
+    if (sh[0] != e.rows || sh[1] != e.cols || sh[2] != 0 || sh[3] != 0)
+      return fail(ctx, SPRINTER_E_WEIGHTS, "%s: tensor '%s' has shape [%lld,%lld,%lld,%lld], expected [%lld,%lld]", who,
+                  names[i], (long long)sh[0], (long long)sh[1], (long long)sh[2], (long long)sh[3], (long long)e.rows,
+                  (long long)e.cols);
+    if (seen[it->second]) return fail(ctx, SPRINTER_E_WEIGHTS, "%s: tensor '%s' given twice", who, names[i]);
+    seen[it->second] = 1;
+    hit[i] = it->second;
+  }
+  for (size_t j = 0; j < exp->size(); ++j)
+    if (!seen[j]) return fail(ctx, SPRINTER_E_WEIGHTS, "%s: tensor '%s' is missing", who, (*exp)[j].name.c_str());
+  for (int i = 0; i < n; ++i) {
+    Expected& e = (*exp)[hit[i]];
+    if (e.pack) {
+      launch_pack_bf16(dev_ptrs[i], e.packed, (int)e.rows, (int)e.cols, ctx->stream);
+      *e.slot = e.packed;
+    } else {
+      *e.slot = dev_ptrs[i];
+    }
+    if (e.slot2) {   // tied LM head
+      if (e.packed2) {
+        launch_pack_bf16(dev_ptrs[i], e.packed2, (int)e.rows, (int)e.cols, ctx->stream);
+        *e.slot2 = e.packed2;
+      } else {
+        *e.slot2 = dev_ptrs[i];
+      }
+    }
+    e.seen = true;
+  }
+  if (which == SPRINTER_DRAFT) ctx->draft.loaded = true;
+  else if (which == SPRINTER_TARGET) ctx->target.loaded = true;
+  else ctx->v_loaded = true;
+  return hip_status(ctx, "sprinter_load_weights");
+}
+
+int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t* host_prompt_len, int B,
+                     int max_prompt) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_prefill: NULL context");
+  if (!dev_prompt || !host_prompt_len) return fail(ctx, SPRINTER_E_NULL, "sprinter_prefill: NULL argument");
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if (B < 1 || B > ctx->cfg.max_batch) return fail(ctx, SPRINTER_E_RANGE, "batch %d outside [1, %d]", B, ctx->cfg.max_batch);
+  if (max_prompt < 1 || max_prompt > ctx->cfg.max_seq)
+    return fail(ctx, SPRINTER_E_RANGE, "max_prompt %d outside [1, max_seq %d]", max_prompt, ctx->cfg.max_seq);
+  int pmax = 0;
+  for (int b = 0; b < B; ++b) {
+    int P = host_prompt_len[b];
+    if (P < 1 || P > max_prompt) return fail(ctx, SPRINTER_E_RANGE, "prompt length %d of row %d outside [1, %d]", P, b, max_prompt);
+    if (P > pmax) pmax = P;
+  }
+  hipStream_t s = ctx->stream;
+  if (hipMemcpyAsync(ctx->st.prompt_len, host_prompt_len, (size_t)B * 4, hipMemcpyHostToDevice, s) != hipSuccess)
+    return fail(ctx, SPRINTER_E_HIP, "copy of prompt lengths failed");
+  ctx->B = B;
+  ctx->max_prompt_len = pmax;
+  ctx->steps_done = 0;
+  Model &dq = ctx->draft, &tp = ctx->target;
+  for (int j = 0; j + 1 < pmax; ++j) {
+    launch_prefill_prep(dev_prompt, max_prompt, j, B, ctx->st.prompt_len, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos,
+                        dq.rd_slot, s);
+    forward(ctx, dq, dq.rd(), B, false, 0u, nullptr);
+    forward(ctx, tp, dq.rd(), B, false, 1u, nullptr);
+  }
+  launch_prefill_finish(dev_prompt, max_prompt, B, ctx->st, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos, dq.rd_slot, s);
+  ctx->prefilled = true;
+  return hip_status(ctx, "sprinter_prefill");
+}
+
+int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_step: NULL context");
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  rc = check_room(ctx, 1);
+  if (rc) return rc;
+  enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
+  ctx->steps_done += 1;
+  return hip_status(ctx, "sprinter_step");
+}
+
+int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uint8_t* dev_out_accept,
+                      float* dev_out_score, int32_t* dev_out_draft_tok) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_generate: NULL context");
+  if (n_tokens < 0) return fail(ctx, SPRINTER_E_RANGE, "n_tokens %d < 0", n_tokens);
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  rc = check_room(ctx, n_tokens);
+  if (rc) return rc;
+  launch_reset_gen_idx(ctx->st.counters, ctx->stream);
+  for (int g = 0; g < n_tokens; ++g)
+    enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+  ctx->steps_done += n_tokens;
+  return hip_status(ctx, "sprinter_generate");
+}
+
+int sprinter_set_tau(sprinter_ctx* ctx, float tau) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_set_tau: NULL context");
+  if (!(tau == tau)) return fail(ctx, SPRINTER_E_CONFIG, "tau is NaN");
+  ctx->cfg.tau = tau;
+  launch_set_f32(ctx->tau_dev, tau, ctx->stream);
+  return hip_status(ctx, "sprinter_set_tau");
+}
+
+int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* host_target_calls) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_get_stats: NULL context");
+  if (!host_out) return fail(ctx, SPRINTER_E_NULL, "sprinter_get_stats: NULL argument");
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
+  long long c[4] = {0, 0, 0, 0};
+  if (ctx->prefilled) {
+    if (hipMemcpy(c, ctx->st.counters, sizeof c, hipMemcpyDeviceToHost) != hipSuccess)
+      return fail(ctx, SPRINTER_E_HIP, "copy of counters failed");
+    if (host_target_calls &&
+        hipMemcpy(host_target_calls, ctx->st.n_target_calls, (size_t)ctx->B * 8, hipMemcpyDeviceToHost) != hipSuccess)
+      return fail(ctx, SPRINTER_E_HIP, "copy of per-row target calls failed");
+  }
+  host_out->steps = c[0];
+  host_out->steps_with_target = c[1];
+  host_out->sum_rejected = c[2];
+  host_out->batch = ctx->B;
+  host_out->reserved = 0;
+  return SPRINTER_OK;
+}
+
+void sprinter_destroy(sprinter_ctx* ctx) { delete ctx; }
+
+const char* sprinter_last_error(const sprinter_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+}  // extern "C"

@@ -1,0 +1,1086 @@
+// HIP kernels of the batched SPRINTER decode step for gfx950 (wave64, MFMA).
+//
+// One decode step (Alg. 2 of the paper, run for B rows in lock step):
+//   draft forward -> LM head + Gumbel-max sample -> verifier + threshold ->
+//   compaction of rejected rows -> target forward on those rows -> sample ->
+//   scatter back.  Every kernel reads the number of active rows from device
+//   memory, so the host never learns how many rows were rejected.
+#include "internal.h"
+#include <math.h>
+
+namespace sprinter {
+
+typedef unsigned short bf16_t;   // raw bfloat16 bits
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef unsigned long long u64;
+
+// ------------------------------------------------------------------ scalars
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest even
+  unsigned u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);   // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
+
+// Activation layout: float32 mode = row-major [m][K]; bf16 mode = MFMA operand tiles.
+template <typename T> __device__ __forceinline__ size_t act_idx(int m, int k, int K);
+template <> __device__ __forceinline__ size_t act_idx<float>(int m, int k, int K) { return (size_t)m * K + k; }
+template <> __device__ __forceinline__ size_t act_idx<bf16_t>(int m, int k, int K) {
+  int Kt = (K + 31) >> 5;
+  return ((size_t)(m >> 4) * Kt + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
+}
+
+// Store one activation.  In bf16 mode a value is kept as the sum of two bf16 numbers
+// (hi = RNE(v), lo = RNE(v - hi)) in two planes of operand tiles, so that the GEMM input
+// carries ~16 mantissa bits while the weights stay plain bf16; each plane is one MFMA operand.
+template <typename T> __device__ __forceinline__ void act_store(T* base, size_t plane, int m, int k, int K, float v);
+template <> __device__ __forceinline__ void act_store<float>(float* base, size_t, int m, int k, int K, float v) {
+  base[act_idx<float>(m, k, K)] = v;
+}
+template <> __device__ __forceinline__ void act_store<bf16_t>(bf16_t* base, size_t plane, int m, int k, int K, float v) {
+  size_t i = act_idx<bf16_t>(m, k, K);
+  bf16_t hi = f2bf(v);
+  base[i] = hi;
+  base[plane + i] = f2bf(v - bf2f(hi));
+}
+
+__device__ __forceinline__ float gelu_tanh(float x) {
+  const float c = 0.7978845608028654f;   // sqrt(2/pi)
+  return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
+}
+__device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
+
+// ------------------------------------------------------------- reductions
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int o) {
+  unsigned lo = __shfl_xor((unsigned)v, o), hi = __shfl_xor((unsigned)(v >> 32), o);
+  return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 umax64(u64 a, u64 b) { return a > b ? a : b; }
+
+// block-wide reductions for 256-thread blocks; result broadcast to all threads
+__device__ __forceinline__ float block_sum256(float v, float* s4) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return ((s4[0] + s4[1]) + s4[2]) + s4[3];
+}
+__device__ __forceinline__ float block_max256(float v, float* s4) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) s4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
+}
+
+// ------------------------------------------------- Philox4x32-10 + Gumbel
+// Counter-based generator of Salmon et al. (SC'11).  key = seed, counter =
+// (vocab index / 4, position, row, stream); word (vocab index % 4) of the block.
+__device__ __forceinline__ unsigned philox_word(unsigned k0, unsigned k1, unsigned stream, unsigned b,
+                                                unsigned t, unsigned v) {
+  unsigned c0 = v >> 2, c1 = t, c2 = b, c3 = stream;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  unsigned sel = v & 3u;
+  return sel == 0 ? c0 : sel == 1 ? c1 : sel == 2 ? c2 : c3;
+}
+// u = ((word >> 9) + 0.5) * 2^-23 is exact in float32 and inside (0,1).
+__device__ __forceinline__ float gumbel_from_word(unsigned w) {
+  float u = ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;
+  return -logf(-logf(u));
+}
+// (value, index) -> one integer whose order is "larger value first, then smaller index"
+__device__ __forceinline__ u64 pack_key(float y, unsigned n) {
+  y = y + 0.0f;   // -0 -> +0
+  unsigned u = __float_as_uint(y);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((u64)u << 32) | (u64)(0xFFFFFFFFu - n);
+}
+__device__ __forceinline__ int key_index(u64 k) { return (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull)); }
+
+__device__ __forceinline__ u64 sample_key(float logit, const SamplerArgs& sa, int b, int t, int n) {
+  float y = logit;
+  if (sa.inv_temperature > 0.0f)
+    y = logit * sa.inv_temperature + gumbel_from_word(philox_word(sa.seed_lo, sa.seed_hi, sa.stream, b, t, n));
+  return pack_key(y, (unsigned)n);
+}
+
+// ================================================================ packing
+// [N, K] row-major bf16 -> operand tiles (zero padded to 16 rows x 32 k).
+__global__ __launch_bounds__(256) void k_pack_bf16(const bf16_t* __restrict__ w, uint4* __restrict__ out, int N, int K,
+                                                   int Kt, size_t total) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  int lane = (int)(i & 63);
+  size_t tile = i >> 6;
+  int kt = (int)(tile % Kt);
+  int nt = (int)(tile / Kt);
+  int n = nt * 16 + (lane & 15);
+  int k0 = kt * 32 + (lane >> 4) * 8;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (n < N) {
+    if (k0 + 8 <= K) {
+      v = *reinterpret_cast<const uint4*>(w + (size_t)n * K + k0);   // K % 8 == 0 keeps this aligned
+    } else if (k0 < K) {
+      bf16_t t[8];
+      for (int e = 0; e < 8; ++e) t[e] = (k0 + e < K) ? w[(size_t)n * K + k0 + e] : (bf16_t)0;
+      v = *reinterpret_cast<uint4*>(t);
+    }
+  }
+  out[i] = v;
+}
+void launch_pack_bf16(const void* w, void* out, int N, int K, hipStream_t s) {
+  int Kt = (K + 31) / 32, Nt = (N + 15) / 16;
+  size_t total = (size_t)Nt * Kt * 64;
+  hipLaunchKernelGGL(k_pack_bf16, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)w,
+                     (uint4*)out, N, K, Kt, total);
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * 256;
+  for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  size_t n16 = bytes / 16;
+  if (!n16) return;
+  unsigned grid = (unsigned)((n16 + 255) / 256);
+  if (grid > 4096) grid = 4096;
+  hipLaunchKernelGGL(k_fill_zero, dim3(grid), dim3(256), 0, s, (uint4*)p, n16);
+}
+
+// ================================================================== embed
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed(const T* __restrict__ E, const T* __restrict__ P, RowDesc rd,
+                                               float* __restrict__ h, float* __restrict__ rope, int d, int dh,
+                                               float theta, int use_rope, int V, int max_pos) {
+  int r = blockIdx.x;
+  if (r >= *rd.n_rows) return;
+  int tok = rd.tok[r], pos = rd.pos[r];
+  tok = min(max(tok, 0), V - 1);            // an out-of-vocabulary id must not become a wild read
+  if (P) pos = min(max(pos, 0), max_pos - 1);
+  const T* e = E + (size_t)tok * d;
+  const T* p = P ? P + (size_t)pos * d : nullptr;
+  for (int k = threadIdx.x; k < d; k += 256) {
+    float v = to_f<T>(e[k]);
+    if (p) v += to_f<T>(p[k]);
+    h[(size_t)r * d + k] = v;
+  }
+  if (use_rope && (int)threadIdx.x < dh / 2) {
+    // angle = pos * theta^(-2i/dh), evaluated in double so that large positions stay accurate
+    double inv = pow((double)theta, -2.0 * (double)threadIdx.x / (double)dh);
+    double ang = (double)pos * inv;
+    rope[(size_t)r * dh + 2 * threadIdx.x] = (float)cos(ang);
+    rope[(size_t)r * dh + 2 * threadIdx.x + 1] = (float)sin(ang);
+  }
+}
+void launch_embed(int dtype, const ModelDims& md, const void* tok_emb, const void* pos_emb, const RowDesc& rd,
+                  float* h, float* rope, int max_rows, hipStream_t s) {
+  int use_rope = md.arch == 1;
+  if (dtype == 0)
+    hipLaunchKernelGGL(k_embed<float>, dim3(max_rows), dim3(256), 0, s, (const float*)tok_emb,
+                       (const float*)pos_emb, rd, h, rope, md.d, md.dh, md.theta, use_rope, md.V, md.max_pos);
+  else
+    hipLaunchKernelGGL(k_embed<bf16_t>, dim3(max_rows), dim3(256), 0, s, (const bf16_t*)tok_emb,
+                       (const bf16_t*)pos_emb, rd, h, rope, md.d, md.dh, md.theta, use_rope, md.V, md.max_pos);
+}
+
+// =================================================================== norm
+// LayerNorm (arch 0) / RMSNorm (arch 1) of one row per workgroup; two-pass statistics.
+template <typename AT, int ARCH>
+__global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const float* __restrict__ g,
+                                              const float* __restrict__ b, float eps, int d,
+                                              const int* __restrict__ n_rows, AT* __restrict__ act_out,
+                                              size_t plane, float* __restrict__ f32_out) {
+  __shared__ float s4[4];
+  int r = blockIdx.x;
+  if (r >= *n_rows) return;
+  const float* x = h + (size_t)r * d;
+  float v[32];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    int k = threadIdx.x + i * 256;
+    v[i] = k < d ? x[k] : 0.f;
+    sum += v[i];
+  }
+  float mean = 0.f;
+  if (ARCH == 0) mean = block_sum256(sum, s4) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    int k = threadIdx.x + i * 256;
+    float c = k < d ? v[i] - mean : 0.f;
+    sq += c * c;
+  }
+  float var = block_sum256(sq, s4) / (float)d;
+  float rstd = 1.0f / sqrtf(var + eps);
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    int k = threadIdx.x + i * 256;
+    if (k < d) {
+      float o = (v[i] - mean) * rstd * g[k];
+      if (ARCH == 0) o += b[k];
+      act_store<AT>(act_out, plane, r, k, d, o);
+      if (f32_out) f32_out[(size_t)r * d + k] = o;
+    }
+  }
+}
+void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
+                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s) {
+#define NORM_CASE(AT, ARCH) \
+  hipLaunchKernelGGL((k_norm<AT, ARCH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (AT*)act_out, plane, f32_out)
+  if (dtype == 0) { if (arch == 0) NORM_CASE(float, 0); else NORM_CASE(float, 1); }
+  else            { if (arch == 0) NORM_CASE(bf16_t, 0); else NORM_CASE(bf16_t, 1); }
+#undef NORM_CASE
+}
+
+// =================================================================== GEMM
+struct GemmArgs {
+  const void* W; const void* W2; const void* X; const int* n_rows;
+  int N, K, Kt, n_tiles;
+  const float* bias; float* out_f32; int ldo; void* out_act; int out_K;
+  size_t x_plane;     // elements between the hi and lo planes of X (bf16 mode)
+  size_t out_plane;   // same for out_act
+};
+
+template <int EPI, typename AT>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int m, int n, float v, float v2) {
+  if (m >= n_rows || n >= a.N) return;
+  float bias = a.bias ? a.bias[n] : 0.f;
+  if (EPI == EPI_F32) a.out_f32[(size_t)m * a.ldo + n] = v + bias;
+  else if (EPI == EPI_RESID) a.out_f32[(size_t)m * a.ldo + n] += v + bias;
+  else if (EPI == EPI_GELU) act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, gelu_tanh(v + bias));
+  else act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, silu(v) * v2);
+}
+
+__device__ __forceinline__ f32x4 mfma_bf16(uint4 x, uint4 w, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8*>(&x), *reinterpret_cast<bf16x8*>(&w), c, 0,
+                                                 0, 0);
+}
+
+// bf16 GEMM on MFMA.  512 threads = 8 waves = (8/KW) column groups x KW-way split of K.
+// Each wave owns NTW column tiles (16 columns each) and MT row tiles (16 rows each):
+// D[m][n] += X[m][k] W[n][k]; lane l of an accumulator holds n = l%16, m = (l/16)*4 + v.
+template <int MT, int NTW, int KW, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NW = 8 / KW;
+  constexpr int NI = NTW * MT * 4;
+  constexpr int NI2 = NI * (DUAL ? 2 : 1);
+  // partial accumulators of the waves with kw > 0, handed to the kw == 0 wave of their column group
+  __shared__ float red[(KW > 1) ? (KW - 1) * NW * NI2 * 64 : 1];
+  const int n_rows = *a.n_rows;
+  if (n_rows <= 0) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int kw = w % KW, ng = w / KW;
+  const int nt0 = (blockIdx.x * NW + ng) * NTW;
+  const uint4* __restrict__ Wp = (const uint4*)a.W;
+  const uint4* __restrict__ W2p = (const uint4*)a.W2;
+  const uint4* __restrict__ Xp = (const uint4*)a.X;
+  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
+  const int Kt = a.Kt;
+  for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
+    const int mt_act = min(MT, (n_rows - m0 + 15) >> 4);
+    const int mtile0 = m0 >> 4;
+    f32x4 acc[NTW][MT], acc2[DUAL ? NTW : 1][MT];
+#pragma unroll
+    for (int j = 0; j < NTW; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        if (DUAL) acc2[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+    constexpr int U = 4;
+    for (int kt = kw; kt < Kt; kt += KW * U) {
+      uint4 wv[U][NTW], wv2[U][DUAL ? NTW : 1];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int kc = min(kt + u * KW, Kt - 1);                    // clamped: always a valid tile
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) {
+          int nt = min(nt0 + j, a.n_tiles - 1);
+          wv[u][j] = Wp[((size_t)nt * Kt + kc) * 64 + lane];
+          if (DUAL) wv2[u][j] = W2p[((size_t)nt * Kt + kc) * 64 + lane];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int kc = kt + u * KW;
+        if (kc < Kt) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            if (mt < mt_act) {
+              uint4 xv = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+              uint4 xl = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+#pragma unroll
+              for (int j = 0; j < NTW; ++j) {
+                acc[j][mt] = mfma_bf16(xv, wv[u][j], acc[j][mt]);
+                acc[j][mt] = mfma_bf16(xl, wv[u][j], acc[j][mt]);
+                if (DUAL) {
+                  acc2[j][mt] = mfma_bf16(xv, wv2[u][j], acc2[j][mt]);
+                  acc2[j][mt] = mfma_bf16(xl, wv2[u][j], acc2[j][mt]);
+                }
+              }
+            }
+          }
+        }
+      }
+    }
+    if (KW > 1) {
+      // sum the KW partial accumulators in a fixed order (kw = 0, 1, ..)
+      if (kw > 0) {
+        float* dst = red + (size_t)(ng * (KW - 1) + kw - 1) * NI2 * 64;
+#pragma unroll
+        for (int j = 0; j < NTW; ++j)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              int it = (j * MT + mt) * 4 + v;
+              dst[it * 64 + lane] = acc[j][mt][v];
+              if (DUAL) dst[(NI + it) * 64 + lane] = acc2[j][mt][v];
+            }
+      }
+      __syncthreads();
+      if (kw == 0) {
+#pragma unroll
+        for (int q = 1; q < KW; ++q) {
+          const float* src = red + (size_t)(ng * (KW - 1) + q - 1) * NI2 * 64;
+#pragma unroll
+          for (int j = 0; j < NTW; ++j)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                int it = (j * MT + mt) * 4 + v;
+                acc[j][mt][v] += src[it * 64 + lane];
+                if (DUAL) acc2[j][mt][v] += src[(NI + it) * 64 + lane];
+              }
+        }
+      }
+    }
+    if (kw == 0) {
+#pragma unroll
+      for (int j = 0; j < NTW; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          if (mt < mt_act && nt0 + j < a.n_tiles) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              gemm_epilogue<EPI, bf16_t>(a, n_rows, m0 + mt * 16 + (lane >> 4) * 4 + v, (nt0 + j) * 16 + (lane & 15),
+                                         acc[j][mt][v], DUAL ? acc2[j][mt][v] : 0.f);
+          }
+    }
+    if (KW > 1) __syncthreads();
+  }
+}
+
+// float32 GEMM on the vector ALU: one wave per output column, 8 rows at a time.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  const int n_rows = *a.n_rows;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + w;
+  if (n >= a.N || n_rows <= 0) return;
+  const int K = a.K;
+  const float* __restrict__ wr = (const float*)a.W + (size_t)n * K;
+  const float* __restrict__ wr2 = DUAL ? (const float*)a.W2 + (size_t)n * K : nullptr;
+  const float* __restrict__ X = (const float*)a.X;
+  for (int m0 = 0; m0 < n_rows; m0 += 8) {
+    float acc[8], acc2[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = acc2[i] = 0.f;
+    for (int k = lane * 4; k < K; k += 256) {
+      float4 wv = *reinterpret_cast<const float4*>(wr + k);
+      float4 wv2 = DUAL ? *reinterpret_cast<const float4*>(wr2 + k) : make_float4(0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (m0 + i < n_rows) {
+          float4 xv = *reinterpret_cast<const float4*>(X + (size_t)(m0 + i) * K + k);
+          acc[i] += xv.x * wv.x + xv.y * wv.y + xv.z * wv.z + xv.w * wv.w;
+          if (DUAL) acc2[i] += xv.x * wv2.x + xv.y * wv2.y + xv.z * wv2.z + xv.w * wv2.w;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float s1 = wave_sum(acc[i]);
+      float s2 = DUAL ? wave_sum(acc2[i]) : 0.f;
+      if (lane == i) gemm_epilogue<EPI, float>(a, n_rows, m0 + i, n, s1, s2);
+    }
+  }
+}
+
+template <int EPI>
+static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
+  // (row tiles, column tiles per wave, K split) chosen from the launch-time row maximum
+  if (max_rows <= 16) {
+    int grid = a.n_tiles;                        // 1 column tile per workgroup, K split over 8 waves
+    hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(grid), dim3(512), 0, s, a);
+  } else if (max_rows <= 32) {
+    hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  } else if (max_rows <= 64) {
+    int grid = (a.n_tiles + 1) / 2;              // 2 column groups x 4-way K split
+    hipLaunchKernelGGL((k_gemm_bf16<4, 1, 4, EPI>), dim3(grid), dim3(512), 0, s, a);
+  } else {
+    int grid = (a.n_tiles + 3) / 4;              // 4 column groups x 2-way K split
+    hipLaunchKernelGGL((k_gemm_bf16<8, 1, 2, EPI>), dim3(grid), dim3(512), 0, s, a);
+  }
+}
+
+void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane, const int* n_rows,
+                 int N, int K, const float* bias, float* out_f32, int ldo, void* out_act, int out_K, size_t out_plane,
+                 int max_rows, hipStream_t s) {
+  GemmArgs a;
+  a.x_plane = x_plane; a.out_plane = out_plane;
+  a.W = W; a.W2 = W2; a.X = X; a.n_rows = n_rows; a.N = N; a.K = K;
+  a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16;
+  a.bias = bias; a.out_f32 = out_f32; a.ldo = ldo; a.out_act = out_act; a.out_K = out_K;
+  if (dtype == 0) {
+    dim3 grid((N + 3) / 4), block(256);
+    switch (epi) {
+      case EPI_F32: hipLaunchKernelGGL(k_gemm_f32<EPI_F32>, grid, block, 0, s, a); break;
+      case EPI_RESID: hipLaunchKernelGGL(k_gemm_f32<EPI_RESID>, grid, block, 0, s, a); break;
+      case EPI_GELU: hipLaunchKernelGGL(k_gemm_f32<EPI_GELU>, grid, block, 0, s, a); break;
+      default: hipLaunchKernelGGL(k_gemm_f32<EPI_SWIGLU>, grid, block, 0, s, a); break;
+    }
+  } else {
+    switch (epi) {
+      case EPI_F32: launch_gemm_bf16<EPI_F32>(a, max_rows, s); break;
+      case EPI_RESID: launch_gemm_bf16<EPI_RESID>(a, max_rows, s); break;
+      case EPI_GELU: launch_gemm_bf16<EPI_GELU>(a, max_rows, s); break;
+      default: launch_gemm_bf16<EPI_SWIGLU>(a, max_rows, s); break;
+    }
+  }
+}
+
+// ============================================================== attention
+// One workgroup per (row, KV head): rotary on q and the new k, append k/v to the
+// cache, scores against all cached keys, softmax, weighted sum of values.
+// The G query heads that share the KV head are processed together.
+struct AttnArgs {
+  const float* y; const float* rope; RowDesc rd;
+  void* kcache; void* vcache; size_t layer_off;
+  int H, KVH, dqkv, max_seq, use_rope; float scale;
+  void* ao; int ao_K; size_t ao_plane;
+};
+
+template <typename T, int DH, int G>
+__global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
+  extern __shared__ float smem[];
+  __shared__ float s4[4];
+  __shared__ float s_inv[G];
+  float* qs = smem;                    // [G][DH]
+  float* knew = qs + G * DH;           // [DH]
+  float* vnew = knew + DH;             // [DH]
+  float* red = vnew + DH;              // [4][G][DH]
+  float* sc = red + 4 * G * DH;        // [G][max_seq]
+  const int r = blockIdx.y;
+  if (r >= *a.rd.n_rows) return;
+  const int kvh = blockIdx.x, tid = threadIdx.x;
+  const int b = a.rd.b[r], slot = a.rd.slot[r], nk = slot + 1, S = a.max_seq;
+  const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
+  const float* __restrict__ cs = a.rope + (size_t)r * DH;
+  constexpr int HALF = DH / 2;
+  for (int idx = tid; idx < G * DH; idx += 256) {
+    int g = idx / DH, i = idx % DH;
+    const float* qh = y + (size_t)(kvh * G + g) * DH;
+    float val = qh[i];
+    if (a.use_rope) {
+      int j = i < HALF ? i : i - HALF;
+      float c = cs[2 * j], sn = cs[2 * j + 1];
+      val = i < HALF ? qh[i] * c - qh[i + HALF] * sn : qh[i] * c + qh[i - HALF] * sn;
+    }
+    qs[idx] = val * a.scale;
+  }
+  T* __restrict__ Kc = (T*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+  T* __restrict__ Vc = (T*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+  for (int i = tid; i < DH; i += 256) {
+    const float* kh = y + (size_t)(a.H + kvh) * DH;
+    const float* vh = y + (size_t)(a.H + a.KVH + kvh) * DH;
+    float kv = kh[i];
+    if (a.use_rope) {
+      int j = i < HALF ? i : i - HALF;
+      float c = cs[2 * j], sn = cs[2 * j + 1];
+      kv = i < HALF ? kh[i] * c - kh[i + HALF] * sn : kh[i] * c + kh[i - HALF] * sn;
+    }
+    T kt = from_f<T>(kv), vt = from_f<T>(vh[i]);
+    Kc[(size_t)slot * DH + i] = kt;
+    Vc[(size_t)slot * DH + i] = vt;
+    knew[i] = to_f<T>(kt);             // the entry as later steps will read it back
+    vnew[i] = to_f<T>(vt);
+  }
+  __syncthreads();
+
+  constexpr int EPL = 16 / sizeof(T);  // elements per 16-byte lane load
+  constexpr int LPK = DH / EPL;        // lanes per key
+  constexpr int KPW = 64 / LPK;        // keys per wave per iteration
+  const int lane = tid & 63, w = tid >> 6;
+  const int chunk = lane % LPK, kin = lane / LPK;
+  float qreg[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) qreg[g][e] = qs[g * DH + chunk * EPL + e];
+
+  // pass 1: scores
+  for (int key0 = w * KPW; key0 < nk; key0 += 4 * KPW) {
+    int key = key0 + kin;
+    float kv[EPL];
+    if (key < slot) {
+      uint4 raw = *reinterpret_cast<const uint4*>(Kc + (size_t)key * DH + chunk * EPL);
+      const T* t = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) kv[e] = to_f<T>(t[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) kv[e] = (key == slot) ? knew[chunk * EPL + e] : 0.f;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float p = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) p += qreg[g][e] * kv[e];
+#pragma unroll
+      for (int o = 1; o < LPK; o <<= 1) p += __shfl_xor(p, o);
+      if (chunk == 0 && key < nk) sc[g * S + key] = p;
+    }
+  }
+  __syncthreads();
+  // softmax over the nk keys of every head
+  for (int g = 0; g < G; ++g) {
+    float mx = -INFINITY;
+    for (int k = tid; k < nk; k += 256) mx = fmaxf(mx, sc[g * S + k]);
+    mx = block_max256(mx, s4);
+    float sum = 0.f;
+    for (int k = tid; k < nk; k += 256) {
+      float e = expf(sc[g * S + k] - mx);
+      sc[g * S + k] = e;
+      sum += e;
+    }
+    sum = block_sum256(sum, s4);
+    if (tid == 0) s_inv[g] = 1.0f / sum;
+  }
+  __syncthreads();
+  // pass 2: weighted values
+  float acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  for (int key0 = w * KPW; key0 < nk; key0 += 4 * KPW) {
+    int key = key0 + kin;
+    float vv[EPL];
+    if (key < slot) {
+      uint4 raw = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * EPL);
+      const T* t = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) vv[e] = to_f<T>(t[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) vv[e] = (key == slot) ? vnew[chunk * EPL + e] : 0.f;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float p = key < nk ? sc[g * S + key] : 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] += p * vv[e];
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      float v = acc[g][e];
+#pragma unroll
+      for (int o = LPK; o < 64; o <<= 1) v += __shfl_xor(v, o);
+      if (kin == 0) red[(w * G + g) * DH + chunk * EPL + e] = v;
+    }
+  __syncthreads();
+  T* __restrict__ ao = (T*)a.ao;
+  for (int idx = tid; idx < G * DH; idx += 256) {
+    int g = idx / DH;
+    float o = ((red[idx] + red[G * DH + idx]) + red[2 * G * DH + idx]) + red[3 * G * DH + idx];
+    o *= s_inv[g];
+    act_store<T>(ao, a.ao_plane, r, kvh * G * DH + idx, a.ao_K, o);
+  }
+}
+
+static size_t attn_smem_bytes(int DH, int G, int max_seq) {
+  return (size_t)(G * DH + 2 * DH + 4 * G * DH + G * max_seq) * sizeof(float);
+}
+
+template <typename T, int DH>
+static void launch_attn_g(const AttnArgs& a, int G, int max_rows, hipStream_t s) {
+  dim3 grid(a.KVH, max_rows), block(256);
+  size_t sm = attn_smem_bytes(DH, G, a.max_seq);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((k_attn<T, DH, 1>), grid, block, sm, s, a); break;
+    case 2: hipLaunchKernelGGL((k_attn<T, DH, 2>), grid, block, sm, s, a); break;
+    case 4: hipLaunchKernelGGL((k_attn<T, DH, 4>), grid, block, sm, s, a); break;
+    default: hipLaunchKernelGGL((k_attn<T, DH, 8>), grid, block, sm, s, a); break;
+  }
+}
+
+void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
+                      void* kcache, void* vcache, size_t layer_off, int max_batch, int max_seq, void* ao,
+                      size_t ao_plane, int max_rows, hipStream_t s) {
+  (void)max_batch;
+  AttnArgs a;
+  a.y = y; a.rope = rope; a.rd = rd; a.kcache = kcache; a.vcache = vcache; a.layer_off = layer_off;
+  a.H = md.H; a.KVH = md.KVH; a.dqkv = md.dqkv; a.max_seq = max_seq; a.use_rope = md.arch == 1;
+  a.scale = 1.0f / sqrtf((float)md.dh);
+  a.ao = ao; a.ao_K = md.H * md.dh; a.ao_plane = ao_plane;
+  int G = md.H / md.KVH;
+  if (dtype == 0) {
+    if (md.dh == 64) launch_attn_g<float, 64>(a, G, max_rows, s); else launch_attn_g<float, 128>(a, G, max_rows, s);
+  } else {
+    if (md.dh == 64) launch_attn_g<bf16_t, 64>(a, G, max_rows, s); else launch_attn_g<bf16_t, 128>(a, G, max_rows, s);
+  }
+}
+
+// ======================================================= LM head + sample
+struct LmArgs {
+  const void* W; const void* X; RowDesc rd; int V, K, Kt, n_tiles;
+  SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_plane;
+};
+
+// bf16: each workgroup owns a contiguous range of column tiles; its 8 waves take
+// tiles round-robin, keep a running (value, index) maximum per row, and the
+// workgroup writes one partial per row.
+template <int MT>
+__global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
+  __shared__ u64 sbest[8][MT * 16];
+  const int n_rows = *a.rd.n_rows;
+  if (n_rows <= 0) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int tpw = (a.n_tiles + gridDim.x - 1) / gridDim.x;
+  const int t0 = blockIdx.x * tpw, t1 = min(t0 + tpw, a.n_tiles);
+  const uint4* __restrict__ Wp = (const uint4*)a.W;
+  const uint4* __restrict__ Xp = (const uint4*)a.X;
+  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
+  const int Kt = a.Kt;
+  for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
+    const int mt_act = min(MT, (n_rows - m0 + 15) >> 4);
+    const int mtile0 = m0 >> 4;
+    u64 best[MT][4];
+    int rb[MT][4], rt[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        best[mt][v] = 0;
+        int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
+        rb[mt][v] = m < n_rows ? a.rd.b[m] : 0;
+        rt[mt][v] = m < n_rows ? a.rd.pos[m] + 1 : 0;     // the position being generated
+      }
+    for (int nt = t0 + w; nt < t1; nt += 8) {
+      f32x4 acc[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      constexpr int U = 4;
+      for (int kt = 0; kt < Kt; kt += U) {
+        uint4 wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) wv[u] = Wp[((size_t)nt * Kt + min(kt + u, Kt - 1)) * 64 + lane];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (kt + u < Kt) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              if (mt < mt_act) {
+                uint4 xv = Xp[((size_t)(mtile0 + mt) * Kt + kt + u) * 64 + lane];
+                uint4 xl = Xl[((size_t)(mtile0 + mt) * Kt + kt + u) * 64 + lane];
+                acc[mt] = mfma_bf16(xv, wv[u], acc[mt]);
+                acc[mt] = mfma_bf16(xl, wv[u], acc[mt]);
+              }
+          }
+      }
+      const int n = nt * 16 + (lane & 15);
+      if (n < a.V) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          if (mt < mt_act) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
+              if (m < n_rows) {
+                float logit = acc[mt][v];
+                if (a.logits_out) a.logits_out[(size_t)m * a.V + n] = logit;
+                best[mt][v] = umax64(best[mt][v], sample_key(logit, a.sa, rb[mt][v], rt[mt][v], n));
+              }
+            }
+          }
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        u64 k = best[mt][v];
+#pragma unroll
+        for (int o = 1; o < 16; o <<= 1) k = umax64(k, shfl_xor_u64(k, o));
+        if ((lane & 15) == 0) sbest[w][mt * 16 + (lane >> 4) * 4 + v] = k;
+      }
+    __syncthreads();
+    for (int i = threadIdx.x; i < MT * 16; i += 512) {
+      u64 k = sbest[0][i];
+#pragma unroll
+      for (int q = 1; q < 8; ++q) k = umax64(k, sbest[q][i]);
+      if (m0 + i < a.Mpad) a.part[(size_t)blockIdx.x * a.Mpad + m0 + i] = k;
+    }
+    __syncthreads();
+  }
+}
+
+// float32: one wave per vocabulary column, 8 rows at a time.
+__global__ __launch_bounds__(256) void k_lmhead_f32(LmArgs a) {
+  __shared__ u64 sbest[4][8];
+  const int n_rows = *a.rd.n_rows;
+  if (n_rows <= 0) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int cpw = (a.V + gridDim.x - 1) / gridDim.x;
+  const int c0 = blockIdx.x * cpw, c1 = min(c0 + cpw, a.V);
+  const int K = a.K;
+  const float* __restrict__ W = (const float*)a.W;
+  const float* __restrict__ X = (const float*)a.X;
+  for (int m0 = 0; m0 < n_rows; m0 += 8) {
+    u64 best = 0;
+    const int my_m = m0 + lane;
+    const int my_b = (lane < 8 && my_m < n_rows) ? a.rd.b[my_m] : 0;
+    const int my_t = (lane < 8 && my_m < n_rows) ? a.rd.pos[my_m] + 1 : 0;
+    for (int n = c0 + w; n < c1; n += 4) {
+      const float* wr = W + (size_t)n * K;
+      float acc[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+      for (int k = lane * 4; k < K; k += 256) {
+        float4 wv = *reinterpret_cast<const float4*>(wr + k);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (m0 + i < n_rows) {
+            float4 xv = *reinterpret_cast<const float4*>(X + (size_t)(m0 + i) * K + k);
+            acc[i] += xv.x * wv.x + xv.y * wv.y + xv.z * wv.z + xv.w * wv.w;
+          }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float sacc = wave_sum(acc[i]);
+        if (lane == i && m0 + i < n_rows) {
+          if (a.logits_out) a.logits_out[(size_t)(m0 + i) * a.V + n] = sacc;
+          best = umax64(best, sample_key(sacc, a.sa, my_b, my_t, n));
+        }
+      }
+    }
+    if (lane < 8) sbest[w][lane] = best;
+    __syncthreads();
+    if (threadIdx.x < 8 && m0 + (int)threadIdx.x < a.Mpad) {
+      u64 k = umax64(umax64(sbest[0][threadIdx.x], sbest[1][threadIdx.x]),
+                     umax64(sbest[2][threadIdx.x], sbest[3][threadIdx.x]));
+      a.part[(size_t)blockIdx.x * a.Mpad + m0 + threadIdx.x] = k;
+    }
+    __syncthreads();
+  }
+}
+
+int lmhead_num_wg(int dtype, int V) {
+  int n = (dtype == 0) ? (V + 7) / 8 : ((V + 15) / 16 + 7) / 8;
+  return n < 512 ? n : 512;
+}
+
+void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, const RowDesc& rd, int V, int K,
+                   const SamplerArgs& sa, unsigned long long* part, int n_wg, int Mpad, float* logits_out, int max_rows,
+                   hipStream_t s) {
+  LmArgs a;
+  a.x_plane = x_plane;
+  a.W = W; a.X = X; a.rd = rd; a.V = V; a.K = K; a.Kt = (K + 31) / 32; a.n_tiles = (V + 15) / 16;
+  a.sa = sa; a.part = part; a.Mpad = Mpad; a.logits_out = logits_out;
+  if (dtype == 0) {
+    hipLaunchKernelGGL(k_lmhead_f32, dim3(n_wg), dim3(256), 0, s, a);
+  } else if (max_rows <= 16) {
+    hipLaunchKernelGGL(k_lmhead_bf16<1>, dim3(n_wg), dim3(512), 0, s, a);
+  } else if (max_rows <= 32) {
+    hipLaunchKernelGGL(k_lmhead_bf16<2>, dim3(n_wg), dim3(512), 0, s, a);
+  } else if (max_rows <= 64) {
+    hipLaunchKernelGGL(k_lmhead_bf16<4>, dim3(n_wg), dim3(512), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(k_lmhead_bf16<8>, dim3(n_wg), dim3(512), 0, s, a);
+  }
+}
+
+// =============================================================== verifier
+// Hidden layer of the verifier MLP, spread over workgroups of 8 waves (one hidden
+// unit per wave); each workgroup leaves its share of the output logit per row.
+// d_hidden == 0: the logit is w2 . hf (a single chunk).
+__global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__ hf, int d, int d_hidden,
+                                                       const float* __restrict__ w1, const float* __restrict__ b1,
+                                                       const float* __restrict__ w2, const int* __restrict__ n_rows_p,
+                                                       float* __restrict__ part, int max_rows) {
+  extern __shared__ float contrib[];   // [8][max_rows]
+  const int n_rows = *n_rows_p;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (d_hidden == 0) {
+    for (int m = w; m < n_rows; m += 8) {
+      float acc = 0.f;
+      for (int k = lane; k < d; k += 64) acc += w2[k] * hf[(size_t)m * d + k];
+      acc = wave_sum(acc);
+      if (lane == 0) part[m] = acc;
+    }
+    return;
+  }
+  const int j = blockIdx.x * 8 + w;
+  for (int m = 0; m < n_rows; ++m) {
+    float c = 0.f;
+    if (j < d_hidden) {
+      float acc = 0.f;
+      for (int k = lane; k < d; k += 64) acc += w1[(size_t)j * d + k] * hf[(size_t)m * d + k];
+      acc = wave_sum(acc) + b1[j];
+      c = fmaxf(acc, 0.f) * w2[j];
+    }
+    if (lane == 0) contrib[w * max_rows + m] = c;
+  }
+  __syncthreads();
+  for (int m = threadIdx.x; m < n_rows; m += 512) {
+    float sacc = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) sacc += contrib[q * max_rows + m];
+    part[(size_t)blockIdx.x * max_rows + m] = sacc;
+  }
+}
+int verifier_num_chunks(int d_hidden) { return d_hidden > 0 ? (d_hidden + 7) / 8 : 1; }
+void launch_verifier_part(const float* hf, int d, int d_hidden, const float* w1, const float* b1, const float* w2,
+                          const int* n_rows, float* part, int max_rows, hipStream_t s) {
+  int chunks = verifier_num_chunks(d_hidden);
+  hipLaunchKernelGGL(k_verifier_part, dim3(chunks), dim3(512), (size_t)8 * max_rows * sizeof(float), s, hf, d,
+                     d_hidden, w1, b1, w2, n_rows, part, max_rows);
+}
+
+// ====================================== decide: arg-max merge, threshold, compaction
+__device__ __forceinline__ u64 merge_partials(const u64* part, int n_wg, int Mpad, int m, int lane) {
+  u64 k = 0;
+  for (int i = lane; i < n_wg; i += 64) k = umax64(k, part[(size_t)i * Mpad + m]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) k = umax64(k, shfl_xor_u64(k, o));
+  return k;
+}
+
+// Single workgroup of 1024 threads (B <= 1024).  accept <=> sigmoid(logit) >= tau in float32.
+// Rejected rows are listed in ascending order: ballot + popcount inside each wave,
+// wave totals prefix-summed through LDS.
+__global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
+  __shared__ int s_tok[1024];
+  __shared__ int s_wave_cnt[16];
+  __shared__ int s_rej[1024];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int B = a.B;
+  for (int m = w; m < B; m += 16) {
+    u64 k = merge_partials(a.am_part, a.n_lm_wg, a.Mpad, m, lane);
+    if (lane == 0) s_tok[m] = key_index(k);
+  }
+  __syncthreads();
+  bool active = tid < B;
+  float score = 0.f;
+  bool acc = true;
+  if (active) {
+    float z = a.b2[0];
+    for (int c = 0; c < a.n_chunks; ++c) z += a.ver_part[(size_t)c * B + tid];
+    score = 1.0f / (1.0f + expf(-z));
+    acc = score >= *a.tau_ptr;
+  }
+  const bool rej = active && !acc;
+  const u64 mask = __ballot(rej);
+  const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+  if (lane == 0) s_wave_cnt[w] = __popcll(mask);
+  __syncthreads();
+  int off = 0, total = 0;
+  for (int q = 0; q < 16; ++q) {
+    int c = s_wave_cnt[q];
+    if (q < w) off += c;
+    total += c;
+  }
+  if (rej) s_rej[off + rank] = tid;
+  if (active) {
+    int dt = s_tok[tid];
+    a.draft_tok[tid] = dt;
+    a.score[tid] = score;
+    a.accept[tid] = acc ? 1 : 0;
+    a.committed[tid] = acc ? dt : -1;
+    if (a.o_draft_tok) a.o_draft_tok[tid] = dt;
+    if (a.o_score) a.o_score[tid] = score;
+    if (a.o_accept) a.o_accept[tid] = acc ? 1 : 0;
+  }
+  __syncthreads();
+  if (tid < total) {
+    int b = s_rej[tid];
+    a.rej_idx[tid] = b;
+    if (a.o_rej_idx) a.o_rej_idx[tid] = b;
+    a.t_b[tid] = b;
+    a.t_tok[tid] = a.st.last_tok[b];
+    a.t_pos[tid] = a.st.len_q[b];       // true position id of the input token
+    a.t_slot[tid] = a.st.len_p[b];      // next free slot of the row's target cache
+  }
+  if (tid == 0) {
+    *a.n_rej = total;
+    *a.t_n_rows = total;
+    if (a.o_n_rej) *a.o_n_rej = total;
+  }
+}
+void launch_draft_decide(const DecideArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_draft_decide, dim3(1), dim3(1024), 0, s, a);
+}
+
+// ===================== finish: target arg-max merge, scatter back, advance state
+__global__ __launch_bounds__(1024) void k_step_finish(FinishArgs a) {
+  __shared__ int s_commit[1024];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int B = a.B, R = *a.n_rej;
+  if (tid < B) s_commit[tid] = a.committed[tid];
+  __syncthreads();
+  for (int i = w; i < R; i += 16) {
+    u64 k = merge_partials(a.am_part, a.n_lm_wg, a.Mpad, i, lane);
+    if (lane == 0) s_commit[a.rej_idx[i]] = key_index(k);
+  }
+  __syncthreads();
+  const long long g = a.st.counters[3];
+  if (tid < B) {
+    int c = s_commit[tid];
+    bool acc = a.accept[tid] != 0;
+    a.committed[tid] = c;
+    a.st.last_tok[tid] = c;
+    int lq = a.st.len_q[tid] + 1;
+    a.st.len_q[tid] = lq;
+    if (!acc) {
+      a.st.len_p[tid] += 1;
+      a.st.n_target_calls[tid] += 1;
+    }
+    if (a.o_committed) a.o_committed[tid] = c;
+    if (a.n_tokens > 0 && g < a.n_tokens) {
+      size_t o = (size_t)tid * a.n_tokens + (size_t)g;
+      if (a.g_tok) a.g_tok[o] = c;
+      if (a.g_accept) a.g_accept[o] = acc ? 1 : 0;
+      if (a.g_score) a.g_score[o] = a.score[tid];
+      if (a.g_draft_tok) a.g_draft_tok[o] = a.draft_tok[tid];
+    }
+    // the next step's draft forward: every row, its last token at the next position
+    a.d_b[tid] = tid;
+    a.d_tok[tid] = c;
+    a.d_pos[tid] = lq;
+    a.d_slot[tid] = lq;
+  }
+  if (tid == 0) {
+    *a.d_n_rows = B;
+    a.st.counters[0] += 1;
+    a.st.counters[1] += (R > 0) ? 1 : 0;
+    a.st.counters[2] += R;
+    a.st.counters[3] = g + 1;
+  }
+}
+void launch_step_finish(const FinishArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_step_finish, dim3(1), dim3(1024), 0, s, a);
+}
+
+// ================================================================ prefill
+// Rows whose prompt still has a token at index j (other than its last one).
+__global__ __launch_bounds__(1024) void k_prefill_prep(const int* __restrict__ prompt, int max_prompt, int j, int B,
+                                                       const int* __restrict__ prompt_len, int* n_rows, int* rb,
+                                                       int* rtok, int* rpos, int* rslot) {
+  __shared__ int s_wave_cnt[16];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const bool on = tid < B && j < prompt_len[tid] - 1;
+  const u64 mask = __ballot(on);
+  const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+  if (lane == 0) s_wave_cnt[w] = __popcll(mask);
+  __syncthreads();
+  int off = 0, total = 0;
+  for (int q = 0; q < 16; ++q) {
+    int c = s_wave_cnt[q];
+    if (q < w) off += c;
+    total += c;
+  }
+  if (on) {
+    int i = off + rank;
+    rb[i] = tid;
+    rtok[i] = prompt[(size_t)tid * max_prompt + j];
+    rpos[i] = j;
+    rslot[i] = j;
+  }
+  if (tid == 0) *n_rows = total;
+}
+void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const int* prompt_len, int* n_rows, int* rb,
+                         int* rtok, int* rpos, int* rslot, hipStream_t s) {
+  hipLaunchKernelGGL(k_prefill_prep, dim3(1), dim3(1024), 0, s, prompt, max_prompt, j, B, prompt_len, n_rows, rb,
+                     rtok, rpos, rslot);
+}
+
+__global__ __launch_bounds__(1024) void k_prefill_finish(const int* __restrict__ prompt, int max_prompt, int B,
+                                                         State st, int* d_n_rows, int* d_b, int* d_tok, int* d_pos,
+                                                         int* d_slot) {
+  const int tid = threadIdx.x;
+  if (tid < B) {
+    int P = st.prompt_len[tid];
+    int last = prompt[(size_t)tid * max_prompt + P - 1];
+    st.last_tok[tid] = last;
+    st.len_q[tid] = P - 1;
+    st.len_p[tid] = P - 1;
+    st.n_target_calls[tid] = 0;
+    d_b[tid] = tid;
+    d_tok[tid] = last;
+    d_pos[tid] = P - 1;
+    d_slot[tid] = P - 1;
+  }
+  if (tid == 0) {
+    *d_n_rows = B;
+    st.counters[0] = st.counters[1] = st.counters[2] = st.counters[3] = 0;
+  }
+}
+void launch_prefill_finish(const int* prompt, int max_prompt, int B, State st, int* d_n_rows, int* d_b, int* d_tok,
+                           int* d_pos, int* d_slot, hipStream_t s) {
+  hipLaunchKernelGGL(k_prefill_finish, dim3(1), dim3(1024), 0, s, prompt, max_prompt, B, st, d_n_rows, d_b, d_tok,
+                     d_pos, d_slot);
+}
+
+__global__ void k_set_f32(float* p, float v) { *p = v; }
+void launch_set_f32(float* p, float v, hipStream_t s) { hipLaunchKernelGGL(k_set_f32, dim3(1), dim3(1), 0, s, p, v); }
+
+__global__ void k_reset_gen_idx(long long* counters) { counters[3] = 0; }
+void launch_reset_gen_idx(long long* counters, hipStream_t s) {
+  hipLaunchKernelGGL(k_reset_gen_idx, dim3(1), dim3(1), 0, s, counters);
+}
+
+__global__ __launch_bounds__(256) void k_copy_rows(const float* __restrict__ src, float* __restrict__ dst,
+                                                   const int* __restrict__ n_rows, int row_len) {
+  int r = blockIdx.x;
+  if (r >= *n_rows) return;
+  for (int k = threadIdx.x; k < row_len; k += 256) dst[(size_t)r * row_len + k] = src[(size_t)r * row_len + k];
+}
+void launch_copy_f32(const float* src, float* dst, const int* n_rows, int row_len, int max_rows, hipStream_t s) {
+  hipLaunchKernelGGL(k_copy_rows, dim3(max_rows), dim3(256), 0, s, src, dst, n_rows, row_len);
+}
+
+}  // namespace sprinter

@@ -1,0 +1,110 @@
+"""Shared helpers of the GPU parity tests: build both sides from one seeded
+workload, run them, and compare decision by decision with the tolerance bands.
+
+Tolerances (stated by the benchmark spec: logits / hidden states within 2e-2 in bf16 and
+1e-4 in fp32, max-abs or relative):
+  eps      = 1e-4 (fp32) | 2e-2 (bf16)      on logits and hidden states
+  token    mismatch tolerated iff the oracle's top-2 margin of the perturbed
+           logits is <= 2 * eps / T (both candidates moved by at most eps / T)
+  flag     mismatch tolerated iff |score_oracle - tau| <= eps_s, eps_s = eps / 4
+           (the sigmoid's slope is at most 1/4)
+Everything else must match bit for bit.
+"""
+from __future__ import annotations
+import numpy as np
+import workloads as W
+from oracle import model as om, sprinter as osp
+
+
+def eps_of(cfg):
+    return 1e-4 if cfg.dtype == W.DT_F32 else 2e-2
+
+
+class Pair:
+    """The same workload on both sides."""
+
+    def __init__(self, cfg, ver_scale=1.0, ver_bias_shift=0.0, weights=None, oracle_store=np.float64):
+        from paper_2502_04557_amd import binding
+        self.cfg = cfg
+        dw, tw, vw = weights if weights is not None else W.make_weights(cfg)
+        if ver_scale != 1.0 or ver_bias_shift != 0.0:
+            vw = {k: (v * np.float32(ver_scale) if k.endswith(("w1", "w2")) else v) for k, v in vw.items()}
+            vw["v.b2"] = vw["v.b2"] + np.float32(ver_bias_shift)
+        self.weights = (dw, tw, vw)
+        self.draft = om.Decoder(cfg.draft, dw, store=oracle_store)
+        self.target = om.Decoder(cfg.target, tw, store=oracle_store)
+        self.verifier = om.Verifier(vw)
+        self.gpu = binding.Sprinter(cfg)
+        self.gpu.load_weights(binding.DRAFT, dw)
+        self.gpu.load_weights(binding.TARGET, tw)
+        self.gpu.load_weights(binding.VERIFIER, vw)
+        self.prompts, self.plen = W.make_prompts(cfg)
+
+    def oracle(self, n_gen, tau=None, forced=None, rows=None, keep_logits=False):
+        cfg = self.cfg
+        pr, pl = (self.prompts, self.plen) if rows is None else (self.prompts[rows], self.plen[rows])
+        return osp.generate(self.draft, self.target, self.verifier, pr, pl, n_gen,
+                            cfg.tau if tau is None else tau, cfg.temperature, cfg.seed,
+                            forced=forced, rows=rows, keep_logits=keep_logits)
+
+    def gpu_generate(self, n_gen):
+        self.gpu.prefill(self.prompts, self.plen)
+        o = self.gpu.generate(n_gen)
+        st = self.gpu.stats()
+        return {k: v.cpu().numpy() for k, v in o.items()}, st
+
+    def gpu_steps(self, n_gen, debug=True):
+        self.gpu.prefill(self.prompts, self.plen)
+        outs = []
+        for _ in range(n_gen):
+            o = self.gpu.step(debug=debug)
+            outs.append({k: v.cpu().numpy() for k, v in o.items()})
+        return outs, self.gpu.stats()
+
+    def close(self):
+        self.gpu.close()
+
+
+def close_enough(a, b, eps):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return np.abs(a - b) <= eps * np.maximum(1.0, np.abs(b))
+
+
+def compare_replay(cfg, g, rec, rows=None, tau=None):
+    """g: GPU outputs (tok, accept, score, draft_tok [B,G]); rec: oracle record replayed on the
+    GPU's history.  Returns a report dict; raises AssertionError on an untolerated mismatch."""
+    eps = eps_of(cfg)
+    tau = cfg.tau if tau is None else tau
+    T = cfg.temperature if cfg.temperature > 0 else 1.0
+    sel = slice(None) if rows is None else rows
+    gt, ga, gs, gd = g["tok"][sel], g["accept"][sel], g["score"][sel], g["draft_tok"][sel]
+    G = rec["tok"].shape[1]
+    gt, ga, gs, gd = gt[:, :G], ga[:, :G], gs[:, :G], gd[:, :G]
+    rep = {}
+    # scores
+    ds = np.abs(gs.astype(np.float64) - rec["score"].astype(np.float64))
+    rep["max_score_diff"] = float(ds.max())
+    eps_s = eps / 4
+    assert ds.max() <= eps_s, f"verifier score differs by {ds.max()} > {eps_s}"
+    # flags
+    bad = ga != rec["accept"]
+    near = np.abs(rec["score"].astype(np.float64) - np.float32(tau)) <= eps_s
+    rep["flag_flips_tolerated"] = int(bad.sum())
+    assert not (bad & ~near).any(), f"accept flag mismatch outside the band at {np.argwhere(bad & ~near)[:5]}"
+    # the GPU's own flags obey the rule on the GPU's own scores
+    assert np.array_equal(ga, (gs >= np.float32(tau)).astype(np.uint8))
+    # draft tokens
+    bad = gd != rec["draft_tok"]
+    near = rec["draft_margin"] <= 2 * eps / T
+    rep["draft_tok_flips_tolerated"] = int(bad.sum())
+    assert not (bad & ~near).any(), f"draft token mismatch outside the band at {np.argwhere(bad & ~near)[:5]}"
+    # committed tokens: accepted -> the GPU's own draft token; rejected -> the target's sample
+    acc = ga.astype(bool)
+    assert np.array_equal(gt[acc], gd[acc])
+    bad = (~acc) & (gt != rec["target_tok"])
+    near = rec["target_margin"] <= 2 * eps / T
+    rep["target_tok_flips_tolerated"] = int(bad.sum())
+    assert not (bad & ~near).any(), f"target token mismatch outside the band at {np.argwhere(bad & ~near)[:5]}"
+    rep["n"] = int(ga.size)
+    rep["reject_rate"] = float(1 - ga.mean())
+    return rep

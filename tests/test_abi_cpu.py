@@ -1,0 +1,86 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every
+symbol the header declares, and validates configurations without a GPU."""
+import ctypes as C
+import os
+import re
+import pytest
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_04557_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_library(verbose=False)
+    return binding.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    hdr = open(os.path.join(ROOT, "include", "sprinter.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(sprinter_[a-z_]+)\s*\(", hdr))
+    assert {"sprinter_load_weights", "sprinter_prefill", "sprinter_step", "sprinter_generate"} <= declared
+    from paper_2502_04557_amd import binding
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    from paper_2502_04557_amd import binding
+    assert C.sizeof(binding.ModelCfgC) == 40
+    assert C.sizeof(binding.CfgC) == 2 * 40 + 5 * 4 + 2 * 4 + 8 + 2 * 4 + 4   # incl. 4 bytes padding before seed
+    assert binding.CfgC.seed.offset % 8 == 0
+    assert C.sizeof(binding.StepOutC) == 10 * 8 and C.sizeof(binding.StatsC) == 32
+
+
+def _ws(lib, cfg):
+    from paper_2502_04557_amd import binding
+    c = binding.cfg_to_c(cfg)
+    n = C.c_size_t(0)
+    rc = lib.sprinter_workspace_bytes(C.byref(c), C.byref(n))
+    return rc, n.value, lib.sprinter_last_error(None).decode()
+
+
+def test_workspace_sizes_cover_kv_caches(lib):
+    for name in W.CONFIG_NAMES:
+        cfg = W.config(name)
+        rc, n, _ = _ws(lib, cfg)
+        assert rc == 0
+        es = 4 if cfg.dtype == W.DT_F32 else 2
+        kv = sum(2 * m.n_layer * cfg.max_batch * m.n_kv_head * cfg.max_seq * m.d_head * es
+                 for m in (cfg.draft, cfg.target))
+        assert n > kv and n < kv + 40e9
+
+
+def test_config_validation(lib):
+    from dataclasses import replace
+    base = W.mini_config("gpt", W.DT_BF16)
+    cases = [
+        (replace(base, draft=replace(base.draft, d_model=200)), "not divisible"),
+        (replace(base, draft=replace(base.draft, n_head=2)), "head dimension"),           # 96
+        (replace(base, target=replace(base.target, vocab=999)), "vocabular"),
+        (replace(base, max_batch=0), "max_batch"),
+        (replace(base, max_batch=2000), "max_batch"),
+        (replace(base, max_seq=4096), "max_pos"),
+        (replace(base, dtype=7), "dtype"),
+        (replace(base, target_ctx_mode=1), "target_ctx_mode"),
+        (replace(base, temperature=-1.0), "temperature"),
+        (replace(base, draft=replace(base.draft, arch=5)), "arch"),
+        (replace(base, draft=replace(base.draft, d_ff=643)), "multiples of 8"),
+    ]
+    for cfg, word in cases:
+        rc, _, msg = _ws(lib, cfg)
+        assert rc == -2 and word in msg, (rc, msg, word)
+    from paper_2502_04557_amd import binding
+    c = binding.cfg_to_c(base)
+    c.ver_d_in = 100
+    n = C.c_size_t(0)
+    assert lib.sprinter_workspace_bytes(C.byref(c), C.byref(n)) == -2
+    assert lib.sprinter_workspace_bytes(None, C.byref(n)) == -1
+    # no GPU work is needed to refuse a NULL context
+    assert lib.sprinter_step(None, None) == -1
+    assert lib.sprinter_generate(None, 4, None, None, None, None) == -1
+    assert lib.sprinter_prefill(None, None, None, 1, 1) == -1

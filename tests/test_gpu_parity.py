@@ -1,0 +1,163 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Run with -m gpu on an MI355X."""
+import numpy as np
+import pytest
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(cfg, **kw):
+    from parity_util import Pair
+    return Pair(cfg, **kw)
+
+
+def test_c1_free_run_is_identical():
+    """Config 1 (fp32, batch 1, seed 0): free-running GPU and oracle agree on every
+    token, flag and score of the 64 generated positions."""
+    from parity_util import compare_replay
+    cfg = W.config("c1")
+    p = _pair(cfg)
+    g, st = p.gpu_generate(cfg.n_gen)
+    rec = p.oracle(cfg.n_gen)
+    print("c1 gpu tok", g["tok"][0, :16], "oracle", rec["tok"][0, :16], flush=True)
+    assert np.array_equal(g["tok"], rec["tok"])
+    assert np.array_equal(g["accept"], rec["accept"])
+    assert np.array_equal(g["draft_tok"], rec["draft_tok"])
+    assert np.abs(g["score"] - rec["score"]).max() < 2.5e-5
+    assert st["steps"] == cfg.n_gen and st["sum_rejected"] == int((rec["accept"] == 0).sum())
+    assert np.array_equal(st["target_calls"], rec["n_target_calls"])
+    print(compare_replay(cfg, g, rec))
+    p.close()
+
+
+@pytest.mark.parametrize("kind,dtype", [("gpt", W.DT_F32), ("llama", W.DT_F32), ("linear", W.DT_F32),
+                                        ("gpt", W.DT_BF16), ("llama", W.DT_BF16), ("linear", W.DT_BF16)])
+def test_mini_step_by_step(kind, dtype):
+    """Every per-step output of sprinter_step against the oracle replayed on the GPU's
+    history: logits and hidden states within eps, tokens / flags / index lists exact
+    outside the bands; then sprinter_generate must reproduce the step loop bit for bit."""
+    from parity_util import compare_replay, close_enough, eps_of
+    cfg = W.mini_config(kind, dtype)
+    p = _pair(cfg, ver_scale=8.0)
+    eps = eps_of(cfg)
+    G = cfg.n_gen
+    outs, st = p.gpu_steps(G, debug=True)
+    g = {k: np.stack([o[k2] for o in outs], axis=1) for k, k2 in
+         (("tok", "committed_tok"), ("accept", "accept"), ("score", "score"), ("draft_tok", "draft_tok"))}
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"]), keep_logits=True)
+    rep = compare_replay(cfg, g, rec)
+    print(kind, dtype, rep, flush=True)
+    worst = 0.0
+    for s, o in enumerate(outs):
+        R = int(o["n_rej"][0])
+        rej = list(np.flatnonzero(o["accept"] == 0))
+        assert R == len(rej) and list(o["rej_idx"][:R]) == rej          # stable ascending compaction
+        assert close_enough(o["draft_logits"], rec["draft_logits"][s], eps).all()
+        assert close_enough(o["draft_hidden"], rec["draft_hidden"][s], eps).all()
+        worst = max(worst, np.abs(o["draft_logits"] - rec["draft_logits"][s]).max())
+        if R:
+            assert rec["rejected"][s] == rej
+            assert close_enough(o["target_logits"][:R], rec["target_logits"][s], eps).all()
+            assert close_enough(o["target_hidden"][:R], rec["target_hidden"][s], eps).all()
+            worst = max(worst, np.abs(o["target_logits"][:R] - rec["target_logits"][s]).max())
+    print("max |logit diff|", worst, flush=True)
+    assert 0.05 < rep["reject_rate"] < 0.95
+    assert st["steps"] == G and st["sum_rejected"] == int((g["accept"] == 0).sum())
+    assert np.array_equal(st["target_calls"], (g["accept"] == 0).sum(1))
+    assert st["steps_with_target"] == sum(1 for o in outs if o["n_rej"][0] > 0)
+    # the two entry points agree bit for bit, and a second run is bit-identical (determinism)
+    g2, st2 = p.gpu_generate(G)
+    for k in ("tok", "accept", "draft_tok"):
+        assert np.array_equal(g2[k], g[k]), k
+    assert np.array_equal(g2["score"].view(np.uint32), g["score"].view(np.uint32))
+    g3, _ = p.gpu_generate(G)
+    for k in g2:
+        assert np.array_equal(g3[k].view(np.uint8), g2[k].view(np.uint8)), k
+    p.close()
+
+
+@pytest.mark.parametrize("kind", ["gpt", "llama"])
+def test_threshold_extremes(kind):
+    """tau = 0: every token accepted, the target never runs, output = pure draft decoding.
+    tau > 1: every token rejected, output = pure target decoding."""
+    from parity_util import compare_replay
+    cfg = W.mini_config(kind, W.DT_F32, n_gen=8)
+    p = _pair(cfg)
+    p.gpu.set_tau(0.0)
+    g, st = p.gpu_generate(8)
+    rec = p.oracle(8, tau=0.0)
+    assert g["accept"].all() and st["sum_rejected"] == 0 and st["steps_with_target"] == 0
+    assert np.array_equal(g["tok"], rec["tok"]) and np.array_equal(g["tok"], g["draft_tok"])
+    p.gpu.set_tau(1.5)
+    g, st = p.gpu_generate(8)
+    rec = p.oracle(8, tau=1.5)
+    assert not g["accept"].any() and st["sum_rejected"] == 8 * cfg.batch and st["steps_with_target"] == 8
+    assert np.array_equal(g["tok"], rec["tok"])
+    assert np.array_equal(st["target_calls"], np.full(cfg.batch, 8))
+    p.close()
+
+
+def test_greedy_temperature_zero():
+    from dataclasses import replace
+    cfg = replace(W.mini_config("llama", W.DT_F32, n_gen=8), temperature=0.0)
+    p = _pair(cfg, ver_scale=8.0)
+    g, _ = p.gpu_generate(8)
+    rec = p.oracle(8)
+    assert np.array_equal(g["tok"], rec["tok"]) and np.array_equal(g["accept"], rec["accept"])
+    p.close()
+
+
+def test_error_paths():
+    from dataclasses import replace
+    from paper_2502_04557_amd import binding
+    cfg = W.mini_config("gpt", W.DT_F32)
+    s = binding.Sprinter(cfg)
+    dw, tw, vw = W.make_weights(cfg)
+    with pytest.raises(binding.SprinterError) as e:          # generate before weights
+        s.prefill(*W.make_prompts(cfg))
+    assert e.value.code == -4
+    bad = dict(dw); bad.pop("l0.wo")
+    with pytest.raises(binding.SprinterError) as e:
+        s.load_weights(binding.DRAFT, bad)
+    assert e.value.code == -4 and "l0.wo" in str(e.value)
+    bad = dict(dw); bad["l0.wo"] = bad["l0.wo"][:, :-8]
+    with pytest.raises(binding.SprinterError) as e:
+        s.load_weights(binding.DRAFT, bad)
+    assert e.value.code == -4
+    bad = dict(dw); bad["nonsense"] = bad["l0.wo"]
+    with pytest.raises(binding.SprinterError):
+        s.load_weights(binding.DRAFT, bad)
+    s.load_weights(binding.DRAFT, dw); s.load_weights(binding.TARGET, tw); s.load_weights(binding.VERIFIER, vw)
+    with pytest.raises(binding.SprinterError) as e:          # step before prefill
+        s.step()
+    assert e.value.code == -6
+    prompts, plen = W.make_prompts(cfg)
+    with pytest.raises(binding.SprinterError) as e:          # batch too large
+        s.prefill(np.zeros((cfg.max_batch + 1, 4), np.int32), np.full(cfg.max_batch + 1, 4, np.int32))
+    assert e.value.code == -5
+    with pytest.raises(binding.SprinterError) as e:          # zero-length prompt
+        s.prefill(prompts, np.zeros_like(plen))
+    assert e.value.code == -5
+    s.prefill(prompts, plen)
+    with pytest.raises(binding.SprinterError) as e:          # would run past max_seq
+        s.generate(cfg.max_seq)
+    assert e.value.code == -5
+    out = s.generate(cfg.max_seq - int(plen.max()) + 1)       # exactly fills the cache: allowed
+    assert out["tok"].shape[1] == cfg.max_seq - int(plen.max()) + 1
+    with pytest.raises(binding.SprinterError):
+        s.step()
+    s.close()
+
+
+def test_single_token_prompt_and_full_batch():
+    """Degenerate inputs: prompts of length 1 (empty prefill) and the maximum batch."""
+    from dataclasses import replace
+    from parity_util import compare_replay
+    cfg = replace(W.mini_config("llama", W.DT_BF16), prompt_len=1, prompt_len_min=0, n_gen=6)
+    p = _pair(cfg, ver_scale=8.0)
+    assert p.plen.max() == 1 and len(p.plen) == cfg.max_batch
+    g, _ = p.gpu_generate(6)
+    rec = p.oracle(6, forced=dict(tok=g["tok"], accept=g["accept"]))
+    print(compare_replay(cfg, g, rec))
+    p.close()
