@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched SPRINTER decode step on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+
+A "step" is one pass of the whole hot path over the batch: draft forward, sample,
+verifier, compaction, target forward on the rejected rows, scatter-back.  The
+workload is BASELINE config 2 (GPT-2-small/XL-shaped pair, bf16, batch 16, 128-token
+Zipf prompts, threshold 0.5) with synthetic random-init weights.  Prints one JSON line.
+"""
+from __future__ import annotations
+import argparse
+import json
+import os
+import sys
+import time
+from dataclasses import replace
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+
+
+def model_bytes(m, es):
+    """Weight bytes one forward streams: every block matrix + the LM head (embedding rows are gathered)."""
+    d, ff = m.d_model, m.d_ff
+    per_layer = m.d_qkv * d + d * m.n_head * m.d_head + (2 if m.arch == 0 else 3) * d * ff
+    return (m.n_layer * per_layer + m.vocab * d) * es
+
+
+def kv_bytes_per_token(m, es):
+    return 2 * m.n_layer * m.n_kv_head * m.d_head * es
+
+
+def algorithmic_bytes(cfg, plen, accept, first_step):
+    """Bytes the method must move per step, from the actual accept flags:
+    draft weights + draft KV (read len+1, write 1) + verifier + [R>0](target weights + target KV of the R rows)."""
+    import numpy as np
+    es = 4 if cfg.dtype == 0 else 2
+    Wq, Wp = model_bytes(cfg.draft, es), model_bytes(cfg.target, es)
+    kq, kp = kv_bytes_per_token(cfg.draft, es), kv_bytes_per_token(cfg.target, es)
+    h = cfg.ver_d_hidden
+    Wv = ((cfg.ver_d_in * h + 2 * h + 1) if h else (cfg.ver_d_in + 1)) * 4
+    B, K = accept.shape
+    rej = (accept == 0)
+    len_q = (plen[:, None] - 1) + first_step + np.arange(K)[None, :]          # entries before the step
+    calls_before = np.cumsum(rej, axis=1) - rej                                  # target calls before the step
+    len_p = (plen[:, None] - 1) + calls_before
+    per_step = np.full(K, float(Wq + Wv))
+    per_step += ((len_q + 2) * kq).sum(0)                                         # read len+1, write 1
+    R = rej.sum(0)
+    per_step += (R > 0) * Wp + (rej * (len_p + 2) * kp).sum(0)
+    return per_step, R
+
+
+def cpu_baseline(cfg, weights, n_rows, max_seconds=15.0, max_steps=64):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import workloads as W
+    from oracle import model as om, sprinter as osp
+    dw, tw, vw = weights
+    d, t, v = om.Decoder(cfg.draft, dw), om.Decoder(cfg.target, tw), om.Verifier(vw)
+    prompts, plen = W.make_prompts(cfg)
+    prompts, plen = prompts[:n_rows, :2].copy(), np.full(n_rows, 2, np.int32)
+    dc, tc = osp.prefill(d, prompts, plen), osp.prefill(t, prompts, plen)
+    steps, t0 = 0, time.perf_counter()
+    rec = None
+    forced = None
+    # one generate call per step so that the run can stop on the time bound
+    seqs = [list(p) for p in prompts]
+    while steps < max_steps and time.perf_counter() - t0 < max_seconds:
+        pr = np.array(seqs, dtype=np.int32)
+        pl = np.full(n_rows, pr.shape[1], np.int32)
+        rec = osp.generate(d, t, v, pr, pl, 1, cfg.tau, cfg.temperature, cfg.seed, draft_caches=dc, target_caches=tc)
+        for b in range(n_rows):
+            seqs[b].append(int(rec["tok"][b, 0]))
+        steps += 1
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=n_rows * steps / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"{cfg.name}: first {n_rows} rows, prompts cut to 2 tokens, {steps} decode steps "
+                       f"in {dt:.1f} s (NumPy float64, os.cpu_count()={os.cpu_count()})")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU decode step only; this build has no multi-GPU path "
+              f"(--gpus {args.gpus} is not supported, use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2502_04557_amd import binding
+
+    base = W.config(args.config)
+    K, Wm = args.steps, args.warmup
+    pmax = base.prompt_len
+    need = pmax + Wm + K
+    lim = min(m.max_pos for m in (base.draft, base.target))
+    if need > lim:
+        raise SystemExit(f"prompt {pmax} + warmup {Wm} + steps {K} exceeds the models' context {lim}")
+    cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau)
+
+    t0 = time.time()
+    weights = W.make_weights(cfg)
+    prompts, plen = W.make_prompts(cfg)
+    print(f"[bench] {cfg.name}: weights generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 26, dtype=torch.float32, device="cuda:0")      # 256 MiB read + 256 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    s = binding.Sprinter(cfg, "cuda:0")
+    for which, w in zip((binding.DRAFT, binding.TARGET, binding.VERIFIER), weights):
+        s.load_weights(which, w)
+    B = len(plen)
+    dev = s.device
+    s.prefill(prompts, plen)
+    if Wm:
+        s.generate(Wm, want=("tok",))
+    tok = torch.zeros(B, K, dtype=torch.int32, device=dev)
+    acc = torch.zeros(B, K, dtype=torch.uint8, device=dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(s.stream)
+    s.generate_into(K, tok=tok, accept=acc)
+    ev1.record(s.stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    st = s.stats()
+    accept = acc.cpu().numpy()
+    per_step_bytes, R = algorithmic_bytes(cfg, plen, accept, Wm)
+    step_ms = ev_ms / K
+    achieved = per_step_bytes.mean() / (step_ms * 1e-3) / 1e9
+    out = {
+        "metric": "generated tokens/sec at batch B (1 GPU)",
+        "value": B * K / wall,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": wall * 1e3 / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: batch {B}, prompt {pmax}, tau {cfg.tau}, T {cfg.temperature}; "
+                               f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
+                               f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts",
+                   "batch": B, "prompt_len": pmax},
+        "target_calls_per_token": float(R.sum() / (B * K)),
+        "steps_with_target_frac": float((R > 0).mean()),
+        "avg_accepted_run": float(accept.sum() / max(1, (accept == 0).sum())),
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "one decode step (all kernels of sprinter_step)",
+                     "bytes_per_launch": float(per_step_bytes.mean()), "ms_per_launch": step_ms},
+    }
+    s.close()
+    del s
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, weights, B)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -146,8 +146,9 @@ class Decoder:
         return hf, hf @ self.lm_head.T
 
     # ---- route 1: whole sequence, no cache ----------------------------------
-    def forward_full(self, tokens, positions=None):
-        """tokens [T] (one row) -> (hf [T, d], logits [T, V]); entry j attends to entries <= j."""
+    def forward_full(self, tokens, positions=None, cache=None, want_logits=True):
+        """tokens [T] (one row) -> (hf [T, d], logits [T, V]); entry j attends to entries <= j.
+        If an (empty) cache is given, the keys and values of all T entries are left in it."""
         tokens = np.asarray(tokens)
         T = tokens.shape[0]
         pos = np.arange(T) if positions is None else np.asarray(positions)
@@ -157,6 +158,14 @@ class Decoder:
             a = np.stack([attend(q[j], k[:j + 1], v[:j + 1]) for j in range(T)])
             h = self._attn_out(i, h, a)
             h = self._ffn(i, h)
+            if cache is not None:
+                assert len(cache.K[i]) == 0
+                cache.K[i].extend(k[j] for j in range(T))
+                cache.V[i].extend(v[j] for j in range(T))
+        if cache is not None:
+            cache.positions.extend(int(p) for p in pos)
+        if not want_logits:
+            return self._norm(h, "normf"), None
         return self._head(h)
 
     # ---- route 2: one token per row against that row's cache ------------------

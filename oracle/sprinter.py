@@ -65,6 +65,19 @@ def prefill(model, prompts, prompt_len):
     return caches
 
 
+def prefill_whole_prompt(model, prompts, prompt_len):
+    """Same caches as prefill(), filled by one uncached forward per row (matrix-matrix
+    products instead of one matrix-vector product per token; used for the large models)."""
+    caches = []
+    for b in range(len(prompt_len)):
+        c = model.new_cache()
+        n = int(prompt_len[b]) - 1
+        if n > 0:
+            model.forward_full(list(prompts[b][:n]), cache=c, want_logits=False)
+        caches.append(c)
+    return caches
+
+
 def generate(draft, target, verifier, prompts, prompt_len, n_gen, tau, temperature, seed,
              ctx_mode=CTX_OWN_HISTORY, forced=None, rows=None, keep_logits=False,
              draft_caches=None, target_caches=None):

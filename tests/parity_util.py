@@ -40,12 +40,18 @@ class Pair:
         self.gpu.load_weights(binding.VERIFIER, vw)
         self.prompts, self.plen = W.make_prompts(cfg)
 
-    def oracle(self, n_gen, tau=None, forced=None, rows=None, keep_logits=False):
+    def oracle(self, n_gen, tau=None, forced=None, rows=None, keep_logits=False, whole_prompt_prefill=False):
         cfg = self.cfg
         pr, pl = (self.prompts, self.plen) if rows is None else (self.prompts[rows], self.plen[rows])
+        if forced is not None and rows is not None:
+            forced = {k: np.asarray(v)[rows] for k, v in forced.items()}
+        caches = {}
+        if whole_prompt_prefill:
+            caches = dict(draft_caches=osp.prefill_whole_prompt(self.draft, pr, pl),
+                          target_caches=osp.prefill_whole_prompt(self.target, pr, pl))
         return osp.generate(self.draft, self.target, self.verifier, pr, pl, n_gen,
                             cfg.tau if tau is None else tau, cfg.temperature, cfg.seed,
-                            forced=forced, rows=rows, keep_logits=keep_logits)
+                            forced=forced, rows=rows, keep_logits=keep_logits, **caches)
 
     def gpu_generate(self, n_gen):
         self.gpu.prefill(self.prompts, self.plen)

@@ -161,3 +161,30 @@ def test_single_token_prompt_and_full_batch():
     rec = p.oracle(6, forced=dict(tok=g["tok"], accept=g["accept"]))
     print(compare_replay(cfg, g, rec))
     p.close()
+
+
+def test_c2_full_size_sampled_rows():
+    """Config 2 at its full size and in the launch configuration the benchmark times
+    (GPT-2-small/XL shapes, bf16, batch 16, 128-token Zipf prompts): the oracle replays
+    a sample of rows (first, last, two seeded) over the first steps on the GPU's history."""
+    import time
+    from parity_util import compare_replay
+    cfg = W.config("c2")
+    t0 = time.time()
+    p = _pair(cfg)
+    print(f"c2 built in {time.time() - t0:.0f} s", flush=True)
+    G = 24
+    g, st = p.gpu_generate(G)
+    print(f"gpu done, reject rate {1 - g['accept'].mean():.3f}, steps_with_target {st['steps_with_target']}", flush=True)
+    rng = np.random.default_rng(7)
+    rows = sorted({0, cfg.batch - 1, *rng.choice(np.arange(1, cfg.batch - 1), 2, replace=False).tolist()})
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"]), rows=rows, whole_prompt_prefill=True)
+    rep = compare_replay(cfg, g, rec, rows=rows)
+    print("c2 rows", rows, rep, f"total {time.time() - t0:.0f} s", flush=True)
+    # properties that hold for every row at any size
+    assert np.array_equal(g["accept"], (g["score"] >= np.float32(cfg.tau)).astype(np.uint8))
+    acc = g["accept"].astype(bool)
+    assert np.array_equal(g["tok"][acc], g["draft_tok"][acc])
+    assert np.array_equal(st["target_calls"], (~acc).sum(1))
+    assert (g["tok"] >= 0).all() and (g["tok"] < cfg.draft.vocab).all()
+    p.close()

@@ -117,6 +117,19 @@ def test_replay_mode_follows_forced_history(run):
     assert np.array_equal(rep2["tok"][1:], rec["tok"][1:])      # other rows untouched
 
 
+def test_whole_prompt_prefill_equals_token_by_token_prefill(run):
+    cfg, d, t, v, prompts, plen, rec = run
+    for m in (d, t):
+        a, b = osp.prefill(m, prompts, plen), osp.prefill_whole_prompt(m, prompts, plen)
+        for ca, cb in zip(a, b):
+            assert ca.positions == cb.positions
+            for i in range(m.cfg.n_layer):
+                assert len(ca.K[i]) == len(cb.K[i])
+                if ca.K[i]:
+                    assert np.abs(np.stack(ca.K[i]) - np.stack(cb.K[i])).max() < 1e-12
+                    assert np.abs(np.stack(ca.V[i]) - np.stack(cb.V[i])).max() < 1e-12
+
+
 def test_row_subset_uses_original_row_streams(run):
     cfg, d, t, v, prompts, plen, rec = run
     sub = [len(plen) - 1, 0]
