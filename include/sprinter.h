@@ -179,6 +179,14 @@ int sprinter_set_tau(sprinter_ctx* ctx, float tau);
  * host_target_calls, if not NULL, receives the per-row number of target calls [B]. */
 int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* host_target_calls);
 
+/* For tuning tools and other callers that want a time breakdown (no paper passage: a
+ * diagnostic).  With the environment variable SPRINTER_PHASE_TICKS=1 set at create time,
+ * workgroup 0 of the persistent decode kernel accumulates 100 MHz clock ticks per phase
+ * type; this call waits for the stream and copies 32 words to host_out: [0..15] ticks of
+ * embed, norm, QKV, attention, O-proj, FFN-up, FFN-down, LM head, verifier, decide, finish,
+ * barrier wait, per-step fence; [16..31] the matching event counts.  All zero when off. */
+int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out);
+
 void sprinter_destroy(sprinter_ctx* ctx);
 
 /* Text of the last error on ctx (or of the last failed sprinter_create /

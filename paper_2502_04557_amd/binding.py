@@ -17,7 +17,7 @@ DRAFT, TARGET, VERIFIER = 0, 1, 2
 F32, BF16 = 0, 1
 
 EXPORTS = ("sprinter_workspace_bytes", "sprinter_create", "sprinter_load_weights", "sprinter_prefill",
-           "sprinter_step", "sprinter_generate", "sprinter_set_tau", "sprinter_get_stats",
+           "sprinter_step", "sprinter_generate", "sprinter_set_tau", "sprinter_get_stats", "sprinter_debug_phase_ticks",
            "sprinter_destroy", "sprinter_last_error")
 
 
@@ -64,6 +64,7 @@ def load_library(path: str = LIB_PATH):
     lib.sprinter_generate.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.sprinter_set_tau.argtypes = [vp, C.c_float]
     lib.sprinter_get_stats.argtypes = [vp, C.POINTER(StatsC), C.POINTER(C.c_int64)]
+    lib.sprinter_debug_phase_ticks.argtypes = [vp, C.POINTER(C.c_uint64)]
     lib.sprinter_destroy.argtypes = [vp]
     lib.sprinter_destroy.restype = None
     lib.sprinter_last_error.argtypes = [vp]
@@ -206,6 +207,13 @@ class Sprinter:
 
     def set_tau(self, tau: float):
         self._check(self.lib.sprinter_set_tau(self.ctx, tau), self.ctx)
+
+    def phase_ticks(self) -> dict:
+        buf = (C.c_uint64 * 32)()
+        self._check(self.lib.sprinter_debug_phase_ticks(self.ctx, buf), self.ctx)
+        names = ("embed", "norm", "qkv", "attn", "oproj", "ffn1", "ffn2", "lmhead", "verifier", "decide", "finish",
+                 "barrier", "fence", "g_prep", "g_mma", "st_ack")
+        return {n: (buf[i] / 100.0, int(buf[16 + i])) for i, n in enumerate(names)}   # (microseconds, events)
 
     def stats(self) -> dict:
         st = StatsC()

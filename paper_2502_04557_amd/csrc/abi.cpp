@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <unordered_map>
@@ -75,6 +76,16 @@ struct sprinter_ctx {
   float* score = nullptr;
   unsigned char* accept = nullptr;
   int rows_alloc = 0;
+  // persistent decode kernel (bf16 mode)
+  bool mega_on = false, mega_built = false;
+  int mega_mt = 1, mega_grid = 0;
+  size_t mega_smem = 0;
+  MegaParams mega_host;
+  MegaParams* mega_dev = nullptr;
+  LayerW *mega_layers_q = nullptr, *mega_layers_p = nullptr;
+  std::vector<PhaseDesc> mega_phases_q, mega_phases_p;
+  int* mega_err = nullptr;
+  unsigned long long* mega_prof = nullptr;
   // host bookkeeping
   int B = 0, max_prompt_len = 0;
   long long steps_done = 0;
@@ -108,6 +119,8 @@ size_t act_plane(int dtype, int rows, int K) { return (size_t)rows * (dtype == S
 // bf16 mode keeps every activation as hi + lo in two planes
 size_t act_elems(int dtype, int rows, int K) { return act_plane(dtype, rows, K) * (dtype == SPRINTER_F32 ? 1 : 2); }
 size_t packed_elems(int N, int K) { return (size_t)round_up(N, 16) * round_up(K, 32); }
+
+constexpr int MEGA_MAX_WG = 512;
 
 const char* check_model(const sprinter_model_cfg& m, const char* who, char* buf, size_t n) {
 #define BAD(...) do { snprintf(buf, n, __VA_ARGS__); return buf; } while (0)
@@ -258,8 +271,52 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   int* rej_idx = (int*)bump.take((size_t)c.max_batch * 4);
   int* n_rej = (int*)bump.take(4);
   int* committed = (int*)bump.take((size_t)c.max_batch * 4);
+  // buffers of the persistent decode kernel: one activation buffer per layer (written once per step)
+  MegaParams mp;
+  memset(&mp, 0, sizeof mp);
+  LayerW *lw_q = nullptr, *lw_p = nullptr;
+  MegaParams* mp_dev = nullptr;
+  if (c.dtype == SPRINTER_BF16) {
+    int which = 0;
+    for (const sprinter_model_cfg* mc : {&c.draft, &c.target}) {
+      MegaModel& mm = which == 0 ? mp.draft : mp.target;
+      ModelDims md = dims_of(*mc);
+      const int L = md.n_layer;
+      mm.md = md;
+      mm.pl_d = act_plane(c.dtype, rows, md.d);
+      mm.pl_a = act_plane(c.dtype, rows, md.H * md.dh);
+      mm.pl_f = act_plane(c.dtype, rows, md.ff);
+      mm.xn_stride = 2 * mm.pl_d; mm.ao_stride = 2 * mm.pl_a; mm.mid_stride = 2 * mm.pl_f;
+      mm.y_stride = (size_t)rows * md.dqkv; mm.h_stride = (size_t)rows * md.d;
+      mm.h0 = (float*)bump.take(mm.h_stride * 4);
+      mm.xn1 = (unsigned short*)bump.take(mm.xn_stride * L * 2);
+      mm.xn2 = (unsigned short*)bump.take(mm.xn_stride * L * 2);
+      mm.y = (float*)bump.take(mm.y_stride * L * 4);
+      mm.ao = (unsigned short*)bump.take(mm.ao_stride * L * 2);
+      mm.mid = (unsigned short*)bump.take(mm.mid_stride * L * 2);
+      mm.hA = (float*)bump.take(mm.h_stride * L * 4);
+      mm.hB = (float*)bump.take(mm.h_stride * L * 4);
+      mm.hf = (float*)bump.take(mm.h_stride * 4);
+      mm.hfn = (unsigned short*)bump.take(mm.xn_stride * 2);
+      mm.rope = (float*)bump.take((size_t)rows * md.dh * 4);
+      mm.stats_stride = (size_t)((md.d + 15) / 16) * 16 * 2;
+      mm.stats = (float*)bump.take(mm.stats_stride * (2 * L + 1) * 4);
+      mm.am_part = (unsigned long long*)bump.take((size_t)MEGA_MAX_WG * rows * 8);
+      LayerW* lw = (LayerW*)bump.take((size_t)L * sizeof(LayerW));
+      mm.phases = (const PhaseDesc*)bump.take((size_t)(7 * L + 4) * sizeof(PhaseDesc));
+      if (which == 0) lw_q = lw; else lw_p = lw;
+      ++which;
+    }
+    mp.sync = (unsigned*)bump.take(65536);
+    mp.epoch = (unsigned*)bump.take(256);
+    mp.err = (int*)bump.take(256);
+    mp.prof = (unsigned long long*)bump.take(256);
+    mp_dev = (MegaParams*)bump.take(sizeof(MegaParams));
+  }
   size_t total = (bump.off + 255) & ~(size_t)255;
   if (ctx) {
+    ctx->mega_host = mp; ctx->mega_layers_q = lw_q; ctx->mega_layers_p = lw_p; ctx->mega_dev = mp_dev;
+    ctx->mega_err = mp.err;
     ctx->ver_part = ver_part; ctx->ver_chunks = chunks; ctx->st = st; ctx->tau_dev = tau;
     ctx->draft_tok = draft_tok; ctx->score = score; ctx->accept = accept; ctx->rej_idx = rej_idx;
     ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows;
@@ -313,6 +370,133 @@ int check_ready(sprinter_ctx* ctx) {
   if (!ctx->draft.loaded || !ctx->target.loaded || !ctx->v_loaded)
     return fail(ctx, SPRINTER_E_WEIGHTS, "weights not loaded (draft %d, target %d, verifier %d)", (int)ctx->draft.loaded,
                 (int)ctx->target.loaded, (int)ctx->v_loaded);
+  return SPRINTER_OK;
+}
+
+// Fills the device-side description of both models for the persistent kernel (once, after all weights are in).
+int build_mega(sprinter_ctx* ctx) {
+  if (!ctx->mega_on || ctx->mega_built) return SPRINTER_OK;
+  MegaParams& hp = ctx->mega_host;
+  int which = 0;
+  for (Model* m : {&ctx->draft, &ctx->target}) {
+    MegaModel& mm = which == 0 ? hp.draft : hp.target;
+    LayerW* lw = which == 0 ? ctx->mega_layers_q : ctx->mega_layers_p;
+    mm.tok_emb = m->tok_emb; mm.pos_emb = m->pos_emb; mm.lm_head = m->lm_head;
+    mm.normf_g = (const float*)m->normf_g; mm.normf_b = (const float*)m->normf_b;
+    mm.layers = lw;
+    mm.kcache = m->kcache; mm.vcache = m->vcache; mm.layer_stride = m->layer_stride;
+    mm.rd_n = m->rd_n; mm.rd_b = m->rd_b; mm.rd_tok = m->rd_tok; mm.rd_pos = m->rd_pos; mm.rd_slot = m->rd_slot;
+    if (hipMemcpyAsync(lw, m->layers.data(), m->layers.size() * sizeof(LayerW), hipMemcpyHostToDevice, ctx->stream) !=
+        hipSuccess)
+      return fail(ctx, SPRINTER_E_HIP, "copy of the layer table failed");
+    {   // the phase list of one forward
+      std::vector<PhaseDesc>& ph = which == 0 ? ctx->mega_phases_q : ctx->mega_phases_p;
+      ph.clear();
+      const ModelDims& md = mm.md;
+      const int d = md.d, Kt_d = (d + 31) / 32, Kt_a = (md.H * md.dh + 31) / 32, Kt_f = (md.ff + 31) / 32;
+      const bool fused = ctx->mega_mt == 1;
+      const bool gpt = md.arch == SPRINTER_ARCH_GPT;
+      auto blank = [](int kind) { PhaseDesc p; memset(&p, 0, sizeof p); p.kind = kind; return p; };
+      auto norm_phase = [&](const float* h, const float* g, const float* b, unsigned short* out, float* f32_out) {
+        PhaseDesc p = blank(PK_NORM);
+        p.h = h; p.g = g; p.b = b; p.eps = md.eps; p.arch = md.arch; p.K = d; p.out_act = out; p.out_plane = mm.pl_d;
+        p.f32_out2 = f32_out;
+        return p;
+      };
+      ph.push_back(blank(PK_EMBED));
+      const float* h_prev = mm.h0;
+      const float* st_prev = mm.stats;
+      for (int l = 0; l < md.n_layer; ++l) {
+        const LayerW& L = m->layers[l];
+        unsigned short* xn1 = mm.xn1 + mm.xn_stride * l;
+        unsigned short* xn2 = mm.xn2 + mm.xn_stride * l;
+        float* y = mm.y + mm.y_stride * l;
+        unsigned short* ao = mm.ao + mm.ao_stride * l;
+        unsigned short* mid = mm.mid + mm.mid_stride * l;
+        float* hA = mm.hA + mm.h_stride * l;
+        float* hB = mm.hB + mm.h_stride * l;
+        float* stA = mm.stats + mm.stats_stride * (1 + 2 * l);
+        float* stB = mm.stats + mm.stats_stride * (2 + 2 * l);
+        if (!fused) ph.push_back(norm_phase(h_prev, L.n1g, L.n1b, xn1, nullptr));
+        {
+          PhaseDesc p = blank(PK_GEMM);
+          p.epi = EPI_F32; p.layer = 2; p.fused_norm = fused;
+          p.W = (const uint4*)L.wqkv; p.N = md.dqkv; p.Kt = Kt_d; p.n_tiles = (md.dqkv + 15) / 16; p.K = d; p.bias = L.bqkv;
+          if (fused) { p.h = h_prev; p.stats_in = st_prev; p.n_stat_tiles = (d + 15) / 16; p.g = L.n1g; p.b = L.n1b; p.eps = md.eps; p.arch = md.arch; }
+          else { p.X = (const uint4*)xn1; p.x_plane16 = mm.pl_d / 8; }
+          p.out_f32 = y; p.ldo = md.dqkv;
+          ph.push_back(p);
+        }
+        { PhaseDesc p = blank(PK_ATTN); p.layer = l; ph.push_back(p); }
+        {
+          PhaseDesc p = blank(PK_GEMM);
+          p.epi = EPI_RESID; p.layer = 4;
+          p.W = (const uint4*)L.wo; p.N = d; p.Kt = Kt_a; p.n_tiles = (d + 15) / 16; p.K = md.H * md.dh; p.bias = L.bo;
+          p.X = (const uint4*)ao; p.x_plane16 = mm.pl_a / 8;
+          p.resid = h_prev; p.out_f32 = hA; p.ldo = d; p.stats_out = fused ? stA : nullptr;
+          ph.push_back(p);
+        }
+        if (!fused) ph.push_back(norm_phase(hA, L.n2g, L.n2b, xn2, nullptr));
+        {
+          PhaseDesc p = blank(PK_GEMM);
+          p.epi = gpt ? EPI_GELU : EPI_SWIGLU; p.layer = 5; p.fused_norm = fused;
+          p.W = (const uint4*)(gpt ? L.w1 : L.wg); p.W2 = gpt ? nullptr : (const uint4*)L.wu;
+          p.N = md.ff; p.Kt = Kt_d; p.n_tiles = (md.ff + 15) / 16; p.K = d; p.bias = gpt ? L.b1 : nullptr;
+          if (fused) { p.h = hA; p.stats_in = stA; p.n_stat_tiles = (d + 15) / 16; p.g = L.n2g; p.b = L.n2b; p.eps = md.eps; p.arch = md.arch; }
+          else { p.X = (const uint4*)xn2; p.x_plane16 = mm.pl_d / 8; }
+          p.out_act = mid; p.out_K = md.ff; p.out_plane = mm.pl_f;
+          ph.push_back(p);
+        }
+        {
+          PhaseDesc p = blank(PK_GEMM);
+          p.epi = EPI_RESID; p.layer = 6;
+          p.W = (const uint4*)L.w2; p.N = d; p.Kt = Kt_f; p.n_tiles = (d + 15) / 16; p.K = md.ff; p.bias = L.b2;
+          p.X = (const uint4*)mid; p.x_plane16 = mm.pl_f / 8;
+          p.resid = hA; p.out_f32 = hB; p.ldo = d; p.stats_out = fused ? stB : nullptr;
+          ph.push_back(p);
+        }
+        h_prev = hB;
+        st_prev = stB;
+      }
+      ph.push_back(norm_phase(h_prev, (const float*)m->normf_g, (const float*)m->normf_b, mm.hfn, mm.hf));
+      ph.push_back(blank(PK_LMHEAD));
+      mm.n_phases = (int)ph.size();
+      if (hipMemcpyAsync((void*)mm.phases, ph.data(), ph.size() * sizeof(PhaseDesc), hipMemcpyHostToDevice, ctx->stream) !=
+          hipSuccess)
+        return fail(ctx, SPRINTER_E_HIP, "copy of the phase table failed");
+    }
+    ++which;
+  }
+  hp.v_w1 = (const float*)ctx->v_w1; hp.v_b1 = (const float*)ctx->v_b1;
+  hp.v_w2 = (const float*)ctx->v_w2; hp.v_b2 = (const float*)ctx->v_b2;
+  hp.ver_d_hidden = ctx->cfg.ver_d_hidden; hp.ver_chunks = ctx->ver_chunks; hp.ver_part = ctx->ver_part;
+  hp.st = ctx->st; hp.tau = ctx->tau_dev;
+  hp.draft_tok = ctx->draft_tok; hp.rej_idx = ctx->rej_idx; hp.n_rej = ctx->n_rej; hp.committed = ctx->committed;
+  hp.score = ctx->score; hp.accept = ctx->accept;
+  hp.seed_lo = (unsigned)(ctx->cfg.seed & 0xFFFFFFFFull); hp.seed_hi = (unsigned)(ctx->cfg.seed >> 32);
+  hp.inv_temperature = ctx->cfg.temperature > 0.f ? 1.0f / ctx->cfg.temperature : 0.f;
+  hp.rows_alloc = ctx->rows_alloc; hp.max_seq = ctx->cfg.max_seq; hp.max_batch = ctx->cfg.max_batch;
+  if (hipMemcpyAsync(ctx->mega_dev, &hp, sizeof hp, hipMemcpyHostToDevice, ctx->stream) != hipSuccess)
+    return fail(ctx, SPRINTER_E_HIP, "copy of the kernel parameters failed");
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
+  ctx->mega_built = true;
+  return SPRINTER_OK;
+}
+
+int enqueue_mega(sprinter_ctx* ctx, const sprinter_step_out* out, int n_steps, int n_tokens, int32_t* g_tok,
+                 uint8_t* g_accept, float* g_score, int32_t* g_draft_tok) {
+  MegaOut o;
+  memset(&o, 0, sizeof o);
+  o.B = ctx->B; o.n_tokens = n_tokens;
+  if (out) {
+    o.o_draft_tok = out->draft_tok; o.o_rej_idx = out->rej_idx; o.o_n_rej = out->n_rej;
+    o.o_committed = out->committed_tok; o.o_score = out->score; o.o_accept = out->accept;
+    o.o_draft_logits = out->draft_logits; o.o_draft_hidden = out->draft_hidden;
+    o.o_target_logits = out->target_logits; o.o_target_hidden = out->target_hidden;
+  }
+  o.g_tok = g_tok; o.g_draft_tok = g_draft_tok; o.g_accept = g_accept; o.g_score = g_score;
+  hipError_t e = launch_mega(ctx->mega_dev, ctx->mega_mt, n_steps, o, ctx->mega_smem, ctx->mega_grid, ctx->stream);
+  if (e != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "cooperative launch failed: %s", hipGetErrorString(e));
   return SPRINTER_OK;
 }
 
@@ -415,6 +599,46 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     launch_fill_zero(m->sc.hfn, act_elems(cfg->dtype, rows, m->md.d) * es, ctx->stream);
   }
   launch_set_f32(ctx->tau_dev, cfg->tau, ctx->stream);
+  if (cfg->dtype == SPRINTER_BF16) {
+    // operand-tile planes of the persistent kernel: padding lanes must read as zero
+    for (MegaModel* mm : {&ctx->mega_host.draft, &ctx->mega_host.target}) {
+      const int L = mm->md.n_layer;
+      launch_fill_zero(mm->xn1, mm->xn_stride * L * 2, ctx->stream);
+      launch_fill_zero(mm->xn2, mm->xn_stride * L * 2, ctx->stream);
+      launch_fill_zero(mm->ao, mm->ao_stride * L * 2, ctx->stream);
+      launch_fill_zero(mm->mid, mm->mid_stride * L * 2, ctx->stream);
+      launch_fill_zero(mm->hfn, mm->xn_stride * 2, ctx->stream);
+    }
+    launch_fill_zero(ctx->mega_host.sync, 65536, ctx->stream);
+    launch_fill_zero(ctx->mega_host.epoch, 256, ctx->stream);
+    launch_fill_zero(ctx->mega_host.err, 256, ctx->stream);
+    launch_fill_zero(ctx->mega_host.prof, 256, ctx->stream);
+    ctx->mega_prof = ctx->mega_host.prof;
+    {
+      const char* pp = getenv("SPRINTER_PHASE_TICKS");
+      if (!(pp && pp[0] == '1')) ctx->mega_host.prof = nullptr;
+    }
+    // the persistent kernel is opt-in while the per-operation kernels are the faster path
+    const char* on = getenv("SPRINTER_PERSISTENT");
+    if (on && on[0] == '1') {
+      const int rows = ctx->rows_alloc;
+      ctx->mega_mt = rows <= 16 ? 1 : rows <= 32 ? 2 : rows <= 64 ? 4 : 8;
+      MegaParams& hp = ctx->mega_host;
+      hp.max_seq = cfg->max_seq; hp.max_batch = cfg->max_batch; hp.rows_alloc = rows;
+      ctx->mega_smem = mega_smem_bytes(hp, ctx->mega_mt);
+      int grid = 0;
+      hipError_t e = ctx->mega_smem <= 160 * 1024 ? mega_prepare(ctx->mega_mt, ctx->mega_smem, &grid) : hipErrorInvalidValue;
+      int dev = 0, coop = 0;
+      (void)hipGetDevice(&dev);
+      (void)hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev);
+      if (e == hipSuccess && grid > 0 && coop) {
+        ctx->mega_on = true;
+        ctx->mega_grid = grid < MEGA_MAX_WG ? grid : MEGA_MAX_WG;
+      } else {
+        (void)hipGetLastError();   // the per-operation kernels remain available
+      }
+    }
+  }
   rc = hip_status(ctx, "sprinter_create");
   if (rc) { delete ctx; return rc; }
   *out_ctx = ctx;
@@ -481,6 +705,8 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
   if (!dev_prompt || !host_prompt_len) return fail(ctx, SPRINTER_E_NULL, "sprinter_prefill: NULL argument");
   int rc = check_ready(ctx);
   if (rc) return rc;
+  rc = build_mega(ctx);
+  if (rc) return rc;
   if (B < 1 || B > ctx->cfg.max_batch) return fail(ctx, SPRINTER_E_RANGE, "batch %d outside [1, %d]", B, ctx->cfg.max_batch);
   if (max_prompt < 1 || max_prompt > ctx->cfg.max_seq)
     return fail(ctx, SPRINTER_E_RANGE, "max_prompt %d outside [1, max_seq %d]", max_prompt, ctx->cfg.max_seq);
@@ -514,7 +740,12 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
   if (rc) return rc;
   rc = check_room(ctx, 1);
   if (rc) return rc;
-  enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
+  if (ctx->mega_on) {
+    rc = enqueue_mega(ctx, out, 1, 0, nullptr, nullptr, nullptr, nullptr);
+    if (rc) return rc;
+  } else {
+    enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
+  }
   ctx->steps_done += 1;
   return hip_status(ctx, "sprinter_step");
 }
@@ -528,8 +759,15 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
   rc = check_room(ctx, n_tokens);
   if (rc) return rc;
   launch_reset_gen_idx(ctx->st.counters, ctx->stream);
-  for (int g = 0; g < n_tokens; ++g)
-    enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+  if (ctx->mega_on) {
+    if (n_tokens > 0) {
+      rc = enqueue_mega(ctx, nullptr, n_tokens, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+      if (rc) return rc;
+    }
+  } else {
+    for (int g = 0; g < n_tokens; ++g)
+      enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+  }
   ctx->steps_done += n_tokens;
   return hip_status(ctx, "sprinter_generate");
 }
@@ -547,6 +785,12 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
   if (!host_out) return fail(ctx, SPRINTER_E_NULL, "sprinter_get_stats: NULL argument");
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
   long long c[4] = {0, 0, 0, 0};
+  if (ctx->mega_on) {
+    int derr = 0;
+    if (hipMemcpy(&derr, ctx->mega_err, 4, hipMemcpyDeviceToHost) != hipSuccess)
+      return fail(ctx, SPRINTER_E_HIP, "copy of the device error flag failed");
+    if (derr) return fail(ctx, SPRINTER_E_HIP, "a grid barrier of the persistent decode kernel timed out; results are invalid");
+  }
   if (ctx->prefilled) {
     if (hipMemcpy(c, ctx->st.counters, sizeof c, hipMemcpyDeviceToHost) != hipSuccess)
       return fail(ctx, SPRINTER_E_HIP, "copy of counters failed");
@@ -559,6 +803,16 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
   host_out->sum_rejected = c[2];
   host_out->batch = ctx->B;
   host_out->reserved = 0;
+  return SPRINTER_OK;
+}
+
+int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out) {
+  if (!ctx || !host_out) return fail(ctx, SPRINTER_E_NULL, "sprinter_debug_phase_ticks: NULL argument");
+  for (int i = 0; i < 32; ++i) host_out[i] = 0;
+  if (!ctx->mega_prof) return SPRINTER_OK;
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
+  if (hipMemcpy(host_out, ctx->mega_prof, 256, hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(ctx, SPRINTER_E_HIP, "copy of the tick counters failed");
   return SPRINTER_OK;
 }
 

@@ -5,129 +5,9 @@
 //   compaction of rejected rows -> target forward on those rows -> sample ->
 //   scatter back.  Every kernel reads the number of active rows from device
 //   memory, so the host never learns how many rows were rejected.
-#include "internal.h"
-#include <math.h>
+#include "dev.h"
 
 namespace sprinter {
-
-typedef unsigned short bf16_t;   // raw bfloat16 bits
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
-typedef unsigned long long u64;
-
-// ------------------------------------------------------------------ scalars
-__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {   // round to nearest even
-  unsigned u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);   // NaN stays NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-template <typename T> __device__ __forceinline__ float to_f(T v);
-template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
-template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
-template <typename T> __device__ __forceinline__ T from_f(float v);
-template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
-template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
-
-// Activation layout: float32 mode = row-major [m][K]; bf16 mode = MFMA operand tiles.
-template <typename T> __device__ __forceinline__ size_t act_idx(int m, int k, int K);
-template <> __device__ __forceinline__ size_t act_idx<float>(int m, int k, int K) { return (size_t)m * K + k; }
-template <> __device__ __forceinline__ size_t act_idx<bf16_t>(int m, int k, int K) {
-  int Kt = (K + 31) >> 5;
-  return ((size_t)(m >> 4) * Kt + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
-}
-
-// Store one activation.  In bf16 mode a value is kept as the sum of two bf16 numbers
-// (hi = RNE(v), lo = RNE(v - hi)) in two planes of operand tiles, so that the GEMM input
-// carries ~16 mantissa bits while the weights stay plain bf16; each plane is one MFMA operand.
-template <typename T> __device__ __forceinline__ void act_store(T* base, size_t plane, int m, int k, int K, float v);
-template <> __device__ __forceinline__ void act_store<float>(float* base, size_t, int m, int k, int K, float v) {
-  base[act_idx<float>(m, k, K)] = v;
-}
-template <> __device__ __forceinline__ void act_store<bf16_t>(bf16_t* base, size_t plane, int m, int k, int K, float v) {
-  size_t i = act_idx<bf16_t>(m, k, K);
-  bf16_t hi = f2bf(v);
-  base[i] = hi;
-  base[plane + i] = f2bf(v - bf2f(hi));
-}
-
-__device__ __forceinline__ float gelu_tanh(float x) {
-  const float c = 0.7978845608028654f;   // sqrt(2/pi)
-  return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
-}
-__device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
-
-// ------------------------------------------------------------- reductions
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
-}
-__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int o) {
-  unsigned lo = __shfl_xor((unsigned)v, o), hi = __shfl_xor((unsigned)(v >> 32), o);
-  return ((u64)hi << 32) | lo;
-}
-__device__ __forceinline__ u64 umax64(u64 a, u64 b) { return a > b ? a : b; }
-
-// block-wide reductions for 256-thread blocks; result broadcast to all threads
-__device__ __forceinline__ float block_sum256(float v, float* s4) {
-  v = wave_sum(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) s4[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return ((s4[0] + s4[1]) + s4[2]) + s4[3];
-}
-__device__ __forceinline__ float block_max256(float v, float* s4) {
-  v = wave_max(v);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) s4[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return fmaxf(fmaxf(s4[0], s4[1]), fmaxf(s4[2], s4[3]));
-}
-
-// ------------------------------------------------- Philox4x32-10 + Gumbel
-// Counter-based generator of Salmon et al. (SC'11).  key = seed, counter =
-// (vocab index / 4, position, row, stream); word (vocab index % 4) of the block.
-__device__ __forceinline__ unsigned philox_word(unsigned k0, unsigned k1, unsigned stream, unsigned b,
-                                                unsigned t, unsigned v) {
-  unsigned c0 = v >> 2, c1 = t, c2 = b, c3 = stream;
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-    unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
-    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
-    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
-  }
-  unsigned sel = v & 3u;
-  return sel == 0 ? c0 : sel == 1 ? c1 : sel == 2 ? c2 : c3;
-}
-// u = ((word >> 9) + 0.5) * 2^-23 is exact in float32 and inside (0,1).
-__device__ __forceinline__ float gumbel_from_word(unsigned w) {
-  float u = ((float)(w >> 9) + 0.5f) * 1.1920928955078125e-07f;
-  return -logf(-logf(u));
-}
-// (value, index) -> one integer whose order is "larger value first, then smaller index"
-__device__ __forceinline__ u64 pack_key(float y, unsigned n) {
-  y = y + 0.0f;   // -0 -> +0
-  unsigned u = __float_as_uint(y);
-  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-  return ((u64)u << 32) | (u64)(0xFFFFFFFFu - n);
-}
-__device__ __forceinline__ int key_index(u64 k) { return (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull)); }
-
-__device__ __forceinline__ u64 sample_key(float logit, const SamplerArgs& sa, int b, int t, int n) {
-  float y = logit;
-  if (sa.inv_temperature > 0.0f)
-    y = logit * sa.inv_temperature + gumbel_from_word(philox_word(sa.seed_lo, sa.seed_hi, sa.stream, b, t, n));
-  return pack_key(y, (unsigned)n);
-}
 
 // ================================================================ packing
 // [N, K] row-major bf16 -> operand tiles (zero padded to 16 rows x 32 k).
@@ -278,10 +158,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int
   else act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, silu(v) * v2);
 }
 
-__device__ __forceinline__ f32x4 mfma_bf16(uint4 x, uint4 w, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8*>(&x), *reinterpret_cast<bf16x8*>(&w), c, 0,
-                                                 0, 0);
-}
 
 // bf16 GEMM on MFMA.  512 threads = 8 waves = (8/KW) column groups x KW-way split of K.
 // Each wave owns NTW column tiles (16 columns each) and MT row tiles (16 rows each):
