@@ -319,14 +319,11 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   if (max_rows <= 16) {
     int grid = a.n_tiles;                        // 1 column tile per workgroup, K split over 8 waves
     hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(grid), dim3(512), 0, s, a);
-  } else if (max_rows <= 32) {
-    hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
-  } else if (max_rows <= 64) {
-    int grid = (a.n_tiles + 1) / 2;              // 2 column groups x 4-way K split
-    hipLaunchKernelGGL((k_gemm_bf16<4, 1, 4, EPI>), dim3(grid), dim3(512), 0, s, a);
   } else {
-    int grid = (a.n_tiles + 3) / 4;              // 4 column groups x 2-way K split
-    hipLaunchKernelGGL((k_gemm_bf16<8, 1, 2, EPI>), dim3(grid), dim3(512), 0, s, a);
+    // More than 32 rows: the kernel walks the rows 32 at a time and streams the weights once per
+    // pass.  Wider row blocks per wave multiply the activation traffic from L2 (a 16 x 32 weight
+    // tile needs 2 KiB of activations per 16 rows) and measured far slower than re-streaming.
+    hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
   }
 }
 

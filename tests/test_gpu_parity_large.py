@@ -1,0 +1,270 @@
+"""GPU parity at the full sizes of configs 3, 4 and 5 (LLaMA-shaped pairs, bf16).
+
+The HIP path runs the whole batch; the oracle replays a sample of rows (rows are
+independent) on the GPU's committed history, decision by decision.  Properties that
+hold for every row at any size (accept rule, compaction, commit rule, counters) are
+checked on the full batch.  Run with -m gpu on an MI355X; the oracle legs need about
+130 GB of host memory (float64 copies of the 7B / 8B parameter sets)."""
+import os
+import sys
+import time
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+_T0 = time.time()
+
+
+def progress(msg):
+    """A line that survives pytest's capture: long legs must show that they are alive."""
+    line = f"[{time.time() - _T0:7.1f} s] {msg}\n"
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "test_progress.log"), "a") as f:
+            f.write(line)
+    except OSError:
+        pass
+    try:
+        sys.__stderr__.write(line)
+        sys.__stderr__.flush()
+    except Exception:
+        pass
+
+
+class Side:
+    """One workload on both sides; the oracle decoders may be shared between workloads."""
+
+    def __init__(self, cfg, weights, oracle_models):
+        from paper_2502_04557_amd import binding
+        self.cfg = cfg
+        self.b = binding
+        self.weights = weights
+        self.draft, self.target = oracle_models
+        self.gpu = binding.Sprinter(cfg)
+        self.gpu.load_weights(binding.DRAFT, weights[0])
+        self.gpu.load_weights(binding.TARGET, weights[1])
+        self.gpu.load_weights(binding.VERIFIER, weights[2])
+        self.prompts, self.plen = W.make_prompts(cfg)
+
+    def close(self):
+        self.gpu.close()
+
+
+def _oracle_models(cfg, weights):
+    from oracle import model as om
+    t = time.time()
+    d = om.Decoder(cfg.draft, weights[0])
+    tg = om.Decoder(cfg.target, weights[1])
+    progress(f"{cfg.name}: oracle float64 copies ready in {time.time() - t:.0f} s")
+    return d, tg
+
+
+def _whole_batch_properties(g, st, tau, vocab):
+    acc = g["accept"].astype(bool)
+    assert np.array_equal(g["accept"], (g["score"] >= np.float32(tau)).astype(np.uint8))
+    assert np.array_equal(g["tok"][acc], g["draft_tok"][acc])
+    assert np.array_equal(st["target_calls"], (~acc).sum(1))
+    assert st["sum_rejected"] == int((~acc).sum())
+    assert st["steps_with_target"] == int(((~acc).sum(0) > 0).sum())
+    assert (g["tok"] >= 0).all() and (g["tok"] < vocab).all()
+
+
+def _replay_segments(side, g, rows, settings):
+    """Oracle replay of the sampled rows on the GPU's committed history.  settings[step] =
+    (tau, b2): the threshold and the verifier's output bias in force at that step; consecutive
+    steps with the same setting are replayed in one oracle call, the caches carry over."""
+    from oracle import model as om, sprinter as osp
+    from parity_util import compare_replay
+    cfg = side.cfg
+    G = len(settings)
+    pr, pl = side.prompts[rows], side.plen[rows]
+    t = time.time()
+    dc = osp.prefill_whole_prompt(side.draft, pr, pl)
+    progress(f"{cfg.name}: oracle draft prefill of rows {rows} in {time.time() - t:.0f} s")
+    t = time.time()
+    tc = []
+    for i in range(len(rows)):       # row by row, with a progress line each
+        tc += osp.prefill_whole_prompt(side.target, pr[i:i + 1], pl[i:i + 1])
+        progress(f"{cfg.name}: oracle target prefill row {rows[i]} (P={int(pl[i])}) at {time.time() - t:.0f} s")
+    seqs = [list(map(int, pr[i][:pl[i]])) for i in range(len(rows))]
+    tot = dict(flag_flips_tolerated=0, draft_tok_flips_tolerated=0, target_tok_flips_tolerated=0, n=0,
+               max_score_diff=0.0, rejected=0)
+    g0 = 0
+    while g0 < G:
+        tau, b2 = settings[g0]
+        g1 = g0
+        while g1 < G and settings[g1] == (tau, b2):
+            g1 += 1
+        vw = dict(side.weights[2])
+        vw["v.b2"] = np.array([b2], np.float32)
+        P = max(len(q) for q in seqs)
+        prm = np.zeros((len(rows), P), np.int32)
+        for i, q in enumerate(seqs):
+            prm[i, :len(q)] = q
+        pln = np.array([len(q) for q in seqs], np.int32)
+        gs = {k: v[:, g0:g1] for k, v in g.items()}
+        forced = dict(tok=gs["tok"][rows], accept=gs["accept"][rows])
+        rec = osp.generate(side.draft, side.target, om.Verifier(vw), prm, pln, g1 - g0, tau, cfg.temperature, cfg.seed,
+                           forced=forced, rows=rows, draft_caches=dc, target_caches=tc)
+        rep = compare_replay(cfg, gs, rec, rows=rows, tau=tau)
+        for k in ("flag_flips_tolerated", "draft_tok_flips_tolerated", "target_tok_flips_tolerated", "n"):
+            tot[k] += rep[k]
+        tot["max_score_diff"] = max(tot["max_score_diff"], rep["max_score_diff"])
+        tot["rejected"] += int((forced["accept"] == 0).sum())
+        for i in range(len(rows)):
+            seqs[i] += [int(x) for x in gs["tok"][rows[i]]]
+        progress(f"{cfg.name}: oracle steps {g0}..{g1 - 1} tau {tau}: {rep}")
+        g0 = g1
+    progress(f"{cfg.name}: rows {rows} totals {tot}")
+    return tot
+
+
+def _logit(p):
+    return float(np.log(p) - np.log1p(-p))
+
+
+def _shifted_bias(scores, b2_in_force, tau, rho):
+    """Output bias that puts the rho-quantile of the verifier's pre-bias logit on logit(tau)."""
+    sc = np.asarray(scores, np.float64)
+    z_pre = np.log(sc) - np.log1p(-sc) - b2_in_force
+    return float(np.float32(_logit(tau) - np.quantile(z_pre, rho)))
+
+
+@pytest.fixture(scope="module")
+def llama7b():
+    """Weights of configs 3 and 4 (the same pair) and their oracle decoders."""
+    cfg = W.config("c3")
+    t = time.time()
+    weights = W.make_weights(cfg)
+    progress(f"c3/c4 weights generated in {time.time() - t:.0f} s")
+    models = _oracle_models(cfg, weights)
+    yield weights, models
+    del weights, models
+
+
+def test_c3_full_size_sampled_rows(llama7b):
+    """Config 3: batch 32, 256-token Zipf prompts, 2-layer draft / 32-layer d=4096 target.
+    Eight steps with the workload's own verifier (which rejects about 1 % at this size), then
+    eight with its output bias shifted to a 40 % reject rate so that the target path is
+    exercised on the sampled rows too."""
+    weights, models = llama7b
+    cfg = replace(W.config("c3"), max_seq=320)
+    s = Side(cfg, weights, models)
+    n1, n2 = 8, 8
+    t = time.time()
+    s.gpu.prefill(s.prompts, s.plen)
+    b2_0 = float(weights[2]["v.b2"][0])
+    o1 = {k: v.cpu().numpy() for k, v in s.gpu.generate(n1).items()}
+    b2 = _shifted_bias(o1["score"], b2_0, cfg.tau, 0.40)
+    vw = dict(weights[2])
+    vw["v.b2"] = np.array([b2], np.float32)
+    s.gpu.load_weights(s.b.VERIFIER, vw)
+    o2 = {k: v.cpu().numpy() for k, v in s.gpu.generate(n2).items()}
+    g = {k: np.concatenate([o1[k], o2[k]], 1) for k in o1}
+    st = s.gpu.stats()
+    progress(f"c3: GPU prefill + {n1 + n2} steps in {time.time() - t:.0f} s, reject rates "
+             f"{1 - o1['accept'].mean():.3f} then {1 - o2['accept'].mean():.3f}")
+    _whole_batch_properties(g, st, cfg.tau, cfg.draft.vocab)
+    assert 0.2 < 1 - o2["accept"].mean() < 0.6
+    rng = np.random.default_rng(3)
+    rows = sorted({0, cfg.batch - 1, int(rng.integers(1, cfg.batch - 1))})
+    tot = _replay_segments(s, g, rows, [(cfg.tau, b2_0)] * n1 + [(cfg.tau, b2)] * n2)
+    assert tot["rejected"] > 0
+    s.close()
+
+
+def test_c4_compaction_and_ragged_target(llama7b):
+    """Config 4: batch 128, per-row prompt lengths in [64, 1024]; the verifier's output bias is
+    shifted so that the reject rate runs near 5 %, 25 % and 60 % at thresholds 0.3, 0.5, 0.7.
+    Per step: the rejected-row list equals the brute-force list of cleared flags (ascending),
+    its length is R; the oracle replays three rows (shortest prompt, median, one seeded) over
+    the whole sweep with the same shifted verifiers."""
+    import torch
+    weights, models = llama7b
+    base = W.config("c4")
+    n_cal, n_seg = 8, 4
+    combos = [(tau, rho) for tau in (0.3, 0.5, 0.7) for rho in (0.05, 0.25, 0.60)]
+    G = n_cal + n_seg * len(combos)
+    cfg = replace(base, max_seq=base.prompt_len + G + 2)
+    s = Side(cfg, weights, models)
+    B = cfg.batch
+    assert s.plen.min() >= 64 and s.plen.max() <= 1024 and len(set(s.plen.tolist())) > 64
+    t = time.time()
+    s.gpu.prefill(s.prompts, s.plen)
+    torch.cuda.synchronize()
+    progress(f"c4: GPU prefill of {B} ragged rows (max {int(s.plen.max())}) in {time.time() - t:.0f} s")
+
+    b2_0 = float(weights[2]["v.b2"][0])
+    steps = []          # per step: dict of host arrays
+    settings = []       # per step: (tau, b2)
+
+    def run_steps(n, tau, b2):
+        for _ in range(n):
+            o = s.gpu.step()
+            steps.append({k: v.cpu().numpy() for k, v in o.items()})
+            settings.append((tau, b2))
+
+    run_steps(n_cal, cfg.tau, b2_0)
+    cal_scores = np.stack([x["score"] for x in steps], 1)
+    achieved = []
+    for tau, rho in combos:
+        b2 = _shifted_bias(cal_scores, b2_0, tau, rho)
+        vw = dict(weights[2])
+        vw["v.b2"] = np.array([b2], np.float32)
+        s.gpu.load_weights(s.b.VERIFIER, vw)
+        s.gpu.set_tau(tau)
+        n0 = len(steps)
+        run_steps(n_seg, tau, b2)
+        rate = 1.0 - np.mean([x["accept"].mean() for x in steps[n0:]])
+        achieved.append(rate)
+        progress(f"c4: tau {tau} target reject rate {rho:.2f} achieved {rate:.3f} "
+                 f"(R per step {[int(x['n_rej'][0]) for x in steps[n0:]]})")
+        assert abs(rate - rho) < 0.12
+    st = s.gpu.stats()
+    # compaction on the whole batch, every step
+    for x, (tau, _) in zip(steps, settings):
+        rej = np.flatnonzero(x["accept"] == 0)
+        R = int(x["n_rej"][0])
+        assert R == len(rej) and np.array_equal(x["rej_idx"][:R], rej)
+        assert np.array_equal(x["accept"], (x["score"] >= np.float32(tau)).astype(np.uint8))
+        acc = x["accept"].astype(bool)
+        assert np.array_equal(x["committed_tok"][acc], x["draft_tok"][acc])
+    g = {k: np.stack([x[k2] for x in steps], 1) for k, k2 in
+         (("tok", "committed_tok"), ("accept", "accept"), ("score", "score"), ("draft_tok", "draft_tok"))}
+    assert np.array_equal(st["target_calls"], (g["accept"] == 0).sum(1))
+    assert st["steps"] == G and st["sum_rejected"] == int((g["accept"] == 0).sum())
+    order = np.argsort(s.plen, kind="stable")
+    rng = np.random.default_rng(4)
+    rows = sorted({int(order[0]), int(order[B // 2]), int(rng.choice(order[: B // 2]))})
+    tot = _replay_segments(s, g, rows, settings)
+    assert tot["rejected"] > 0
+    progress(f"c4: achieved reject rates {np.round(achieved, 3).tolist()}")
+    s.close()
+
+
+def test_c5_full_size_sampled_rows():
+    """Config 5: batch 64, 1024-token prompts, grouped-query attention (32 query / 8 KV heads),
+    vocabulary 128256, both KV caches resident."""
+    base = W.config("c5")
+    G = 6
+    cfg = replace(base, max_seq=base.prompt_len + G + 2)
+    t = time.time()
+    weights = W.make_weights(cfg)
+    progress(f"c5 weights generated in {time.time() - t:.0f} s")
+    models = _oracle_models(cfg, weights)
+    s = Side(cfg, weights, models)
+    t = time.time()
+    s.gpu.prefill(s.prompts, s.plen)
+    o = s.gpu.generate(G)
+    g = {k: v.cpu().numpy() for k, v in o.items()}
+    st = s.gpu.stats()
+    progress(f"c5: GPU prefill + {G} steps in {time.time() - t:.0f} s, reject rate {1 - g['accept'].mean():.3f}")
+    _whole_batch_properties(g, st, cfg.tau, cfg.draft.vocab)
+    tot = _replay_segments(s, g, [0, cfg.batch - 1], [(cfg.tau, float(weights[2]["v.b2"][0]))] * G)
+    assert tot["rejected"] > 0
+    s.close()
