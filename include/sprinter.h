@@ -182,9 +182,11 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
 /* For tuning tools and other callers that want a time breakdown (no paper passage: a
  * diagnostic).  With the environment variable SPRINTER_PHASE_TICKS=1 set at create time,
  * workgroup 0 of the persistent decode kernel accumulates 100 MHz clock ticks per phase
- * type; this call waits for the stream and copies 32 words to host_out: [0..15] ticks of
- * embed, norm, QKV, attention, O-proj, FFN-up, FFN-down, LM head, verifier, decide, finish,
- * barrier wait, per-step fence; [16..31] the matching event counts.  All zero when off. */
+ * type; this call waits for the stream and copies 128 words to host_out: [0..63] tick sums
+ * ([0..12]: embed, norm, QKV, attention, O-proj, FFN-up, FFN-down, LM head, verifier,
+ * decide, finish, barrier wait, per-step fence as seen by wave 0; [13..14] wave 0 waiting
+ * for partial sums / running epilogues; [16..47] the timeline of one compute wave inside the
+ * four GEMM kinds), [64..127] the matching event counts.  All zero when off. */
 int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out);
 
 void sprinter_destroy(sprinter_ctx* ctx);

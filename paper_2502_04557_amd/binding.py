@@ -209,11 +209,15 @@ class Sprinter:
         self._check(self.lib.sprinter_set_tau(self.ctx, tau), self.ctx)
 
     def phase_ticks(self) -> dict:
-        buf = (C.c_uint64 * 32)()
+        """Tick counters of the persistent kernels (see sprinter_debug_phase_ticks): name -> (microseconds, events)."""
+        buf = (C.c_uint64 * 128)()
         self._check(self.lib.sprinter_debug_phase_ticks(self.ctx, buf), self.ctx)
-        names = ("embed", "norm", "qkv", "attn", "oproj", "ffn1", "ffn2", "lmhead", "verifier", "decide", "finish",
-                 "barrier", "fence", "g_prep", "g_mma", "st_ack")
-        return {n: (buf[i] / 100.0, int(buf[16 + i])) for i, n in enumerate(names)}   # (microseconds, events)
+        names = ["embed", "norm", "qkv", "attn", "oproj", "ffn1", "ffn2", "lmhead", "verifier", "decide", "finish",
+                 "barrier", "fence", "w0_wait_partials", "w0_epilogue", "w0_15"]
+        for kind in ("qkv", "oproj", "ffn1", "ffn2"):
+            names += [f"c_{kind}_{x}" for x in ("barrier", "stats", "operands", "mfma", "prefetch", "sync", "6", "7")]
+        names += [f"slot{i}" for i in range(len(names), 64)]
+        return {n: (buf[i] / 100.0, int(buf[64 + i])) for i, n in enumerate(names)}
 
     def stats(self) -> dict:
         st = StatsC()

@@ -7,7 +7,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsprinter.so")
-SOURCES = ["kernels.hip", "mega.hip", "abi.cpp"]
+SOURCES = ["kernels.hip", "mega.hip", "mega16.hip", "abi.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are kept off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -80,6 +80,7 @@ struct sprinter_ctx {
   bool mega_on = false, mega_built = false;
   int mega_mt = 1, mega_grid = 0;
   size_t mega_smem = 0;
+  int mega_tab_bytes = 0;
   MegaParams mega_host;
   MegaParams* mega_dev = nullptr;
   LayerW *mega_layers_q = nullptr, *mega_layers_p = nullptr;
@@ -310,7 +311,7 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
     mp.sync = (unsigned*)bump.take(65536);
     mp.epoch = (unsigned*)bump.take(256);
     mp.err = (int*)bump.take(256);
-    mp.prof = (unsigned long long*)bump.take(256);
+    mp.prof = (unsigned long long*)bump.take(1024);
     mp_dev = (MegaParams*)bump.take(sizeof(MegaParams));
   }
   size_t total = (bump.off + 255) & ~(size_t)255;
@@ -460,6 +461,8 @@ int build_mega(sprinter_ctx* ctx) {
       }
       ph.push_back(norm_phase(h_prev, (const float*)m->normf_g, (const float*)m->normf_b, mm.hfn, mm.hf));
       ph.push_back(blank(PK_LMHEAD));
+      if (ctx->mega_mt == 1 && (int)ph.size() != mm.n_phases)
+        return fail(ctx, SPRINTER_E_STATE, "phase list of %d entries, expected %d", (int)ph.size(), mm.n_phases);
       mm.n_phases = (int)ph.size();
       if (hipMemcpyAsync((void*)mm.phases, ph.data(), ph.size() * sizeof(PhaseDesc), hipMemcpyHostToDevice, ctx->stream) !=
           hipSuccess)
@@ -495,7 +498,9 @@ int enqueue_mega(sprinter_ctx* ctx, const sprinter_step_out* out, int n_steps, i
     o.o_target_logits = out->target_logits; o.o_target_hidden = out->target_hidden;
   }
   o.g_tok = g_tok; o.g_draft_tok = g_draft_tok; o.g_accept = g_accept; o.g_score = g_score;
-  hipError_t e = launch_mega(ctx->mega_dev, ctx->mega_mt, n_steps, o, ctx->mega_smem, ctx->mega_grid, ctx->stream);
+  hipError_t e = ctx->mega_mt == 1
+                     ? launch_mega16(ctx->mega_dev, n_steps, o, ctx->mega_smem, ctx->mega_tab_bytes, ctx->mega_grid, ctx->stream)
+                     : launch_mega(ctx->mega_dev, ctx->mega_mt, n_steps, o, ctx->mega_smem, ctx->mega_grid, ctx->stream);
   if (e != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "cooperative launch failed: %s", hipGetErrorString(e));
   return SPRINTER_OK;
 }
@@ -612,7 +617,7 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     launch_fill_zero(ctx->mega_host.sync, 65536, ctx->stream);
     launch_fill_zero(ctx->mega_host.epoch, 256, ctx->stream);
     launch_fill_zero(ctx->mega_host.err, 256, ctx->stream);
-    launch_fill_zero(ctx->mega_host.prof, 256, ctx->stream);
+    launch_fill_zero(ctx->mega_host.prof, 1024, ctx->stream);
     ctx->mega_prof = ctx->mega_host.prof;
     {
       const char* pp = getenv("SPRINTER_PHASE_TICKS");
@@ -625,9 +630,17 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
       ctx->mega_mt = rows <= 16 ? 1 : rows <= 32 ? 2 : rows <= 64 ? 4 : 8;
       MegaParams& hp = ctx->mega_host;
       hp.max_seq = cfg->max_seq; hp.max_batch = cfg->max_batch; hp.rows_alloc = rows;
-      ctx->mega_smem = mega_smem_bytes(hp, ctx->mega_mt);
       int grid = 0;
-      hipError_t e = ctx->mega_smem <= 160 * 1024 ? mega_prepare(ctx->mega_mt, ctx->mega_smem, &grid) : hipErrorInvalidValue;
+      hipError_t e;
+      if (ctx->mega_mt == 1) {
+        hp.draft.n_phases = 5 * hp.draft.md.n_layer + 3;     // embed, 5 per layer, final norm, LM head
+        hp.target.n_phases = 5 * hp.target.md.n_layer + 3;
+        ctx->mega_smem = mega16_smem_bytes(hp, &ctx->mega_tab_bytes);
+        e = ctx->mega_smem <= 160 * 1024 ? mega16_prepare(ctx->mega_smem, &grid) : hipErrorInvalidValue;
+      } else {
+        ctx->mega_smem = mega_smem_bytes(hp, ctx->mega_mt);
+        e = ctx->mega_smem <= 160 * 1024 ? mega_prepare(ctx->mega_mt, ctx->mega_smem, &grid) : hipErrorInvalidValue;
+      }
       int dev = 0, coop = 0;
       (void)hipGetDevice(&dev);
       (void)hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev);
@@ -696,6 +709,7 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
   if (which == SPRINTER_DRAFT) ctx->draft.loaded = true;
   else if (which == SPRINTER_TARGET) ctx->target.loaded = true;
   else ctx->v_loaded = true;
+  ctx->mega_built = false;     // the persistent kernel's tables hold the weight pointers
   return hip_status(ctx, "sprinter_load_weights");
 }
 
@@ -740,6 +754,8 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
   if (rc) return rc;
   rc = check_room(ctx, 1);
   if (rc) return rc;
+  rc = build_mega(ctx);
+  if (rc) return rc;
   if (ctx->mega_on) {
     rc = enqueue_mega(ctx, out, 1, 0, nullptr, nullptr, nullptr, nullptr);
     if (rc) return rc;
@@ -757,6 +773,8 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
   int rc = check_ready(ctx);
   if (rc) return rc;
   rc = check_room(ctx, n_tokens);
+  if (rc) return rc;
+  rc = build_mega(ctx);
   if (rc) return rc;
   launch_reset_gen_idx(ctx->st.counters, ctx->stream);
   if (ctx->mega_on) {
@@ -808,10 +826,10 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
 
 int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out) {
   if (!ctx || !host_out) return fail(ctx, SPRINTER_E_NULL, "sprinter_debug_phase_ticks: NULL argument");
-  for (int i = 0; i < 32; ++i) host_out[i] = 0;
+  for (int i = 0; i < 128; ++i) host_out[i] = 0;
   if (!ctx->mega_prof) return SPRINTER_OK;
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
-  if (hipMemcpy(host_out, ctx->mega_prof, 256, hipMemcpyDeviceToHost) != hipSuccess)
+  if (hipMemcpy(host_out, ctx->mega_prof, 1024, hipMemcpyDeviceToHost) != hipSuccess)
     return fail(ctx, SPRINTER_E_HIP, "copy of the tick counters failed");
   return SPRINTER_OK;
 }

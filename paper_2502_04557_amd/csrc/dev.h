@@ -49,11 +49,28 @@ template <> __device__ __forceinline__ void act_store<bf16_t>(bf16_t* base, size
   base[plane + i] = f2bf(v - bf2f(hi));
 }
 
+// Two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even), and the hi + lo split of a pair.
+typedef float f2v __attribute__((ext_vector_type(2)));
+typedef __bf16 b2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pk_bf16(float a, float b) {
+  f2v v = {a, b};
+  b2v h = __builtin_convertvector(v, b2v);   // v_cvt_pk_bf16_f32, round to nearest even
+  return __builtin_bit_cast(unsigned, h);
+}
+__device__ __forceinline__ void split2(float a, float b, unsigned& hi, unsigned& lo) {
+  hi = pk_bf16(a, b);
+  lo = pk_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float c = 0.7978845608028654f;   // sqrt(2/pi)
   return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
 }
 __device__ __forceinline__ float silu(float x) { return x / (1.0f + expf(-x)); }
+
+// The wave's index inside its workgroup as a scalar.  Conditions built from it are then scalar too,
+// so the compiler branches around matrix instructions instead of masking them with EXEC: the MFMA
+// instructions ignore the EXEC mask and would run (on stale registers) inside a masked-off block.
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // ------------------------------------------------------------- reductions
 __device__ __forceinline__ float wave_sum(float v) {

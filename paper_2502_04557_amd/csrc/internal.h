@@ -219,5 +219,10 @@ size_t mega_smem_bytes(const MegaParams& hp, int MT);
 hipError_t launch_mega(const MegaParams* dev_params, int MT, int n_steps, const MegaOut& out, size_t smem, int grid,
                        hipStream_t s);
 hipError_t mega_prepare(int MT, size_t smem, int* max_grid);
+// the variant for at most 16 rows (mega16.hip); needs draft.n_phases / target.n_phases set
+size_t mega16_smem_bytes(const MegaParams& hp, int* tab_bytes);
+hipError_t mega16_prepare(size_t smem, int* max_grid);
+hipError_t launch_mega16(const MegaParams* dev_params, int n_steps, const MegaOut& out, size_t smem, int tab_bytes, int grid,
+                         hipStream_t s);
 
 }  // namespace sprinter

@@ -6,6 +6,7 @@
 //   scatter back.  Every kernel reads the number of active rows from device
 //   memory, so the host never learns how many rows were rejected.
 #include "dev.h"
+#include <cstring>
 
 namespace sprinter {
 
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
   __shared__ float red[(KW > 1) ? (KW - 1) * NW * NI2 * 64 : 1];
   const int n_rows = *a.n_rows;
   if (n_rows <= 0) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = wave_index();
   const int kw = w % KW, ng = w / KW;
   const int nt0 = (blockIdx.x * NW + ng) * NTW;
   const uint4* __restrict__ Wp = (const uint4*)a.W;
@@ -281,7 +282,7 @@ template <int EPI>
 __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
   constexpr bool DUAL = (EPI == EPI_SWIGLU);
   const int n_rows = *a.n_rows;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = wave_index();
   const int n = blockIdx.x * 4 + w;
   if (n >= a.N || n_rows <= 0) return;
   const int K = a.K;
@@ -315,22 +316,23 @@ __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
 
 template <int EPI>
 static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
-  // (row tiles, column tiles per wave, K split) chosen from the launch-time row maximum
-  if (max_rows <= 16) {
-    int grid = a.n_tiles;                        // 1 column tile per workgroup, K split over 8 waves
-    hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(grid), dim3(512), 0, s, a);
-  } else {
-    // More than 32 rows: the kernel walks the rows 32 at a time and streams the weights once per
-    // pass.  Wider row blocks per wave multiply the activation traffic from L2 (a 16 x 32 weight
-    // tile needs 2 KiB of activations per 16 rows) and measured far slower than re-streaming.
-    hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
-  }
+  // One 16-column tile per workgroup, K split over its 8 waves.  Up to 16 rows: one row tile.  More: the
+  // kernel walks the rows 32 at a time and streams the weights once per pass; wider row blocks per wave
+  // multiply the activation traffic from L2 (a 16 x 32 weight tile needs 2 KiB of activations per 16 rows)
+  // and measured far slower than re-streaming.
+  // (Measured and dropped for the 16-row case: folding the layer norm into this kernel - every workgroup
+  // then normalises the whole activation matrix again, 13.6 us against 5.3 + 5.0 us for norm + GEMM at
+  // d = 1600 - and splitting K over workgroups for narrow outputs - the two device-scope fences of the
+  // last-arriver reduction cost more than the 4 us they save.)
+  if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
 }
 
 void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane, const int* n_rows,
                  int N, int K, const float* bias, float* out_f32, int ldo, void* out_act, int out_K, size_t out_plane,
                  int max_rows, hipStream_t s) {
   GemmArgs a;
+  memset(&a, 0, sizeof a);
   a.x_plane = x_plane; a.out_plane = out_plane;
   a.W = W; a.W2 = W2; a.X = X; a.n_rows = n_rows; a.N = N; a.K = K;
   a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16;
@@ -552,7 +554,7 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
   __shared__ u64 sbest[8][MT * 16];
   const int n_rows = *a.rd.n_rows;
   if (n_rows <= 0) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = wave_index();
   const int tpw = (a.n_tiles + gridDim.x - 1) / gridDim.x;
   const int t0 = blockIdx.x * tpw, t1 = min(t0 + tpw, a.n_tiles);
   const uint4* __restrict__ Wp = (const uint4*)a.W;
@@ -637,7 +639,7 @@ __global__ __launch_bounds__(256) void k_lmhead_f32(LmArgs a) {
   __shared__ u64 sbest[4][8];
   const int n_rows = *a.rd.n_rows;
   if (n_rows <= 0) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = wave_index();
   const int cpw = (a.V + gridDim.x - 1) / gridDim.x;
   const int c0 = blockIdx.x * cpw, c1 = min(c0 + cpw, a.V);
   const int K = a.K;
@@ -717,7 +719,7 @@ __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__
                                                        float* __restrict__ part, int max_rows) {
   extern __shared__ float contrib[];   // [8][max_rows]
   const int n_rows = *n_rows_p;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = wave_index();
   if (d_hidden == 0) {
     for (int m = w; m < n_rows; m += 8) {
       float acc = 0.f;

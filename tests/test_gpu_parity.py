@@ -31,6 +31,19 @@ def test_c1_free_run_is_identical():
     p.close()
 
 
+@pytest.fixture
+def persistent_kernel(monkeypatch):
+    """Contexts created inside the test use the persistent cooperative decode kernel (bf16 only)."""
+    monkeypatch.setenv("SPRINTER_PERSISTENT", "1")
+
+
+@pytest.mark.parametrize("kind", ["gpt", "llama", "linear"])
+def test_mini_step_by_step_persistent_kernel(kind, persistent_kernel):
+    """The same step-by-step parity with the opt-in persistent kernel: mini-gpt and mini-linear take
+    the variant for at most 16 rows, mini-llama (19 rows) the general one."""
+    test_mini_step_by_step(kind, W.DT_BF16)
+
+
 @pytest.mark.parametrize("kind,dtype", [("gpt", W.DT_F32), ("llama", W.DT_F32), ("linear", W.DT_F32),
                                         ("gpt", W.DT_BF16), ("llama", W.DT_BF16), ("linear", W.DT_BF16)])
 def test_mini_step_by_step(kind, dtype):
@@ -161,6 +174,11 @@ def test_single_token_prompt_and_full_batch():
     rec = p.oracle(6, forced=dict(tok=g["tok"], accept=g["accept"]))
     print(compare_replay(cfg, g, rec))
     p.close()
+
+
+def test_c2_persistent_kernel_sampled_rows(persistent_kernel):
+    """Config 2 at full size through the opt-in persistent kernel."""
+    test_c2_full_size_sampled_rows()
 
 
 def test_c2_full_size_sampled_rows():
