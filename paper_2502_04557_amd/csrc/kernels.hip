@@ -7,6 +7,7 @@
 //   memory, so the host never learns how many rows were rejected.
 #include "dev.h"
 #include <cstring>
+#include <cstdlib>
 
 namespace sprinter {
 
@@ -149,12 +150,12 @@ struct GemmArgs {
   size_t out_plane;   // same for out_act
 };
 
+// bias: the column's bias (0 if none); res: the current value of the output element (residual epilogue only)
 template <int EPI, typename AT>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int m, int n, float v, float v2) {
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int m, int n, float v, float v2, float bias, float res) {
   if (m >= n_rows || n >= a.N) return;
-  float bias = a.bias ? a.bias[n] : 0.f;
   if (EPI == EPI_F32) a.out_f32[(size_t)m * a.ldo + n] = v + bias;
-  else if (EPI == EPI_RESID) a.out_f32[(size_t)m * a.ldo + n] += v + bias;
+  else if (EPI == EPI_RESID) a.out_f32[(size_t)m * a.ldo + n] = res + (v + bias);
   else if (EPI == EPI_GELU) act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, gelu_tanh(v + bias));
   else act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, silu(v) * v2);
 }
@@ -171,8 +172,6 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
   constexpr int NI2 = NI * (DUAL ? 2 : 1);
   // partial accumulators of the waves with kw > 0, handed to the kw == 0 wave of their column group
   __shared__ float red[(KW > 1) ? (KW - 1) * NW * NI2 * 64 : 1];
-  const int n_rows = *a.n_rows;
-  if (n_rows <= 0) return;
   const int lane = threadIdx.x & 63, w = wave_index();
   const int kw = w % KW, ng = w / KW;
   const int nt0 = (blockIdx.x * NW + ng) * NTW;
@@ -181,6 +180,38 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
   const uint4* __restrict__ Xp = (const uint4*)a.X;
   const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   const int Kt = a.Kt;
+  constexpr int U = 4;
+  // Requests that depend on nothing are issued before the row count is even read: this wave's first
+  // weight tiles and, in the wave that finishes the tile, the bias and (residual epilogue) the current
+  // output values of the first row block.  That takes three memory latencies off the kernel's chain.
+  uint4 wv[U][NTW], wv2[U][DUAL ? NTW : 1];
+  auto load_weights = [&](int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int kc = min(kt + u * KW, Kt - 1);                    // clamped: always a valid tile
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) {
+        int nt = min(nt0 + j, a.n_tiles - 1);
+        wv[u][j] = Wp[((size_t)nt * Kt + kc) * 64 + lane];
+        if (DUAL) wv2[u][j] = W2p[((size_t)nt * Kt + kc) * 64 + lane];
+      }
+    }
+  };
+  load_weights(min(kw, Kt - 1));
+  float pbias[NTW], pres[NTW][MT][4];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    const int n = (nt0 + j) * 16 + (lane & 15);
+    const bool n_ok = kw == 0 && nt0 + j < a.n_tiles && n < a.N;
+    pbias[j] = (n_ok && a.bias) ? a.bias[n] : 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        pres[j][mt][v] = (EPI == EPI_RESID && n_ok) ? a.out_f32[(size_t)(mt * 16 + (lane >> 4) * 4 + v) * a.ldo + n] : 0.f;
+  }
+  const int n_rows = *a.n_rows;
+  if (n_rows <= 0) return;
   for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
     const int mt_act = min(MT, (n_rows - m0 + 15) >> 4);
     const int mtile0 = m0 >> 4;
@@ -192,19 +223,8 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
         acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
         if (DUAL) acc2[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
-    constexpr int U = 4;
     for (int kt = kw; kt < Kt; kt += KW * U) {
-      uint4 wv[U][NTW], wv2[U][DUAL ? NTW : 1];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int kc = min(kt + u * KW, Kt - 1);                    // clamped: always a valid tile
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) {
-          int nt = min(nt0 + j, a.n_tiles - 1);
-          wv[u][j] = Wp[((size_t)nt * Kt + kc) * 64 + lane];
-          if (DUAL) wv2[u][j] = W2p[((size_t)nt * Kt + kc) * 64 + lane];
-        }
-      }
+      if (kt != kw || m0 != 0) load_weights(kt);            // the first chunk is already on its way
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         int kc = kt + u * KW;
@@ -268,9 +288,12 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
         for (int mt = 0; mt < MT; ++mt)
           if (mt < mt_act && nt0 + j < a.n_tiles) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-              gemm_epilogue<EPI, bf16_t>(a, n_rows, m0 + mt * 16 + (lane >> 4) * 4 + v, (nt0 + j) * 16 + (lane & 15),
-                                         acc[j][mt][v], DUAL ? acc2[j][mt][v] : 0.f);
+            for (int v = 0; v < 4; ++v) {
+              const int m = m0 + mt * 16 + (lane >> 4) * 4 + v, n = (nt0 + j) * 16 + (lane & 15);
+              float res = pres[j][mt][v];
+              if (EPI == EPI_RESID && m0 != 0 && m < n_rows && n < a.N) res = a.out_f32[(size_t)m * a.ldo + n];
+              gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, acc[j][mt][v], DUAL ? acc2[j][mt][v] : 0.f, pbias[j], res);
+            }
           }
     }
     if (KW > 1) __syncthreads();
@@ -309,7 +332,9 @@ __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
     for (int i = 0; i < 8; ++i) {
       float s1 = wave_sum(acc[i]);
       float s2 = DUAL ? wave_sum(acc2[i]) : 0.f;
-      if (lane == i) gemm_epilogue<EPI, float>(a, n_rows, m0 + i, n, s1, s2);
+      if (lane == i && m0 + i < n_rows)
+        gemm_epilogue<EPI, float>(a, n_rows, m0 + i, n, s1, s2, a.bias ? a.bias[n] : 0.f,
+                                  EPI == EPI_RESID ? a.out_f32[(size_t)(m0 + i) * a.ldo + n] : 0.f);
     }
   }
 }
@@ -507,8 +532,185 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
   }
 }
 
+// bf16 single-query attention with a short dependency chain: one workgroup (4 waves) per (row, KV head).
+// Once the row's cache slot is known, every wave requests its share of the cached keys AND values
+// at once (they do not depend on the new query), then the query / new key / new value; each lane
+// group runs an online softmax over its own keys, the groups are merged by shuffles, the 4 waves
+// and the new key by one pass through LDS: a single block-wide synchronisation.
+//   lane = kin * LPK + chunk: LPK = DH / 8 lanes share one key (8 elements each), a wave-wide
+//   16-byte load covers KPW = 64 / LPK consecutive keys; wave w takes key blocks w, w + 4, ...
+template <int DH, int G>
+__global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
+  constexpr int LPK = DH / 8, KPW = 64 / LPK, HALF = DH / 2;
+  constexpr int NB = G <= 2 ? 16 : (G <= 4 ? 8 : 4);      // key blocks held in registers per round and wave
+  constexpr float NEG = -1e30f;
+  __shared__ float s_m[4][G], s_l[4][G], s_o[4][G][DH], s_vnew[DH], s_snew[G];
+  const int r = blockIdx.y;
+  if (r >= *a.rd.n_rows) return;
+  const int kvh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
+  const int chunk = lane % LPK, kin = lane / LPK;
+  const int b = a.rd.b[r], slot = a.rd.slot[r], S = a.max_seq;
+  bf16_t* __restrict__ Kc = (bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+  bf16_t* __restrict__ Vc = (bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+  const int n_blocks = (slot + KPW - 1) / KPW;                 // blocks of cached keys
+  const int n_rounds = (n_blocks + 4 * NB - 1) / (4 * NB);
+  uint4 kb[NB], vb[NB];
+  auto request = [&](int rd) {                                 // clamped addresses, no branches
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int key = min(((rd * NB + j) * 4 + w) * KPW + kin, max(slot - 1, 0));
+      kb[j] = *reinterpret_cast<const uint4*>(Kc + (size_t)key * DH + chunk * 8);
+      vb[j] = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * 8);
+    }
+  };
+  request(0);
+  // query heads, new key and new value: this lane's 8 elements (and their rotary partners)
+  const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
+  const float* __restrict__ cs = a.rope + (size_t)r * DH;
+  float cr[8], sr[8];
+  if (a.use_rope) {
+    const int j0 = (chunk % (LPK / 2)) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { cr[e] = cs[2 * (j0 + e)]; sr[e] = cs[2 * (j0 + e) + 1]; }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { cr[e] = 1.f; sr[e] = 0.f; }
+  }
+  const bool upper = chunk >= LPK / 2;
+  const int pchunk = chunk ^ (LPK / 2);
+  auto rotated = [&](const float* v, float* out) {            // v: one head's DH values
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float x = v[chunk * 8 + e], xp = a.use_rope ? v[pchunk * 8 + e] : 0.f;
+      out[e] = upper ? x * cr[e] + xp * sr[e] : x * cr[e] - xp * sr[e];
+    }
+  };
+  float q[G][8], knew[8], vnew[8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    rotated(y + (size_t)(kvh * G + g) * DH, q[g]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q[g][e] *= a.scale;
+  }
+  rotated(y + (size_t)(a.H + kvh) * DH, knew);
+  unsigned kpk[4], vpk[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float v0 = y[(size_t)(a.H + a.KVH + kvh) * DH + chunk * 8 + 2 * e], v1 = y[(size_t)(a.H + a.KVH + kvh) * DH + chunk * 8 + 2 * e + 1];
+    const bf16_t k0 = f2bf(knew[2 * e]), k1 = f2bf(knew[2 * e + 1]), w0 = f2bf(v0), w1 = f2bf(v1);
+    kpk[e] = (unsigned)k0 | ((unsigned)k1 << 16);
+    vpk[e] = (unsigned)w0 | ((unsigned)w1 << 16);
+    knew[2 * e] = bf2f(k0); knew[2 * e + 1] = bf2f(k1);         // the entry as later steps will read it back
+    vnew[2 * e] = bf2f(w0); vnew[2 * e + 1] = bf2f(w1);
+  }
+  if (w == 0 && kin == 0) {                                     // append to the cache
+    *reinterpret_cast<uint4*>(Kc + (size_t)slot * DH + chunk * 8) = make_uint4(kpk[0], kpk[1], kpk[2], kpk[3]);
+    *reinterpret_cast<uint4*>(Vc + (size_t)slot * DH + chunk * 8) = make_uint4(vpk[0], vpk[1], vpk[2], vpk[3]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s_vnew[chunk * 8 + e] = vnew[e];
+  }
+  float snew[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float p = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p += q[g][e] * knew[e];
+#pragma unroll
+    for (int o = 1; o < LPK; o <<= 1) p += __shfl_xor(p, o);
+    snew[g] = p;
+  }
+  if (w == 0 && lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) s_snew[g] = snew[g];
+  }
+  // online softmax over this lane group's keys
+  float m[G], l[G], acc[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = NEG; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  }
+  for (int rd = 0; rd < n_rounds; ++rd) {
+    if (rd > 0) request(rd);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int key = ((rd * NB + j) * 4 + w) * KPW + kin;
+      const bool valid = key < slot;
+      const bf16_t* kt = reinterpret_cast<const bf16_t*>(&kb[j]);
+      const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vb[j]);
+      float kf[8], vf[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { kf[e] = bf2f(kt[e]); vf[e] = valid ? bf2f(vt[e]) : 0.f; }   // (an empty cache holds no finite data yet)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float sc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sc += q[g][e] * kf[e];
+#pragma unroll
+        for (int o = 1; o < LPK; o <<= 1) sc += __shfl_xor(sc, o);
+        const float mn = valid ? fmaxf(m[g], sc) : m[g];
+        const float corr = __expf(m[g] - mn);
+        const float p = valid ? __expf(sc - mn) : 0.f;
+        m[g] = mn;
+        l[g] = l[g] * corr + p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vf[e];
+      }
+    }
+  }
+  // merge the KPW lane groups of the wave
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int o = LPK; o < 64; o <<= 1) {
+      const float mo = __shfl_xor(m[g], o), lo = __shfl_xor(l[g], o);
+      const float mn = fmaxf(m[g], mo);
+      const float c1 = __expf(m[g] - mn), c2 = __expf(mo - mn);
+      l[g] = l[g] * c1 + lo * c2;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * c1 + __shfl_xor(acc[g][e], o) * c2;
+      m[g] = mn;
+    }
+    if (kin == 0) {
+      if (chunk == 0) { s_m[w][g] = m[g]; s_l[w][g] = l[g]; }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s_o[w][g][chunk * 8 + e] = acc[g][e];
+    }
+  }
+  __syncthreads();
+  // merge the 4 waves and the new key; one output element per thread and pass
+  bf16_t* __restrict__ ao = (bf16_t*)a.ao;
+  for (int idx = tid; idx < G * DH; idx += 256) {
+    const int g = idx / DH, i = idx % DH;
+    const float sn = s_snew[g];
+    float mn = sn;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) mn = fmaxf(mn, s_m[q4][g]);
+    float den = __expf(sn - mn), num = den * s_vnew[i];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const float c = __expf(s_m[q4][g] - mn);
+      den += c * s_l[q4][g];
+      num += c * s_o[q4][g][i];
+    }
+    act_store<bf16_t>(ao, a.ao_plane, r, kvh * G * DH + idx, a.ao_K, num / den);
+  }
+}
+
 static size_t attn_smem_bytes(int DH, int G, int max_seq) {
   return (size_t)(G * DH + 2 * DH + 4 * G * DH + G * max_seq) * sizeof(float);
+}
+
+template <int DH>
+static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, hipStream_t s) {
+  dim3 grid(a.KVH, max_rows), block(256);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((k_attn_bf16<DH, 1>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((k_attn_bf16<DH, 2>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((k_attn_bf16<DH, 4>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((k_attn_bf16<DH, 8>), grid, block, 0, s, a); break;
+  }
 }
 
 template <typename T, int DH>
@@ -536,7 +738,12 @@ void launch_attention(int dtype, const ModelDims& md, const float* y, const floa
   if (dtype == 0) {
     if (md.dh == 64) launch_attn_g<float, 64>(a, G, max_rows, s); else launch_attn_g<float, 128>(a, G, max_rows, s);
   } else {
-    if (md.dh == 64) launch_attn_g<bf16_t, 64>(a, G, max_rows, s); else launch_attn_g<bf16_t, 128>(a, G, max_rows, s);
+    static const bool old_kernel = getenv("SPRINTER_ATTN_TWO_PASS") != nullptr;   // the first, two-pass kernel (kept for comparison runs)
+    if (old_kernel || (G != 1 && G != 2 && G != 4 && G != 8)) {
+      if (md.dh == 64) launch_attn_g<bf16_t, 64>(a, G, max_rows, s); else launch_attn_g<bf16_t, 128>(a, G, max_rows, s);
+    } else {
+      if (md.dh == 64) launch_attn_bf16<64>(a, G, max_rows, s); else launch_attn_bf16<128>(a, G, max_rows, s);
+    }
   }
 }
 
