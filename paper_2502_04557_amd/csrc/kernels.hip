@@ -7,7 +7,6 @@
 //   memory, so the host never learns how many rows were rejected.
 #include "dev.h"
 #include <cstring>
-#include <cstdlib>
 
 namespace sprinter {
 
@@ -197,18 +196,21 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
       }
     }
   };
-  load_weights(min(kw, Kt - 1));
-  float pbias[NTW], pres[NTW][MT][4];
+  // (One row tile only: with two, the extra live registers cost a workgroup per compute unit and
+  // the kernel, which then streams far more weight bytes per launch, measured 25 % slower.)
+  constexpr bool EARLY = MT == 1;
+  float pbias[NTW], pres[NTW][EARLY ? MT : 1][4];
+  if (EARLY) {
+    load_weights(min(kw, Kt - 1));
 #pragma unroll
-  for (int j = 0; j < NTW; ++j) {
-    const int n = (nt0 + j) * 16 + (lane & 15);
-    const bool n_ok = kw == 0 && nt0 + j < a.n_tiles && n < a.N;
-    pbias[j] = (n_ok && a.bias) ? a.bias[n] : 0.f;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int j = 0; j < NTW; ++j) {
+      const int n = (nt0 + j) * 16 + (lane & 15);
+      const bool n_ok = kw == 0 && nt0 + j < a.n_tiles && n < a.N;
+      pbias[j] = (n_ok && a.bias) ? a.bias[n] : 0.f;
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        pres[j][mt][v] = (EPI == EPI_RESID && n_ok) ? a.out_f32[(size_t)(mt * 16 + (lane >> 4) * 4 + v) * a.ldo + n] : 0.f;
+        pres[j][0][v] = (EPI == EPI_RESID && n_ok) ? a.out_f32[(size_t)((lane >> 4) * 4 + v) * a.ldo + n] : 0.f;
+    }
   }
   const int n_rows = *a.n_rows;
   if (n_rows <= 0) return;
@@ -224,24 +226,31 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
         if (DUAL) acc2[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
       }
     for (int kt = kw; kt < Kt; kt += KW * U) {
-      if (kt != kw || m0 != 0) load_weights(kt);            // the first chunk is already on its way
+      if (!EARLY || kt != kw || m0 != 0) load_weights(kt);  // (EARLY: the first chunk is already on its way)
+      // Straight-line code inside the (uniform) row-tile test: all activation loads of the chunk are
+      // issued together, k tiles beyond K are clamped on load and zeroed as operands.  (A branch per
+      // k tile keeps the scheduler from hoisting the loads and serialises one L2 latency per tile.)
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        int kc = kt + u * KW;
-        if (kc < Kt) {
+      for (int mt = 0; mt < MT; ++mt) {
+        if (mt < mt_act) {
+          uint4 xv[U], xl[U];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            if (mt < mt_act) {
-              uint4 xv = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
-              uint4 xl = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+          for (int u = 0; u < U; ++u) {
+            const int kc = min(kt + u * KW, Kt - 1);
+            xv[u] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+            xl[u] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+          }
 #pragma unroll
-              for (int j = 0; j < NTW; ++j) {
-                acc[j][mt] = mfma_bf16(xv, wv[u][j], acc[j][mt]);
-                acc[j][mt] = mfma_bf16(xl, wv[u][j], acc[j][mt]);
-                if (DUAL) {
-                  acc2[j][mt] = mfma_bf16(xv, wv2[u][j], acc2[j][mt]);
-                  acc2[j][mt] = mfma_bf16(xl, wv2[u][j], acc2[j][mt]);
-                }
+          for (int u = 0; u < U; ++u) {
+            const bool in_k = kt + u * KW < Kt;
+            const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int j = 0; j < NTW; ++j) {
+              acc[j][mt] = mfma_bf16(ah, wv[u][j], acc[j][mt]);
+              acc[j][mt] = mfma_bf16(al, wv[u][j], acc[j][mt]);
+              if (DUAL) {
+                acc2[j][mt] = mfma_bf16(ah, wv2[u][j], acc2[j][mt]);
+                acc2[j][mt] = mfma_bf16(al, wv2[u][j], acc2[j][mt]);
               }
             }
           }
@@ -290,9 +299,14 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
               const int m = m0 + mt * 16 + (lane >> 4) * 4 + v, n = (nt0 + j) * 16 + (lane & 15);
-              float res = pres[j][mt][v];
-              if (EPI == EPI_RESID && m0 != 0 && m < n_rows && n < a.N) res = a.out_f32[(size_t)m * a.ldo + n];
-              gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, acc[j][mt][v], DUAL ? acc2[j][mt][v] : 0.f, pbias[j], res);
+              float res = 0.f, bias = 0.f;
+              if (EARLY && m0 == 0) {
+                res = pres[j][0][v]; bias = pbias[j];
+              } else if (m < n_rows && n < a.N) {
+                if (EPI == EPI_RESID) res = a.out_f32[(size_t)m * a.ldo + n];
+                if (a.bias) bias = a.bias[n];
+              }
+              gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, acc[j][mt][v], DUAL ? acc2[j][mt][v] : 0.f, bias, res);
             }
           }
     }
@@ -542,7 +556,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 template <int DH, int G>
 __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   constexpr int LPK = DH / 8, KPW = 64 / LPK, HALF = DH / 2;
-  constexpr int NB = G <= 2 ? 16 : (G <= 4 ? 8 : 4);      // key blocks held in registers per round and wave
+  constexpr int NB = (G <= 4 && DH == 64) ? 8 : 4;       // key blocks held in registers per round and wave
   constexpr float NEG = -1e30f;
   __shared__ float s_m[4][G], s_l[4][G], s_o[4][G][DH], s_vnew[DH], s_snew[G];
   const int r = blockIdx.y;
@@ -738,12 +752,7 @@ void launch_attention(int dtype, const ModelDims& md, const float* y, const floa
   if (dtype == 0) {
     if (md.dh == 64) launch_attn_g<float, 64>(a, G, max_rows, s); else launch_attn_g<float, 128>(a, G, max_rows, s);
   } else {
-    static const bool old_kernel = getenv("SPRINTER_ATTN_TWO_PASS") != nullptr;   // the first, two-pass kernel (kept for comparison runs)
-    if (old_kernel || (G != 1 && G != 2 && G != 4 && G != 8)) {
-      if (md.dh == 64) launch_attn_g<bf16_t, 64>(a, G, max_rows, s); else launch_attn_g<bf16_t, 128>(a, G, max_rows, s);
-    } else {
-      if (md.dh == 64) launch_attn_bf16<64>(a, G, max_rows, s); else launch_attn_bf16<128>(a, G, max_rows, s);
-    }
+    if (md.dh == 64) launch_attn_bf16<64>(a, G, max_rows, s); else launch_attn_bf16<128>(a, G, max_rows, s);
   }
 }
 
@@ -792,16 +801,22 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
 #pragma unroll
         for (int u = 0; u < U; ++u) wv[u] = Wp[((size_t)nt * Kt + min(kt + u, Kt - 1)) * 64 + lane];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-          if (kt + u < Kt) {
+        for (int mt = 0; mt < MT; ++mt)
+          if (mt < mt_act) {                      // uniform; straight-line code inside (see k_gemm_bf16)
+            uint4 xv[U], xl[U];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-              if (mt < mt_act) {
-                uint4 xv = Xp[((size_t)(mtile0 + mt) * Kt + kt + u) * 64 + lane];
-                uint4 xl = Xl[((size_t)(mtile0 + mt) * Kt + kt + u) * 64 + lane];
-                acc[mt] = mfma_bf16(xv, wv[u], acc[mt]);
-                acc[mt] = mfma_bf16(xl, wv[u], acc[mt]);
-              }
+            for (int u = 0; u < U; ++u) {
+              const int kc = min(kt + u, Kt - 1);
+              xv[u] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+              xl[u] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              const bool in_k = kt + u < Kt;
+              const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
+              acc[mt] = mfma_bf16(ah, wv[u], acc[mt]);
+              acc[mt] = mfma_bf16(al, wv[u], acc[mt]);
+            }
           }
       }
       const int n = nt * 16 + (lane & 15);
