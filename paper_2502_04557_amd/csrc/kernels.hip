@@ -131,11 +131,86 @@ __global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const
     }
   }
 }
+// bf16 output: one row per workgroup, one thread per 8 consecutive columns (= one 16-byte slot of an
+// operand tile per plane), so the row, gain and offset are requested with six 16-byte loads per thread
+// before anything is waited for and the result leaves as two 16-byte stores.  d <= 8192.
+template <int ARCH>
+__global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, const float* __restrict__ g,
+                                                   const float* __restrict__ b, float eps, int d,
+                                                   const int* __restrict__ n_rows, bf16_t* __restrict__ act_out, size_t plane,
+                                                   float* __restrict__ f32_out) {
+  __shared__ float s4[4];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float4* __restrict__ x4 = reinterpret_cast<const float4*>(h + (size_t)r * d);
+  const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
+  const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b);
+  const int n_chunks = d >> 3;                       // d is a multiple of 8
+  float x[4][8], gg[4][8], bb[4][8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = min(tid + i * 256, n_chunks - 1);  // clamped: no branch around the loads
+    *reinterpret_cast<float4*>(&x[i][0]) = x4[2 * c]; *reinterpret_cast<float4*>(&x[i][4]) = x4[2 * c + 1];
+    *reinterpret_cast<float4*>(&gg[i][0]) = g4[2 * c]; *reinterpret_cast<float4*>(&gg[i][4]) = g4[2 * c + 1];
+    if (ARCH == 0) { *reinterpret_cast<float4*>(&bb[i][0]) = b4[2 * c]; *reinterpret_cast<float4*>(&bb[i][4]) = b4[2 * c + 1]; }
+  }
+  if (r >= *n_rows) return;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool ok = tid + i * 256 < n_chunks;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { x[i][e] = ok ? x[i][e] : 0.f; sum += x[i][e]; }
+  }
+  float mean = 0.f;
+  if (ARCH == 0) mean = block_sum256(sum, s4) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool ok = tid + i * 256 < n_chunks;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const float c = ok ? x[i][e] - mean : 0.f; sq += c * c; }
+  }
+  const float var = block_sum256(sq, s4) / (float)d;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  const int Kt = (d + 31) >> 5;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + i * 256;
+    if (c < n_chunks) {
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        o[e] = (x[i][e] - mean) * rstd * gg[i][e];
+        if (ARCH == 0) o[e] += bb[i][e];
+      }
+      uint4 hi, lo;
+      split2(o[0], o[1], hi.x, lo.x);
+      split2(o[2], o[3], hi.y, lo.y);
+      split2(o[4], o[5], hi.z, lo.z);
+      split2(o[6], o[7], hi.w, lo.w);
+      const int k = c * 8;
+      const size_t slot = ((size_t)(r >> 4) * Kt + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (r & 15)) * 8;
+      *reinterpret_cast<uint4*>(act_out + slot) = hi;
+      *reinterpret_cast<uint4*>(act_out + plane + slot) = lo;
+      if (f32_out) {
+        *reinterpret_cast<float4*>(f32_out + (size_t)r * d + k) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4*>(f32_out + (size_t)r * d + k + 4) = make_float4(o[4], o[5], o[6], o[7]);
+      }
+    }
+  }
+}
+
 void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
                  const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s) {
 #define NORM_CASE(AT, ARCH) \
   hipLaunchKernelGGL((k_norm<AT, ARCH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (AT*)act_out, plane, f32_out)
   if (dtype == 0) { if (arch == 0) NORM_CASE(float, 0); else NORM_CASE(float, 1); }
+  else if (d % 8 == 0 && d <= 8192) {
+    if (arch == 0)
+      hipLaunchKernelGGL((k_norm_bf16<0>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out);
+    else
+      hipLaunchKernelGGL((k_norm_bf16<1>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out);
+  }
   else            { if (arch == 0) NORM_CASE(bf16_t, 0); else NORM_CASE(bf16_t, 1); }
 #undef NORM_CASE
 }
@@ -179,7 +254,7 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
   const uint4* __restrict__ Xp = (const uint4*)a.X;
   const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   const int Kt = a.Kt;
-  constexpr int U = 4;
+  constexpr int U = 4;      // k tiles per chunk and wave (8 and 16 measured slower at one row tile)
   // Requests that depend on nothing are issued before the row count is even read: this wave's first
   // weight tiles and, in the wave that finishes the tile, the bias and (residual epilogue) the current
   // output values of the first row block.  That takes three memory latencies off the kernel's chain.
@@ -362,7 +437,9 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   // (Measured and dropped for the 16-row case: folding the layer norm into this kernel - every workgroup
   // then normalises the whole activation matrix again, 13.6 us against 5.3 + 5.0 us for norm + GEMM at
   // d = 1600 - and splitting K over workgroups for narrow outputs - the two device-scope fences of the
-  // last-arriver reduction cost more than the 4 us they save.)
+  // last-arriver reduction cost more than the 4 us they save; and a variant that requests all of a wave's
+  // weight and activation tiles up front (K <= 2048) - no faster: these kernels run at the rate the
+  // bytes arrive, not at the length of their dependency chain.)
   if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
   else hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
 }
