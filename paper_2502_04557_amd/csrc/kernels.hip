@@ -440,7 +440,9 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   // last-arriver reduction cost more than the 4 us they save; and a variant that requests all of a wave's
   // weight and activation tiles up front (K <= 2048) - no faster: these kernels run at the rate the
   // bytes arrive, not at the length of their dependency chain.)
-  if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  if (max_rows <= 16 && a.n_tiles >= 256)      // wide outputs: two column tiles per wave share the activation fragments
+    hipLaunchKernelGGL((k_gemm_bf16<1, 2, 8, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
+  else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
   else hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
 }
 
@@ -1028,16 +1030,32 @@ __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__
     }
     return;
   }
+  // one hidden unit per wave: its weight row stays in registers (2048 columns at a time), the rows of the
+  // batch go four at a time so that their loads and reductions overlap
   const int j = blockIdx.x * 8 + w;
-  for (int m = 0; m < n_rows; ++m) {
-    float c = 0.f;
-    if (j < d_hidden) {
-      float acc = 0.f;
-      for (int k = lane; k < d; k += 64) acc += w1[(size_t)j * d + k] * hf[(size_t)m * d + k];
-      acc = wave_sum(acc) + b1[j];
-      c = fmaxf(acc, 0.f) * w2[j];
+  const bool unit = j < d_hidden;
+  const float bj = unit ? b1[j] : 0.f, w2j = unit ? w2[j] : 0.f;
+  for (int m0 = 0; m0 < n_rows; m0 += 4) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int kc = 0; kc < d; kc += 2048) {
+      float wreg[32];
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const int k = kc + lane + 64 * i;
+        wreg[i] = (unit && k < d) ? w1[(size_t)j * d + k] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const int k = min(kc + lane + 64 * i, d - 1);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] += wreg[i] * hf[(size_t)min(m0 + r, n_rows - 1) * d + k];
+      }
     }
-    if (lane == 0) contrib[w * max_rows + m] = c;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float t = wave_sum(acc[r]) + bj;
+      if (lane == 0 && m0 + r < n_rows) contrib[w * max_rows + m0 + r] = unit ? fmaxf(t, 0.f) * w2j : 0.f;
+    }
   }
   __syncthreads();
   for (int m = threadIdx.x; m < n_rows; m += 512) {
