@@ -430,10 +430,10 @@ __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
 
 template <int EPI>
 static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
-  // One 16-column tile per workgroup, K split over its 8 waves.  Up to 16 rows: one row tile.  More: the
-  // kernel walks the rows 32 at a time and streams the weights once per pass; wider row blocks per wave
-  // multiply the activation traffic from L2 (a 16 x 32 weight tile needs 2 KiB of activations per 16 rows)
-  // and measured far slower than re-streaming.
+  // One 16-column tile per workgroup (two per wave for wide outputs at up to 16 rows), K split over its 8
+  // waves; 1, 2 or 4 row tiles per pass over the weights, more rows take further passes.  Above 16 rows the
+  // kernel is bound by the activation traffic from L2: every workgroup reads all rows' activations for its
+  // 16 columns (a 16 x 32 weight tile needs 2 KiB of activations per 16 rows), whatever the rows per pass.
   // (Measured and dropped for the 16-row case: folding the layer norm into this kernel - every workgroup
   // then normalises the whole activation matrix again, 13.6 us against 5.3 + 5.0 us for norm + GEMM at
   // d = 1600 - and splitting K over workgroups for narrow outputs - the two device-scope fences of the
@@ -443,7 +443,8 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   if (max_rows <= 16 && a.n_tiles >= 256)      // wide outputs: two column tiles per wave share the activation fragments
     hipLaunchKernelGGL((k_gemm_bf16<1, 2, 8, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
   else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  else if (max_rows <= 32) hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL((k_gemm_bf16<4, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
 }
 
 void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane, const int* n_rows,
