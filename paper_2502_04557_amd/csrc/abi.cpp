@@ -192,6 +192,7 @@ void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc
   sc.hf = (float*)bump.take((size_t)rows * md.d * 4);
   sc.hfn = bump.take(act_elems(c.dtype, rows, md.d) * es);
   sc.rope = (float*)bump.take((size_t)rows * md.dh * 4);
+  sc.part = (float*)bump.take((size_t)PART_SHARES * 16 * md.d * 4);
   sc.n_lm_wg = lmhead_num_wg(c.dtype, md.V);
   sc.am_part = (unsigned long long*)bump.take((size_t)sc.n_lm_wg * rows * 8);
   int* rd_n = (int*)bump.take(4);
@@ -336,28 +337,44 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
   const int rows = ctx->rows_alloc;
   const size_t pl_d = act_plane(dt, rows, md.d), pl_a = act_plane(dt, rows, md.H * md.dh), pl_f = act_plane(dt, rows, md.ff);
   launch_embed(dt, md, m.tok_emb, m.pos_emb, rd, sc.h, sc.rope, max_rows, s);
+  // At most 16 rows in bf16: O-proj and FFN-down split K over workgroups and leave partial products; the norm
+  // that follows folds them (and the bias) into the residual stream before it normalises the row.
+  const bool split = max_rows <= 16 && norm_takes_pending(dt, md.d);
+  const size_t part_stride = (size_t)16 * md.d;
+  NormPending pend{sc.part, part_stride, 0, nullptr};
+  auto resid_gemm = [&](const void* W, const void* X, size_t plane, int K, const float* bias) {
+    if (split) {
+      pend.shares = launch_gemm_part(W, X, plane, rd.n_rows, md.d, K, sc.part, part_stride, PART_SHARES, s);
+      pend.bias = bias;
+    } else {
+      launch_gemm(dt, EPI_RESID, W, nullptr, X, plane, rd.n_rows, md.d, K, bias, sc.h, md.d, nullptr, 0, 0, max_rows, s);
+    }
+  };
+  auto norm = [&](const float* g, const float* b, void* out, float* f32_out) {
+    launch_norm(dt, md.arch, sc.h, g, b, md.eps, md.d, rd.n_rows, out, pl_d, f32_out, max_rows, s,
+                pend.shares > 0 ? &pend : nullptr);
+    pend.shares = 0;
+  };
   for (int i = 0; i < md.n_layer; ++i) {
     const LayerW& L = m.layers[i];
-    launch_norm(dt, md.arch, sc.h, L.n1g, L.n1b, md.eps, md.d, rd.n_rows, sc.xn, pl_d, nullptr, max_rows, s);
+    norm(L.n1g, L.n1b, sc.xn, nullptr);
     launch_gemm(dt, EPI_F32, L.wqkv, nullptr, sc.xn, pl_d, rd.n_rows, md.dqkv, md.d, L.bqkv, sc.y, md.dqkv, nullptr, 0,
                 0, max_rows, s);
     launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
                      ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
-    launch_gemm(dt, EPI_RESID, L.wo, nullptr, sc.ao, pl_a, rd.n_rows, md.d, md.H * md.dh, L.bo, sc.h, md.d, nullptr, 0,
-                0, max_rows, s);
-    launch_norm(dt, md.arch, sc.h, L.n2g, L.n2b, md.eps, md.d, rd.n_rows, sc.xn, pl_d, nullptr, max_rows, s);
+    if (!want_head && i + 1 == md.n_layer) break;   // a prefill position only has to fill the caches
+    resid_gemm(L.wo, sc.ao, pl_a, md.H * md.dh, L.bo);
+    norm(L.n2g, L.n2b, sc.xn, nullptr);
     if (md.arch == SPRINTER_ARCH_GPT)
       launch_gemm(dt, EPI_GELU, L.w1, nullptr, sc.xn, pl_d, rd.n_rows, md.ff, md.d, L.b1, nullptr, 0, sc.mid, md.ff,
                   pl_f, max_rows, s);
     else
       launch_gemm(dt, EPI_SWIGLU, L.wg, L.wu, sc.xn, pl_d, rd.n_rows, md.ff, md.d, nullptr, nullptr, 0, sc.mid, md.ff,
                   pl_f, max_rows, s);
-    launch_gemm(dt, EPI_RESID, L.w2, nullptr, sc.mid, pl_f, rd.n_rows, md.d, md.ff, L.b2, sc.h, md.d, nullptr, 0, 0,
-                max_rows, s);
+    resid_gemm(L.w2, sc.mid, pl_f, md.ff, L.b2);
   }
   if (!want_head) return;
-  launch_norm(dt, md.arch, sc.h, (const float*)m.normf_g, (const float*)m.normf_b, md.eps, md.d, rd.n_rows, sc.hfn,
-              pl_d, sc.hf, max_rows, s);
+  norm((const float*)m.normf_g, (const float*)m.normf_b, sc.hfn, sc.hf);
   SamplerArgs sa;
   sa.seed_lo = (unsigned)(ctx->cfg.seed & 0xFFFFFFFFull);
   sa.seed_hi = (unsigned)(ctx->cfg.seed >> 32);

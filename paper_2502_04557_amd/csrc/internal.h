@@ -34,6 +34,7 @@ struct ModelDims {
   float eps, theta;
 };
 
+constexpr int PART_SHARES = 4;   // most K shares launch_gemm_part may use
 struct ModelScratch {  // per-model activation buffers, sized for max_batch rows
   float* h;            // [M, d] residual stream, float32
   void* xn;            // [M, d] normalised GEMM input (activation layout)
@@ -43,6 +44,7 @@ struct ModelScratch {  // per-model activation buffers, sized for max_batch rows
   float* hf;           // [M, d] final hidden state after the last norm, float32
   void* hfn;           // same values in activation layout (LM-head input)
   float* rope;         // [M, dh/2, 2] cos/sin of the row's position
+  float* part;         // [PART_SHARES][16, d] partial O-proj / FFN-down products of the 16-row path, float32
   unsigned long long* am_part;  // [n_lm_wg, Mpad] packed (value, index) arg-max partials
   int n_lm_wg;
 };
@@ -58,8 +60,19 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 void launch_embed(int dtype, const ModelDims& md, const void* tok_emb, const void* pos_emb,
                   const RowDesc& rd, float* h, float* rope, int max_rows, hipStream_t s);
+// An update of the residual stream that is still in pieces (launch_gemm_part): the norm kernel adds
+// bias + share 0 + share 1 + ... to the row, writes the row back and normalises the sum.
+struct NormPending {
+  const float* part; size_t stride; int shares; const float* bias;
+};
+// pend is honoured by the bf16 kernel only (d a multiple of 8, at most 8192): see norm_takes_pending().
 void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
-                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s);
+                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s,
+                 const NormPending* pend = nullptr);
+inline bool norm_takes_pending(int dtype, int d) { return dtype == 1 && d % 8 == 0 && d <= 8192; }
+// bf16, at most 16 rows: part[s] = X[:, K share s] W[:, K share s]^T for s < returned share count (<= max_shares)
+int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_rows, int N, int K, float* part,
+                     size_t part_stride, int max_shares, hipStream_t s);
 
 enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_SWIGLU = 3 };
 // Y[M,N] = X[M,K] W[N,K]^T (+bias) with epilogue; X in activation layout, W in weight layout.

@@ -138,7 +138,7 @@ template <int ARCH>
 __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, const float* __restrict__ g,
                                                    const float* __restrict__ b, float eps, int d,
                                                    const int* __restrict__ n_rows, bf16_t* __restrict__ act_out, size_t plane,
-                                                   float* __restrict__ f32_out) {
+                                                   float* __restrict__ f32_out, NormPending pend) {
   __shared__ float s4[4];
   const int r = blockIdx.x, tid = threadIdx.x;
   const float4* __restrict__ x4 = reinterpret_cast<const float4*>(h + (size_t)r * d);
@@ -154,6 +154,29 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
     if (ARCH == 0) { *reinterpret_cast<float4*>(&bb[i][0]) = b4[2 * c]; *reinterpret_cast<float4*>(&bb[i][4]) = b4[2 * c + 1]; }
   }
   if (r >= *n_rows) return;
+  if (pend.shares > 0) {
+    // the residual stream's last update is still in pieces: row += bias + share 0 + share 1 + ..., written back
+    float* hrow = const_cast<float*>(h) + (size_t)r * d;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + i * 256;
+      if (c < n_chunks) {
+        if (pend.bias) {
+          const float4 b0 = reinterpret_cast<const float4*>(pend.bias)[2 * c], b1 = reinterpret_cast<const float4*>(pend.bias)[2 * c + 1];
+          x[i][0] += b0.x; x[i][1] += b0.y; x[i][2] += b0.z; x[i][3] += b0.w;
+          x[i][4] += b1.x; x[i][5] += b1.y; x[i][6] += b1.z; x[i][7] += b1.w;
+        }
+        for (int q = 0; q < pend.shares; ++q) {
+          const float4* p4 = reinterpret_cast<const float4*>(pend.part + (size_t)q * pend.stride + (size_t)r * d);
+          const float4 p0 = p4[2 * c], p1 = p4[2 * c + 1];
+          x[i][0] += p0.x; x[i][1] += p0.y; x[i][2] += p0.z; x[i][3] += p0.w;
+          x[i][4] += p1.x; x[i][5] += p1.y; x[i][6] += p1.z; x[i][7] += p1.w;
+        }
+        *reinterpret_cast<float4*>(hrow + c * 8) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
+        *reinterpret_cast<float4*>(hrow + c * 8 + 4) = make_float4(x[i][4], x[i][5], x[i][6], x[i][7]);
+      }
+    }
+  }
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -201,15 +224,19 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
 }
 
 void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
-                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s) {
+                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s,
+                 const NormPending* pend) {
+  NormPending np;
+  memset(&np, 0, sizeof np);
+  if (pend) np = *pend;
 #define NORM_CASE(AT, ARCH) \
   hipLaunchKernelGGL((k_norm<AT, ARCH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (AT*)act_out, plane, f32_out)
   if (dtype == 0) { if (arch == 0) NORM_CASE(float, 0); else NORM_CASE(float, 1); }
   else if (d % 8 == 0 && d <= 8192) {
     if (arch == 0)
-      hipLaunchKernelGGL((k_norm_bf16<0>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out);
+      hipLaunchKernelGGL((k_norm_bf16<0>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out, np);
     else
-      hipLaunchKernelGGL((k_norm_bf16<1>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out);
+      hipLaunchKernelGGL((k_norm_bf16<1>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out, np);
   }
   else            { if (arch == 0) NORM_CASE(bf16_t, 0); else NORM_CASE(bf16_t, 1); }
 #undef NORM_CASE
@@ -222,6 +249,7 @@ struct GemmArgs {
   const float* bias; float* out_f32; int ldo; void* out_act; int out_K;
   size_t x_plane;     // elements between the hi and lo planes of X (bf16 mode)
   size_t out_plane;   // same for out_act
+  int SK; float* part; size_t part_stride;   // k_gemm16_part: K shares, partial outputs [SK][rows][N], floats per share
 };
 
 // bias: the column's bias (0 if none); res: the current value of the output element (residual epilogue only)
@@ -389,6 +417,86 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
   }
 }
 
+// bf16 GEMM for at most 16 rows whose output only has to exist as a sum: O-proj and FFN-down add into the
+// residual stream, and the layer norm that follows reads the whole row anyway.  K is split into SK shares
+// over workgroups (workgroup = NTW column tiles x one share), each share leaves its partial product in
+// part[s] and the norm kernel adds residual + bias + the shares in fixed order.  No reduction step, no
+// fences, and every workgroup reads only its share of the activations - which at 16 rows cost as much as
+// the weights: a workgroup needs 64 B of activations (L2) per k for 32 B of weights per k and tile.
+template <int NTW>
+__global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
+  constexpr int U = 4;
+  __shared__ float red[7 * NTW * 4 * 64];
+  const int lane = threadIdx.x & 63, kw = wave_index();
+  const int n_groups = (a.n_tiles + NTW - 1) / NTW;
+  const int g = blockIdx.x % n_groups, sk = blockIdx.x / n_groups;
+  const int nt0 = g * NTW, Kt = a.Kt;
+  const int k0 = (int)((long long)Kt * sk / a.SK), k1 = (int)((long long)Kt * (sk + 1) / a.SK);
+  const uint4* __restrict__ Wp = (const uint4*)a.W;
+  const uint4* __restrict__ Xp = (const uint4*)a.X;
+  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
+  uint4 wv[U][NTW];
+  auto load_weights = [&](int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kc = min(kt + u * 8, k1 - 1);                // clamped: always a tile of this share
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) wv[u][j] = Wp[((size_t)min(nt0 + j, a.n_tiles - 1) * Kt + kc) * 64 + lane];
+    }
+  };
+  load_weights(min(k0 + kw, k1 - 1));                         // before the row count is known
+  const int n_rows = *a.n_rows;
+  if (n_rows <= 0) return;
+  f32x4 acc[NTW];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int kt = k0 + kw; kt < k1; kt += 8 * U) {
+    if (kt != k0 + kw) load_weights(kt);
+    uint4 xv[U], xl[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kc = min(kt + u * 8, k1 - 1);
+      xv[u] = Xp[(size_t)kc * 64 + lane];
+      xl[u] = Xl[(size_t)kc * 64 + lane];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool in_k = kt + u * 8 < k1;
+      const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) {
+        acc[j] = mfma_bf16(ah, wv[u][j], acc[j]);
+        acc[j] = mfma_bf16(al, wv[u][j], acc[j]);
+      }
+    }
+  }
+  if (kw > 0) {
+    float* dst = red + (size_t)(kw - 1) * NTW * 4 * 64;
+#pragma unroll
+    for (int j = 0; j < NTW; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) dst[(j * 4 + v) * 64 + lane] = acc[j][v];
+  }
+  __syncthreads();
+  if (kw != 0) return;
+#pragma unroll
+  for (int q = 0; q < 7; ++q)            // fixed order
+#pragma unroll
+    for (int j = 0; j < NTW; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[j][v] += red[(size_t)q * NTW * 4 * 64 + (j * 4 + v) * 64 + lane];
+  float* out = a.part + (size_t)sk * a.part_stride;
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    const int n = (nt0 + j) * 16 + (lane & 15);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int m = (lane >> 4) * 4 + v;
+      if (nt0 + j < a.n_tiles && n < a.N && m < n_rows) out[(size_t)m * a.ldo + n] = acc[j][v];
+    }
+  }
+}
+
 // float32 GEMM on the vector ALU: one wave per output column, 8 rows at a time.
 template <int EPI>
 __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
@@ -472,6 +580,26 @@ void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* 
       default: launch_gemm_bf16<EPI_SWIGLU>(a, max_rows, s); break;
     }
   }
+}
+
+int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_rows, int N, int K, float* part,
+                     size_t part_stride, int max_shares, hipStream_t s) {
+  GemmArgs a;
+  memset(&a, 0, sizeof a);
+  a.W = W; a.X = X; a.x_plane = x_plane; a.n_rows = n_rows; a.N = N; a.K = K;
+  a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16; a.ldo = N;
+  a.part = part; a.part_stride = part_stride;
+  // shares: fill the 256 compute units, at least 12 k tiles per share; long K takes two column tiles per wave
+  const bool two = a.Kt >= 128 && a.n_tiles >= 64;
+  const int groups = two ? (a.n_tiles + 1) / 2 : a.n_tiles;
+  int sk = 256 / groups;
+  if (sk > max_shares) sk = max_shares;
+  while (sk > 1 && a.Kt / sk < 12) --sk;
+  if (sk < 1) sk = 1;
+  a.SK = sk;
+  if (two) hipLaunchKernelGGL((k_gemm16_part<2>), dim3(groups * sk), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL((k_gemm16_part<1>), dim3(groups * sk), dim3(512), 0, s, a);
+  return sk;
 }
 
 // ============================================================== attention
