@@ -10,6 +10,7 @@
 #include <cstring>
 #include <string>
 #include <unordered_map>
+#include <chrono>
 #include <vector>
 
 using namespace sprinter;
@@ -76,6 +77,8 @@ struct sprinter_ctx {
   float* score = nullptr;
   unsigned char* accept = nullptr;
   int rows_alloc = 0;
+  unsigned long long* host_counts = nullptr;   // pinned: [0] (ticket << 32) | rejected rows, written by the decide kernel
+  unsigned ticket = 0;
   // persistent decode kernel (bf16 mode)
   bool mega_on = false, mega_built = false;
   int mega_mt = 1, mega_grid = 0;
@@ -531,7 +534,7 @@ int check_room(sprinter_ctx* ctx, long long extra_steps) {
   return SPRINTER_OK;
 }
 
-void enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, int32_t* g_tok, uint8_t* g_accept,
+int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, int32_t* g_tok, uint8_t* g_accept,
                   float* g_score, int32_t* g_draft_tok) {
   hipStream_t s = ctx->stream;
   const int B = ctx->B;
@@ -550,9 +553,35 @@ void enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens,
   da.o_draft_tok = out ? out->draft_tok : nullptr; da.o_score = out ? out->score : nullptr;
   da.o_accept = out ? out->accept : nullptr; da.o_rej_idx = out ? out->rej_idx : nullptr;
   da.o_n_rej = out ? out->n_rej : nullptr;
+  da.host_word = ctx->host_counts; da.ticket = ++ctx->ticket;
+  if (da.ticket == 0) da.ticket = ++ctx->ticket;   // 0 is the word's initial value
   launch_draft_decide(da, s);
-  forward(ctx, tp, tp.rd(), B, true, 1u, out ? out->target_logits : nullptr);
-  if (out && out->target_hidden) launch_copy_f32(tp.sc.hf, out->target_hidden, tp.rd_n, tp.md.d, B, s);
+  // The host waits for the number of rejected rows R: the target's kernels are then launched for exactly R
+  // rows (row-tile count and K split follow R, not the batch size), and not at all when every row accepted.
+  // The decide kernel stores (ticket, R) into pinned memory and the host polls that word, which costs a few
+  // microseconds; after 2 s without the ticket it falls back to a stream synchronisation.
+  int R = -1;
+  {
+    volatile unsigned long long* word = ctx->host_counts;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (unsigned spin = 0;; ++spin) {
+      const unsigned long long v = *word;
+      if ((unsigned)(v >> 32) == da.ticket) { R = (int)(unsigned)(v & 0xFFFFFFFFull); break; }
+      if ((spin & 0xFFF) == 0xFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+        if (hipStreamSynchronize(s) != hipSuccess)
+          return fail(ctx, SPRINTER_E_HIP, "waiting for the draft pass failed: %s", hipGetErrorString(hipGetLastError()));
+        const unsigned long long v2 = *word;
+        if ((unsigned)(v2 >> 32) != da.ticket) return fail(ctx, SPRINTER_E_HIP, "the draft pass did not report its rejected rows");
+        R = (int)(unsigned)(v2 & 0xFFFFFFFFull);
+        break;
+      }
+    }
+  }
+  if (R < 0 || R > B) return fail(ctx, SPRINTER_E_HIP, "device reported %d rejected rows of %d", R, B);
+  if (R > 0) {
+    forward(ctx, tp, tp.rd(), R, true, 1u, out ? out->target_logits : nullptr);
+    if (out && out->target_hidden) launch_copy_f32(tp.sc.hf, out->target_hidden, tp.rd_n, tp.md.d, R, s);
+  }
   FinishArgs fa;
   fa.am_part = tp.sc.am_part; fa.n_lm_wg = tp.sc.n_lm_wg; fa.Mpad = ctx->rows_alloc; fa.B = B; fa.st = ctx->st;
   fa.draft_tok = ctx->draft_tok; fa.score = ctx->score; fa.accept = ctx->accept; fa.rej_idx = ctx->rej_idx;
@@ -561,6 +590,7 @@ void enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens,
   fa.o_committed = out ? out->committed_tok : nullptr;
   fa.n_tokens = n_tokens; fa.g_tok = g_tok; fa.g_accept = g_accept; fa.g_score = g_score; fa.g_draft_tok = g_draft_tok;
   launch_step_finish(fa, s);
+  return SPRINTER_OK;
 }
 
 int hip_status(sprinter_ctx* ctx, const char* what) {
@@ -621,6 +651,11 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     launch_fill_zero(m->sc.hfn, act_elems(cfg->dtype, rows, m->md.d) * es, ctx->stream);
   }
   launch_set_f32(ctx->tau_dev, cfg->tau, ctx->stream);
+  if (hipHostMalloc((void**)&ctx->host_counts, 256, hipHostMallocDefault) != hipSuccess) {
+    delete ctx;
+    return fail(nullptr, SPRINTER_E_HIP, "allocation of the pinned count buffer failed");
+  }
+  memset(ctx->host_counts, 0, 256);
   if (cfg->dtype == SPRINTER_BF16) {
     // operand-tile planes of the persistent kernel: padding lanes must read as zero
     for (MegaModel* mm : {&ctx->mega_host.draft, &ctx->mega_host.target}) {
@@ -670,7 +705,7 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     }
   }
   rc = hip_status(ctx, "sprinter_create");
-  if (rc) { delete ctx; return rc; }
+  if (rc) { sprinter_destroy(ctx); return rc; }
   *out_ctx = ctx;
   return SPRINTER_OK;
 }
@@ -755,10 +790,12 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
   ctx->steps_done = 0;
   Model &dq = ctx->draft, &tp = ctx->target;
   for (int j = 0; j + 1 < pmax; ++j) {
+    int n_j = 0;                                   // rows whose prompt still has a token to cache at index j
+    for (int b = 0; b < B; ++b) n_j += j < host_prompt_len[b] - 1;
     launch_prefill_prep(dev_prompt, max_prompt, j, B, ctx->st.prompt_len, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos,
                         dq.rd_slot, s);
-    forward(ctx, dq, dq.rd(), B, false, 0u, nullptr);
-    forward(ctx, tp, dq.rd(), B, false, 1u, nullptr);
+    forward(ctx, dq, dq.rd(), n_j, false, 0u, nullptr);
+    forward(ctx, tp, dq.rd(), n_j, false, 1u, nullptr);
   }
   launch_prefill_finish(dev_prompt, max_prompt, B, ctx->st, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos, dq.rd_slot, s);
   ctx->prefilled = true;
@@ -777,7 +814,8 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
     rc = enqueue_mega(ctx, out, 1, 0, nullptr, nullptr, nullptr, nullptr);
     if (rc) return rc;
   } else {
-    enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
+    rc = enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
+    if (rc) return rc;
   }
   ctx->steps_done += 1;
   return hip_status(ctx, "sprinter_step");
@@ -800,8 +838,10 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
       if (rc) return rc;
     }
   } else {
-    for (int g = 0; g < n_tokens; ++g)
-      enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+    for (int g = 0; g < n_tokens; ++g) {
+      rc = enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+      if (rc) return rc;
+    }
   }
   ctx->steps_done += n_tokens;
   return hip_status(ctx, "sprinter_generate");
@@ -851,7 +891,11 @@ int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out) {
   return SPRINTER_OK;
 }
 
-void sprinter_destroy(sprinter_ctx* ctx) { delete ctx; }
+void sprinter_destroy(sprinter_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->host_counts) (void)hipHostFree(ctx->host_counts);
+  delete ctx;
+}
 
 const char* sprinter_last_error(const sprinter_ctx* ctx) { return ctx ? ctx->err : g_err; }
 

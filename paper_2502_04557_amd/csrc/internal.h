@@ -114,6 +114,8 @@ struct DecideArgs {
   int* t_n_rows; int* t_b; int* t_tok; int* t_pos; int* t_slot;
   // optional caller outputs (per-step layout [B])
   int* o_draft_tok; float* o_score; unsigned char* o_accept; int* o_rej_idx; int* o_n_rej;
+  // pinned host word the waiting host thread polls: (ticket << 32) | number of rejected rows
+  unsigned long long* host_word; unsigned ticket;
 };
 void launch_draft_decide(const DecideArgs& a, hipStream_t s);
 

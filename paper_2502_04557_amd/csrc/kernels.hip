@@ -1270,6 +1270,9 @@ __global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
     *a.n_rej = total;
     *a.t_n_rows = total;
     if (a.o_n_rej) *a.o_n_rej = total;
+    if (a.host_word)    // one 8-byte store into pinned host memory: the host launches the target pass from it
+      __hip_atomic_store(a.host_word, ((unsigned long long)a.ticket << 32) | (unsigned)total, __ATOMIC_RELEASE,
+                         __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
 void launch_draft_decide(const DecideArgs& a, hipStream_t s) {
