@@ -33,7 +33,7 @@ def kv_bytes_per_token(m, es):
     return 2 * m.n_layer * m.n_kv_head * m.d_head * es
 
 
-def algorithmic_bytes(cfg, plen, accept, first_step):
+def algorithmic_bytes(cfg, plen, accept, first_step, seen_before=None):
     """Bytes the method must move per step, from the actual accept flags:
     draft weights + draft KV (read len+1, write 1) + verifier + [R>0](target weights + target KV of the R rows)."""
     import numpy as np
@@ -50,7 +50,19 @@ def algorithmic_bytes(cfg, plen, accept, first_step):
     per_step = np.full(K, float(Wq + Wv))
     per_step += ((len_q + 2) * kq).sum(0)                                         # read len+1, write 1
     R = rej.sum(0)
-    per_step += (R > 0) * Wp + (rej * (len_p + 2) * kp).sum(0)
+    if cfg.target_ctx_mode == 0:
+        per_step += (R > 0) * Wp + (rej * (len_p + 2) * kp).sum(0)
+    else:
+        # full prefix: a rejected row brings one entry per token its target cache has not seen
+        # (positions seen .. len_q), each reading the cache up to its position and writing one entry
+        seen = np.array(seen_before, dtype=np.int64)          # entries in the target cache before the timed steps
+        for k in range(K):
+            kv = 0
+            for b in np.flatnonzero(rej[:, k]):
+                pos = np.arange(seen[b], len_q[b, k] + 1)
+                kv += int(((pos + 2) * kp).sum())
+                seen[b] = len_q[b, k] + 1
+            per_step[k] += (R[k] > 0) * Wp + kv
     return per_step, R
 
 
@@ -94,6 +106,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--config", default="c2")
     ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--target-ctx", choices=("own", "full"), default="own",
+                    help="own: single-token target calls on the row's own history (the headline path); "
+                         "full: the target first consumes the committed tokens it has not seen")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
@@ -115,7 +130,8 @@ def main():
     lim = min(m.max_pos for m in (base.draft, base.target))
     if need > lim:
         raise SystemExit(f"prompt {pmax} + warmup {Wm} + steps {K} exceeds the models' context {lim}")
-    cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau)
+    cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau,
+                  target_ctx_mode=W.CTX_FULL_PREFIX if args.target_ctx == "full" else W.CTX_OWN_HISTORY)
 
     t0 = time.time()
     weights = W.make_weights(cfg)
@@ -136,8 +152,13 @@ def main():
     B = len(plen)
     dev = s.device
     s.prefill(prompts, plen)
+    seen_before = plen.astype(np.int64) - 1
     if Wm:
-        s.generate(Wm, want=("tok",))
+        wa = s.generate(Wm, want=("tok", "accept"))["accept"].cpu().numpy()
+        for b in range(B):                                    # full-prefix mode: the cache is complete after a rejection
+            r = np.flatnonzero(wa[b] == 0)
+            if len(r):
+                seen_before[b] = plen[b] - 1 + r[-1] + 1
     tok = torch.zeros(B, K, dtype=torch.int32, device=dev)
     acc = torch.zeros(B, K, dtype=torch.uint8, device=dev)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -151,7 +172,7 @@ def main():
     ev_ms = ev0.elapsed_time(ev1)
     st = s.stats()
     accept = acc.cpu().numpy()
-    per_step_bytes, R = algorithmic_bytes(cfg, plen, accept, Wm)
+    per_step_bytes, R = algorithmic_bytes(cfg, plen, accept, Wm, seen_before)
     step_ms = ev_ms / K
     achieved = per_step_bytes.mean() / (step_ms * 1e-3) / 1e9
     out = {
@@ -164,7 +185,8 @@ def main():
         "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: batch {B}, prompt {pmax}, tau {cfg.tau}, T {cfg.temperature}; "
                                f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
-                               f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts",
+                               f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts"
+                               + ("; full-prefix target context" if cfg.target_ctx_mode == 1 else ""),
                    "batch": B, "prompt_len": pmax},
         "target_calls_per_token": float(R.sum() / (B * K)),
         "steps_with_target_frac": float((R > 0).mean()),

@@ -75,9 +75,17 @@ typedef struct {
  *   temperature 0 selects greedy decoding; otherwise tokens are drawn by
  *   Gumbel-max with Philox4x32-10 noise keyed by (seed; vocab index, position,
  *   row, stream), so a run is reproducible from (seed, prompts) alone.
- *   target_ctx_mode 0: the target's cache holds the prompt plus one entry per
- *   earlier target call of that row (each with its true position id).  Other
- *   values are rejected. */
+ *   target_ctx_mode 0 (own history): the target's cache holds the prompt plus
+ *   one entry per earlier target call of that row (each with its true position
+ *   id), so a target call is a single-token forward (the cost model of
+ *   Sec. 3.1(c)).  target_ctx_mode 1 (full prefix): before it scores the
+ *   rejected position the target first consumes every committed token of that
+ *   row it has not seen, so its distribution is conditioned on the whole
+ *   prefix (Sec. 2, Alg. 2 "Run M_p Once" on Prefix); a rejected row then
+ *   brings one work-list entry per unseen token and the target pass runs over
+ *   the list in chunks of at most max_batch (rounded up) entries.  In this
+ *   mode sprinter_step does not produce target_logits / target_hidden (they
+ *   must be NULL).  Other values are rejected. */
 typedef struct {
   sprinter_model_cfg draft, target;
   int32_t ver_d_in, ver_d_hidden;

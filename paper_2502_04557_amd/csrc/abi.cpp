@@ -10,6 +10,7 @@
 #include <cstring>
 #include <string>
 #include <unordered_map>
+#include <algorithm>
 #include <chrono>
 #include <vector>
 
@@ -79,6 +80,7 @@ struct sprinter_ctx {
   int rows_alloc = 0;
   unsigned long long* host_counts = nullptr;   // pinned: [0] (ticket << 32) | rejected rows, written by the decide kernel
   unsigned ticket = 0;
+  int *ent_off = nullptr, *t_last = nullptr;   // full-prefix mode: work-list prefix sums, last-entry flags of a chunk
   // persistent decode kernel (bf16 mode)
   bool mega_on = false, mega_built = false;
   int mega_mt = 1, mega_grid = 0;
@@ -160,7 +162,8 @@ int validate_cfg(const sprinter_cfg* c, char* buf, size_t n) {
   if (c->target.arch == SPRINTER_ARCH_GPT && c->max_seq > c->target.max_pos) BAD("max_seq %d > target max_pos %d", c->max_seq, c->target.max_pos);
   if (!(c->temperature >= 0.f)) BAD("temperature must be >= 0");
   if (!(c->tau == c->tau)) BAD("tau is NaN");
-  if (c->target_ctx_mode != 0) BAD("target_ctx_mode %d is not supported (only 0, own history)", c->target_ctx_mode);
+  if (c->target_ctx_mode != 0 && c->target_ctx_mode != 1)
+    BAD("target_ctx_mode %d is not one of 0 (own history), 1 (full prefix)", c->target_ctx_mode);
   for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
     int dh = m->d_model / m->n_head, G = m->n_head / m->n_kv_head;
     size_t lds = (size_t)(G * dh + 2 * dh + 4 * G * dh + G * c->max_seq) * 4;
@@ -257,7 +260,9 @@ void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc
 // Lays the whole workspace out; ctx == nullptr only measures.  Returns total bytes.
 size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scratch_begin, size_t* scratch_end) {
   Bump bump(base);
-  const int rows = rows_alloc_for(c.max_batch);
+  // full-prefix mode: every committed token reaches the target once, so a step's work list averages one entry
+  // per batch row with wide swings; buffers for twice the batch keep most steps to a single pass
+  const int rows = rows_alloc_for(c.target_ctx_mode == 1 ? std::min(2 * c.max_batch, 1024) : c.max_batch);
   carve_model(bump, c, c.draft, ctx ? &ctx->draft : nullptr, rows);
   carve_model(bump, c, c.target, ctx ? &ctx->target : nullptr, rows);
   int chunks = verifier_num_chunks(c.ver_d_hidden);
@@ -269,6 +274,10 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   st.prompt_len = (int*)bump.take((size_t)c.max_batch * 4);
   st.n_target_calls = (long long*)bump.take((size_t)c.max_batch * 8);
   st.counters = (long long*)bump.take(4 * 8);
+  st.hist_stride = c.max_seq + 1;
+  st.hist = (int*)bump.take((size_t)c.max_batch * st.hist_stride * 4);
+  int* ent_off = (int*)bump.take((size_t)(c.max_batch + 1) * 4);
+  int* t_last = (int*)bump.take((size_t)rows * 4);
   float* tau = (float*)bump.take(4);
   int* draft_tok = (int*)bump.take((size_t)c.max_batch * 4);
   float* score = (float*)bump.take((size_t)c.max_batch * 4);
@@ -325,14 +334,17 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
     ctx->ver_part = ver_part; ctx->ver_chunks = chunks; ctx->st = st; ctx->tau_dev = tau;
     ctx->draft_tok = draft_tok; ctx->score = score; ctx->accept = accept; ctx->rej_idx = rej_idx;
     ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows;
+    ctx->ent_off = ent_off; ctx->t_last = t_last;
   }
   (void)scratch_begin; (void)scratch_end;
   return total;
 }
 
 // One model forward over the rows described by rd (device-side count).
+// shared_caches: several rows of rd may belong to one batch row (consecutive positions): every layer appends all
+// new keys / values first and attends in a second launch.
 void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool want_head, unsigned stream_id,
-             float* logits_out) {
+             float* logits_out, bool shared_caches = false) {
   const int dt = ctx->cfg.dtype;
   const ModelDims& md = m.md;
   hipStream_t s = ctx->stream;
@@ -363,8 +375,15 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
     norm(L.n1g, L.n1b, sc.xn, nullptr);
     launch_gemm(dt, EPI_F32, L.wqkv, nullptr, sc.xn, pl_d, rd.n_rows, md.dqkv, md.d, L.bqkv, sc.y, md.dqkv, nullptr, 0,
                 0, max_rows, s);
-    launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
-                     ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
+    if (shared_caches) {
+      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 1);
+      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 2);
+    } else {
+      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
+    }
     if (!want_head && i + 1 == md.n_layer) break;   // a prefill position only has to fill the caches
     resid_gemm(L.wo, sc.ao, pl_a, md.H * md.dh, L.bo);
     norm(L.n2g, L.n2b, sc.xn, nullptr);
@@ -553,6 +572,8 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
   da.o_draft_tok = out ? out->draft_tok : nullptr; da.o_score = out ? out->score : nullptr;
   da.o_accept = out ? out->accept : nullptr; da.o_rej_idx = out ? out->rej_idx : nullptr;
   da.o_n_rej = out ? out->n_rej : nullptr;
+  const int mode = ctx->cfg.target_ctx_mode;
+  da.ctx_mode = mode; da.ent_off = ctx->ent_off;
   da.host_word = ctx->host_counts; da.ticket = ++ctx->ticket;
   if (da.ticket == 0) da.ticket = ++ctx->ticket;   // 0 is the word's initial value
   launch_draft_decide(da, s);
@@ -578,9 +599,26 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
     }
   }
   if (R < 0 || R > B) return fail(ctx, SPRINTER_E_HIP, "device reported %d rejected rows of %d", R, B);
-  if (R > 0) {
+  if (R > 0 && mode == 0) {
     forward(ctx, tp, tp.rd(), R, true, 1u, out ? out->target_logits : nullptr);
     if (out && out->target_hidden) launch_copy_f32(tp.sc.hf, out->target_hidden, tp.rd_n, tp.md.d, R, s);
+  } else if (R > 0) {
+    // full prefix: the work list (E entries, at least one per rejected row) goes through the target in chunks of
+    // at most rows_alloc entries, in list order, so that a later entry of a row finds the earlier ones cached
+    const long long E = (long long)((volatile unsigned long long*)ctx->host_counts)[1];
+    if (E < R || E > (long long)B * ctx->cfg.max_seq) return fail(ctx, SPRINTER_E_HIP, "device reported %lld work-list entries for %d rows", E, R);
+    CatchupArgs ca;
+    ca.st = ctx->st; ca.rej_idx = ctx->rej_idx; ca.n_rej = ctx->n_rej; ca.ent_off = ctx->ent_off;
+    ca.t_n_rows = tp.rd_n; ca.t_b = tp.rd_b; ca.t_tok = tp.rd_tok; ca.t_pos = tp.rd_pos; ca.t_slot = tp.rd_slot;
+    ca.t_last = ctx->t_last;
+    for (long long start = 0; start < E; start += ctx->rows_alloc) {
+      const int n = (int)std::min<long long>(ctx->rows_alloc, E - start);
+      ca.start = (int)start; ca.n = n;
+      launch_catchup_chunk(ca, s);
+      forward(ctx, tp, tp.rd(), n, true, 1u, nullptr, true);
+      launch_catchup_collect(tp.sc.am_part, tp.sc.n_lm_wg, ctx->rows_alloc, tp.rd_n, tp.rd_b, ctx->t_last, ctx->committed,
+                             n, s);
+    }
   }
   FinishArgs fa;
   fa.am_part = tp.sc.am_part; fa.n_lm_wg = tp.sc.n_lm_wg; fa.Mpad = ctx->rows_alloc; fa.B = B; fa.st = ctx->st;
@@ -588,6 +626,7 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
   fa.n_rej = ctx->n_rej; fa.committed = ctx->committed;
   fa.d_n_rows = dq.rd_n; fa.d_b = dq.rd_b; fa.d_tok = dq.rd_tok; fa.d_pos = dq.rd_pos; fa.d_slot = dq.rd_slot;
   fa.o_committed = out ? out->committed_tok : nullptr;
+  fa.ctx_mode = mode;
   fa.n_tokens = n_tokens; fa.g_tok = g_tok; fa.g_accept = g_accept; fa.g_score = g_score; fa.g_draft_tok = g_draft_tok;
   launch_step_finish(fa, s);
   return SPRINTER_OK;
@@ -677,7 +716,7 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     }
     // the persistent kernel is opt-in while the per-operation kernels are the faster path
     const char* on = getenv("SPRINTER_PERSISTENT");
-    if (on && on[0] == '1') {
+    if (on && on[0] == '1' && cfg->target_ctx_mode == 0) {
       const int rows = ctx->rows_alloc;
       ctx->mega_mt = rows <= 16 ? 1 : rows <= 32 ? 2 : rows <= 64 ? 4 : 8;
       MegaParams& hp = ctx->mega_host;
@@ -808,6 +847,8 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
   if (rc) return rc;
   rc = check_room(ctx, 1);
   if (rc) return rc;
+  if (ctx->cfg.target_ctx_mode == 1 && out && (out->target_logits || out->target_hidden))
+    return fail(ctx, SPRINTER_E_CONFIG, "target_logits / target_hidden are not produced with the full-prefix target context");
   rc = build_mega(ctx);
   if (rc) return rc;
   if (ctx->mega_on) {

@@ -83,7 +83,9 @@ void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* 
 
 void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
                       void* kcache, void* vcache, size_t layer_off, int max_batch, int max_seq,
-                      void* ao, size_t ao_plane, int max_rows, hipStream_t s);
+                      void* ao, size_t ao_plane, int max_rows, hipStream_t s, int phase = 0);
+// phase 0: append the row's new key / value to the cache and attend (rows of one launch own different caches);
+// phase 1: append only; phase 2: attend only (the pair serves launches where several rows share a cache).
 
 int lmhead_num_wg(int dtype, int V);
 void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, const RowDesc& rd, int V, int K,
@@ -101,6 +103,8 @@ struct State {           // device-resident per-batch state
   long long* n_target_calls;  // [B]
   long long* counters;   // [4] steps, steps_with_target, sum_rejected, gen_idx
   int* prompt_len;       // [B]
+  int* hist;             // [B][hist_stride] every committed token by position (prompt included)
+  int hist_stride;       // max_seq + 1
 };
 
 struct DecideArgs {
@@ -115,7 +119,11 @@ struct DecideArgs {
   // optional caller outputs (per-step layout [B])
   int* o_draft_tok; float* o_score; unsigned char* o_accept; int* o_rej_idx; int* o_n_rej;
   // pinned host word the waiting host thread polls: (ticket << 32) | number of rejected rows
+  // with ctx_mode 1 word [1] receives the number of work-list entries of the target pass
   unsigned long long* host_word; unsigned ticket;
+  // ctx_mode 1 (full prefix): rejected row i brings len_q - len_p + 1 entries (the committed tokens its target
+  // cache has not seen, then the step's own input); ent_off[0 .. R] = exclusive prefix sums of those counts
+  int ctx_mode; int* ent_off;
 };
 void launch_draft_decide(const DecideArgs& a, hipStream_t s);
 
@@ -131,8 +139,20 @@ struct FinishArgs {
   int* o_committed;
   // ... and [B, n_tokens] arrays indexed by the device-side generation counter (generate mode)
   int n_tokens; int* g_tok; unsigned char* g_accept; float* g_score; int* g_draft_tok;
+  int ctx_mode;   // 1: committed[] already holds the target's tokens, and a rejected row's target cache is complete afterwards
 };
 void launch_step_finish(const FinishArgs& a, hipStream_t s);
+
+// Full-prefix target context: entries [start, start + n) of the step's work list become the target's row
+// descriptors (several entries may belong to one batch row; entry order = ascending row, ascending position).
+struct CatchupArgs {
+  State st; const int* rej_idx; const int* n_rej; const int* ent_off; int start, n;
+  int* t_n_rows; int* t_b; int* t_tok; int* t_pos; int* t_slot; int* t_last;   // t_last[e] = 1: last entry of its row
+};
+void launch_catchup_chunk(const CatchupArgs& a, hipStream_t s);
+// After the chunk's forward: the sampled token of every last entry becomes the row's committed token.
+void launch_catchup_collect(const unsigned long long* am_part, int n_lm_wg, int Mpad, const int* n_rows, const int* t_b,
+                            const int* t_last, int* committed, int max_rows, hipStream_t s);
 
 void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const int* prompt_len,
                          int* n_rows, int* rb, int* rtok, int* rpos, int* rslot, hipStream_t s);

@@ -611,6 +611,7 @@ struct AttnArgs {
   void* kcache; void* vcache; size_t layer_off;
   int H, KVH, dqkv, max_seq, use_rope; float scale;
   void* ao; int ao_K; size_t ao_plane;
+  int phase;   // 0 append + attend, 1 append only, 2 attend only
 };
 
 template <typename T, int DH, int G>
@@ -653,11 +654,14 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
       kv = i < HALF ? kh[i] * c - kh[i + HALF] * sn : kh[i] * c + kh[i - HALF] * sn;
     }
     T kt = from_f<T>(kv), vt = from_f<T>(vh[i]);
-    Kc[(size_t)slot * DH + i] = kt;
-    Vc[(size_t)slot * DH + i] = vt;
+    if (a.phase != 2) {
+      Kc[(size_t)slot * DH + i] = kt;
+      Vc[(size_t)slot * DH + i] = vt;
+    }
     knew[i] = to_f<T>(kt);             // the entry as later steps will read it back
     vnew[i] = to_f<T>(vt);
   }
+  if (a.phase == 1) return;
   __syncthreads();
 
   constexpr int EPL = 16 / sizeof(T);  // elements per 16-byte lane load
@@ -826,11 +830,14 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     vnew[2 * e] = bf2f(w0); vnew[2 * e + 1] = bf2f(w1);
   }
   if (w == 0 && kin == 0) {                                     // append to the cache
-    *reinterpret_cast<uint4*>(Kc + (size_t)slot * DH + chunk * 8) = make_uint4(kpk[0], kpk[1], kpk[2], kpk[3]);
-    *reinterpret_cast<uint4*>(Vc + (size_t)slot * DH + chunk * 8) = make_uint4(vpk[0], vpk[1], vpk[2], vpk[3]);
+    if (a.phase != 2) {
+      *reinterpret_cast<uint4*>(Kc + (size_t)slot * DH + chunk * 8) = make_uint4(kpk[0], kpk[1], kpk[2], kpk[3]);
+      *reinterpret_cast<uint4*>(Vc + (size_t)slot * DH + chunk * 8) = make_uint4(vpk[0], vpk[1], vpk[2], vpk[3]);
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_vnew[chunk * 8 + e] = vnew[e];
   }
+  if (a.phase == 1) return;
   float snew[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -949,9 +956,10 @@ static void launch_attn_g(const AttnArgs& a, int G, int max_rows, hipStream_t s)
 
 void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
                       void* kcache, void* vcache, size_t layer_off, int max_batch, int max_seq, void* ao,
-                      size_t ao_plane, int max_rows, hipStream_t s) {
+                      size_t ao_plane, int max_rows, hipStream_t s, int phase) {
   (void)max_batch;
   AttnArgs a;
+  a.phase = phase;
   a.y = y; a.rope = rope; a.rd = rd; a.kcache = kcache; a.vcache = vcache; a.layer_off = layer_off;
   a.H = md.H; a.KVH = md.KVH; a.dqkv = md.dqkv; a.max_seq = max_seq; a.use_rope = md.arch == 1;
   a.scale = 1.0f / sqrtf((float)md.dh);
@@ -1266,6 +1274,24 @@ __global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
     a.t_pos[tid] = a.st.len_q[b];       // true position id of the input token
     a.t_slot[tid] = a.st.len_p[b];      // next free slot of the row's target cache
   }
+  if (a.ctx_mode == 1) {
+    // work list of the full-prefix target pass: entries per rejected row, exclusive prefix sums in ascending row order
+    __syncthreads();
+    int cnt = 0;
+    if (tid < total) { const int b = s_rej[tid]; cnt = a.st.len_q[b] - a.st.len_p[b] + 1; }
+    int inc = cnt;                                     // inclusive scan inside the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(inc, o); if (lane >= o) inc += up; }
+    if (lane == 63) s_wave_cnt[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+    for (int q = 0; q < 16; ++q) { const int c = s_wave_cnt[q]; if (q < w) before += c; all += c; }
+    if (tid < total) a.ent_off[tid] = before + inc - cnt;
+    if (tid == 0) {
+      a.ent_off[total] = all;
+      if (a.host_word) a.host_word[1] = (unsigned long long)(unsigned)all;   // ordered before the release store below
+    }
+  }
   if (tid == 0) {
     *a.n_rej = total;
     *a.t_n_rows = total;
@@ -1286,9 +1312,11 @@ __global__ __launch_bounds__(1024) void k_step_finish(FinishArgs a) {
   const int B = a.B, R = *a.n_rej;
   if (tid < B) s_commit[tid] = a.committed[tid];
   __syncthreads();
-  for (int i = w; i < R; i += 16) {
-    u64 k = merge_partials(a.am_part, a.n_lm_wg, a.Mpad, i, lane);
-    if (lane == 0) s_commit[a.rej_idx[i]] = key_index(k);
+  if (a.ctx_mode == 0) {
+    for (int i = w; i < R; i += 16) {
+      u64 k = merge_partials(a.am_part, a.n_lm_wg, a.Mpad, i, lane);
+      if (lane == 0) s_commit[a.rej_idx[i]] = key_index(k);
+    }
   }
   __syncthreads();
   const long long g = a.st.counters[3];
@@ -1300,9 +1328,10 @@ __global__ __launch_bounds__(1024) void k_step_finish(FinishArgs a) {
     int lq = a.st.len_q[tid] + 1;
     a.st.len_q[tid] = lq;
     if (!acc) {
-      a.st.len_p[tid] += 1;
+      a.st.len_p[tid] = a.ctx_mode == 1 ? lq : a.st.len_p[tid] + 1;
       a.st.n_target_calls[tid] += 1;
     }
+    a.st.hist[(size_t)tid * a.st.hist_stride + lq] = c;
     if (a.o_committed) a.o_committed[tid] = c;
     if (a.n_tokens > 0 && g < a.n_tokens) {
       size_t o = (size_t)tid * a.n_tokens + (size_t)g;
@@ -1373,6 +1402,7 @@ __global__ __launch_bounds__(1024) void k_prefill_finish(const int* __restrict__
     st.len_q[tid] = P - 1;
     st.len_p[tid] = P - 1;
     st.n_target_calls[tid] = 0;
+    for (int j = 0; j < P; ++j) st.hist[(size_t)tid * st.hist_stride + j] = prompt[(size_t)tid * max_prompt + j];
     d_b[tid] = tid;
     d_tok[tid] = last;
     d_pos[tid] = P - 1;
@@ -1387,6 +1417,46 @@ void launch_prefill_finish(const int* prompt, int max_prompt, int B, State st, i
                            int* d_pos, int* d_slot, hipStream_t s) {
   hipLaunchKernelGGL(k_prefill_finish, dim3(1), dim3(1024), 0, s, prompt, max_prompt, B, st, d_n_rows, d_b, d_tok,
                      d_pos, d_slot);
+}
+
+// ============================================ full-prefix target context: work list
+// One thread per entry of the chunk: binary search of the entry's rejected row in the prefix sums.
+__global__ __launch_bounds__(1024) void k_catchup_chunk(CatchupArgs a) {
+  const int R = *a.n_rej;
+  for (int i = threadIdx.x; i < a.n; i += 1024) {
+    const int e = a.start + i;
+    int lo = 0, hi = R - 1;                            // last row index with ent_off[row] <= e
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (a.ent_off[mid] <= e) lo = mid; else hi = mid - 1;
+    }
+    const int b = a.rej_idx[lo];
+    const int pos = a.st.len_p[b] + (e - a.ent_off[lo]);
+    a.t_b[i] = b;
+    a.t_tok[i] = a.st.hist[(size_t)b * a.st.hist_stride + pos];
+    a.t_pos[i] = pos;
+    a.t_slot[i] = pos;                                 // in this mode the target cache has no gaps: slot = position
+    a.t_last[i] = (e + 1 == a.ent_off[lo + 1]) ? 1 : 0;
+  }
+  if (threadIdx.x == 0) *a.t_n_rows = a.n;
+}
+void launch_catchup_chunk(const CatchupArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_catchup_chunk, dim3(1), dim3(1024), 0, s, a);
+}
+
+__global__ __launch_bounds__(256) void k_catchup_collect(const u64* __restrict__ am_part, int n_lm_wg, int Mpad,
+                                                        const int* __restrict__ n_rows, const int* __restrict__ t_b,
+                                                        const int* __restrict__ t_last, int* __restrict__ committed) {
+  const int lane = threadIdx.x & 63;
+  const int i = blockIdx.x * 4 + wave_index();
+  if (i >= *n_rows || !t_last[i]) return;
+  const u64 k = merge_partials(am_part, n_lm_wg, Mpad, i, lane);
+  if (lane == 0) committed[t_b[i]] = key_index(k);
+}
+void launch_catchup_collect(const unsigned long long* am_part, int n_lm_wg, int Mpad, const int* n_rows, const int* t_b,
+                            const int* t_last, int* committed, int max_rows, hipStream_t s) {
+  hipLaunchKernelGGL(k_catchup_collect, dim3((max_rows + 3) / 4), dim3(256), 0, s, am_part, n_lm_wg, Mpad, n_rows, t_b,
+                     t_last, committed);
 }
 
 __global__ void k_set_f32(float* p, float v) { *p = v; }

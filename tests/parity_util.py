@@ -40,7 +40,8 @@ class Pair:
         self.gpu.load_weights(binding.VERIFIER, vw)
         self.prompts, self.plen = W.make_prompts(cfg)
 
-    def oracle(self, n_gen, tau=None, forced=None, rows=None, keep_logits=False, whole_prompt_prefill=False):
+    def oracle(self, n_gen, tau=None, forced=None, rows=None, keep_logits=False, whole_prompt_prefill=False,
+               ctx_mode=None):
         cfg = self.cfg
         pr, pl = (self.prompts, self.plen) if rows is None else (self.prompts[rows], self.plen[rows])
         if forced is not None and rows is not None:
@@ -51,7 +52,8 @@ class Pair:
                           target_caches=osp.prefill_whole_prompt(self.target, pr, pl))
         return osp.generate(self.draft, self.target, self.verifier, pr, pl, n_gen,
                             cfg.tau if tau is None else tau, cfg.temperature, cfg.seed,
-                            forced=forced, rows=rows, keep_logits=keep_logits, **caches)
+                            ctx_mode=cfg.target_ctx_mode if ctx_mode is None else ctx_mode, forced=forced, rows=rows, keep_logits=keep_logits,
+                            **caches)
 
     def gpu_generate(self, n_gen):
         self.gpu.prefill(self.prompts, self.plen)

@@ -66,7 +66,7 @@ def test_config_validation(lib):
         (replace(base, max_batch=2000), "max_batch"),
         (replace(base, max_seq=4096), "max_pos"),
         (replace(base, dtype=7), "dtype"),
-        (replace(base, target_ctx_mode=1), "target_ctx_mode"),
+        (replace(base, target_ctx_mode=2), "target_ctx_mode"),
         (replace(base, temperature=-1.0), "temperature"),
         (replace(base, draft=replace(base.draft, arch=5)), "arch"),
         (replace(base, draft=replace(base.draft, d_ff=643)), "multiples of 8"),

@@ -111,6 +111,51 @@ def test_threshold_extremes(kind):
     p.close()
 
 
+@pytest.mark.parametrize("kind,dtype", [("gpt", W.DT_F32), ("llama", W.DT_F32), ("gpt", W.DT_BF16), ("llama", W.DT_BF16)])
+def test_full_prefix_target_context(kind, dtype):
+    """target_ctx_mode 1: before the target scores a rejected position it first consumes the committed tokens
+    it has not seen (Sec. 2: p(. | prefix); Alg. 2 runs M_p on Prefix).  The GPU's work list against the oracle
+    replayed on the GPU's history.  Segments: the configured threshold; tau = 0 (every row accepts, so every
+    target cache falls behind); tau > 1 (every row rejects: the work list has 5 entries per row, more than one
+    chunk, rows split over chunk borders); the configured threshold again."""
+    from dataclasses import replace
+    from parity_util import compare_replay
+    segments = [(None, 6), (0.0, 4), (1.5, 2), (None, 6)]
+    G = sum(n for _, n in segments)
+    cfg = replace(W.mini_config(kind, dtype, n_gen=G), target_ctx_mode=W.CTX_FULL_PREFIX)
+    p = _pair(cfg, ver_scale=8.0)
+    p.gpu.prefill(p.prompts, p.plen)
+    parts = []
+    for tau, n in segments:
+        p.gpu.set_tau(cfg.tau if tau is None else tau)
+        parts.append({k: v.cpu().numpy() for k, v in p.gpu.generate(n).items()})
+    g = {k: np.concatenate([q[k] for q in parts], axis=1) for k in parts[0]}
+    st = p.gpu.stats()
+    acc = g["accept"].astype(bool)
+    assert acc[:, 6:10].all() and not acc[:, 10:12].any()
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"]))
+    t0 = 0
+    for tau, n in segments:
+        cut = lambda d: {k: v[:, t0:t0 + n] for k, v in d.items() if isinstance(v, np.ndarray) and v.ndim == 2}
+        tau_seg = cfg.tau if tau is None else tau
+        r = cut(rec)
+        r["accept"] = (r["score"] >= np.float32(tau_seg)).astype(np.uint8)   # the oracle ran on one threshold
+        rep = compare_replay(cfg, cut(g), r, tau=tau_seg)
+        print(kind, dtype, "steps", t0, "..", t0 + n - 1, rep, flush=True)
+        t0 += n
+    assert np.array_equal(st["target_calls"], (~acc).sum(1))
+    # the all-reject step needs several passes: 5 entries per row against buffers of 16 (batch 5) / 64 (batch 19) rows
+    assert 5 * cfg.batch > {5: 16, 19: 64}[cfg.batch]
+    # after a rejection the row's target cache is complete: the oracle's caches end where its last rejection was
+    last_rej = np.array([max(t for t in range(G) if not acc[b, t]) for b in range(cfg.batch)])
+    assert np.array_equal(rec["len_p"], p.plen + last_rej)
+    # the own-history reading gives other target samples on this history: the mode changes the result
+    rec_own = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"]), ctx_mode=W.CTX_OWN_HISTORY)
+    rej = ~acc
+    assert (rec_own["target_tok"][rej] != rec["target_tok"][rej]).any()
+    p.close()
+
+
 def test_greedy_temperature_zero():
     from dataclasses import replace
     cfg = replace(W.mini_config("llama", W.DT_F32, n_gen=8), temperature=0.0)
@@ -181,13 +226,19 @@ def test_c2_persistent_kernel_sampled_rows(persistent_kernel):
     test_c2_full_size_sampled_rows()
 
 
-def test_c2_full_size_sampled_rows():
+def test_c2_full_prefix_sampled_rows():
+    """Config 2 at full size with the full-prefix target context (work lists of about 20 entries per step)."""
+    test_c2_full_size_sampled_rows(W.CTX_FULL_PREFIX)
+
+
+def test_c2_full_size_sampled_rows(ctx_mode=W.CTX_OWN_HISTORY):
     """Config 2 at its full size and in the launch configuration the benchmark times
     (GPT-2-small/XL shapes, bf16, batch 16, 128-token Zipf prompts): the oracle replays
     a sample of rows (first, last, two seeded) over the first steps on the GPU's history."""
     import time
     from parity_util import compare_replay
-    cfg = W.config("c2")
+    from dataclasses import replace
+    cfg = replace(W.config("c2"), target_ctx_mode=ctx_mode)
     t0 = time.time()
     p = _pair(cfg)
     print(f"c2 built in {time.time() - t0:.0f} s", flush=True)

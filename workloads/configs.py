@@ -8,7 +8,7 @@ ARCH_LLAMA = 1   # RMSNorm, no biases, RoPE (rotate-half), SwiGLU, untied LM hea
 DT_F32 = 0
 DT_BF16 = 1
 CTX_OWN_HISTORY = 0   # target cache = prompt + one entry per earlier target call
-CTX_FULL_PREFIX = 1   # (not built) target catches up on skipped tokens
+CTX_FULL_PREFIX = 1   # the target first consumes the committed tokens it has not seen
 
 
 @dataclass(frozen=True)
