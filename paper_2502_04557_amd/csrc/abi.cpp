@@ -198,7 +198,7 @@ void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc
   sc.hf = (float*)bump.take((size_t)rows * md.d * 4);
   sc.hfn = bump.take(act_elems(c.dtype, rows, md.d) * es);
   sc.rope = (float*)bump.take((size_t)rows * md.dh * 4);
-  sc.part = (float*)bump.take((size_t)PART_SHARES * 16 * md.d * 4);
+  sc.part = (float*)bump.take((size_t)PART_SHARES * rows * md.d * 4);
   sc.n_lm_wg = lmhead_num_wg(c.dtype, md.V);
   sc.am_part = (unsigned long long*)bump.take((size_t)sc.n_lm_wg * rows * 8);
   int* rd_n = (int*)bump.take(4);
@@ -352,14 +352,14 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
   const int rows = ctx->rows_alloc;
   const size_t pl_d = act_plane(dt, rows, md.d), pl_a = act_plane(dt, rows, md.H * md.dh), pl_f = act_plane(dt, rows, md.ff);
   launch_embed(dt, md, m.tok_emb, m.pos_emb, rd, sc.h, sc.rope, max_rows, s);
-  // At most 16 rows in bf16: O-proj and FFN-down split K over workgroups and leave partial products; the norm
-  // that follows folds them (and the bias) into the residual stream before it normalises the row.
-  const bool split = max_rows <= 16 && norm_takes_pending(dt, md.d);
-  const size_t part_stride = (size_t)16 * md.d;
+  // bf16: O-proj and FFN-down split K over workgroups and leave partial products; the norm that follows folds
+  // them (and the bias) into the residual stream before it normalises the row.
+  const bool split = norm_takes_pending(dt, md.d);
+  const size_t part_stride = (size_t)rows * md.d;
   NormPending pend{sc.part, part_stride, 0, nullptr};
   auto resid_gemm = [&](const void* W, const void* X, size_t plane, int K, const float* bias) {
     if (split) {
-      pend.shares = launch_gemm_part(W, X, plane, rd.n_rows, md.d, K, sc.part, part_stride, PART_SHARES, s);
+      pend.shares = launch_gemm_part(W, X, plane, rd.n_rows, md.d, K, sc.part, part_stride, PART_SHARES, max_rows, s);
       pend.bias = bias;
     } else {
       launch_gemm(dt, EPI_RESID, W, nullptr, X, plane, rd.n_rows, md.d, K, bias, sc.h, md.d, nullptr, 0, 0, max_rows, s);

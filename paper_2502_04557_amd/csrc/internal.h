@@ -34,7 +34,7 @@ struct ModelDims {
   float eps, theta;
 };
 
-constexpr int PART_SHARES = 4;   // most K shares launch_gemm_part may use
+constexpr int PART_SHARES = 8;   // most K shares launch_gemm_part may use
 struct ModelScratch {  // per-model activation buffers, sized for max_batch rows
   float* h;            // [M, d] residual stream, float32
   void* xn;            // [M, d] normalised GEMM input (activation layout)
@@ -44,7 +44,7 @@ struct ModelScratch {  // per-model activation buffers, sized for max_batch rows
   float* hf;           // [M, d] final hidden state after the last norm, float32
   void* hfn;           // same values in activation layout (LM-head input)
   float* rope;         // [M, dh/2, 2] cos/sin of the row's position
-  float* part;         // [PART_SHARES][16, d] partial O-proj / FFN-down products of the 16-row path, float32
+  float* part;         // [PART_SHARES][M, d] partial O-proj / FFN-down products (bf16 mode), float32
   unsigned long long* am_part;  // [n_lm_wg, Mpad] packed (value, index) arg-max partials
   int n_lm_wg;
 };
@@ -70,11 +70,11 @@ void launch_norm(int dtype, int arch, const float* h, const float* g, const floa
                  const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s,
                  const NormPending* pend = nullptr);
 inline bool norm_takes_pending(int dtype, int d) { return dtype == 1 && d % 8 == 0 && d <= 8192; }
-// bf16, at most 16 rows: part[s] = X[:, K share s] W[:, K share s]^T for s < returned share count (<= max_shares)
+// bf16: part[s] = X[:, K share s] W[:, K share s]^T for s < returned share count (<= max_shares)
 int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_rows, int N, int K, float* part,
-                     size_t part_stride, int max_shares, hipStream_t s);
+                     size_t part_stride, int max_shares, int max_rows, hipStream_t s);
 
-enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_SWIGLU = 3 };
+enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_SWIGLU = 3, EPI_PART = 4 /* partial product of one K share */ };
 // Y[M,N] = X[M,K] W[N,K]^T (+bias) with epilogue; X in activation layout, W in weight layout.
 // x_plane / out_plane: element distance between the hi and lo planes of a bf16 activation buffer.
 void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane,

@@ -4,8 +4,9 @@
 //   draft forward -> LM head + Gumbel-max sample -> verifier + threshold ->
 //   compaction of rejected rows -> target forward on those rows -> sample ->
 //   scatter back.  Every kernel reads the number of active rows from device
-//   memory, so the host never learns how many rows were rejected.
+//   memory; the launch shapes are upper bounds the host chooses.
 #include "dev.h"
+#include <algorithm>
 #include <cstring>
 
 namespace sprinter {
@@ -417,6 +418,131 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
   }
 }
 
+// bf16 GEMM for 17 .. 64 rows per pass (MT row tiles of 16), one column tile per workgroup, K split over
+// the 8 waves.  At these row counts a workgroup pulls the whole activation matrix (MT x 2 KiB per k tile,
+// from L2) for 1 KiB of weights per k tile, so the kernel lives on memory-level parallelism: two register
+// buffers, the loads of chunk c + 1 (weights and all MT row tiles, both planes) are in flight while the
+// MFMAs of chunk c run, and there is no branch inside the loop.  Row tiles beyond the row count are
+// computed on whatever the buffers hold and dropped by the epilogue; k tiles beyond K are clamped on load
+// and their weight operand zeroed.  blockIdx.y = pass over 16 * MT rows.
+template <int MT, int NTW, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NWT = NTW * (DUAL ? 2 : 1);          // weight tiles per k tile and wave
+  constexpr int U = (MT * NWT >= 8) ? 1 : 2, STEP = 8 * U;   // k tiles per buffer
+  constexpr int NI = MT * NWT * 4;
+  __shared__ float red[4 * NI * 64];
+  const int lane = threadIdx.x & 63, kw = wave_index();
+  const int nt0 = blockIdx.x * NTW, mtile0 = blockIdx.y * MT, Kt = a.Kt;
+  // EPI_PART: blockIdx.z = K share, the partial product goes to part[share] (summed by the consumer)
+  const int sk = (EPI == EPI_PART) ? blockIdx.z : 0, SK = (EPI == EPI_PART) ? gridDim.z : 1;
+  const int k0 = (int)((long long)Kt * sk / SK), k1 = (int)((long long)Kt * (sk + 1) / SK);
+  const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
+  const uint4* __restrict__ W2p = DUAL ? (const uint4*)a.W2 + lane : nullptr;
+  const uint4* __restrict__ Xp = (const uint4*)a.X + (size_t)mtile0 * Kt * 64 + lane;
+  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
+  size_t wrow[NTW];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt0 + j, a.n_tiles - 1) * Kt * 64;
+  struct Buf { uint4 w[U][NWT], xh[U][MT], xl[U][MT]; };
+  auto load = [&](Buf& b, int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kc = min(kt + u * 8, k1 - 1);
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) {
+        b.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
+        if (DUAL) b.w[u][NTW + j] = W2p[wrow[j] + (size_t)kc * 64];
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        b.xh[u][mt] = Xp[((size_t)mt * Kt + kc) * 64];
+        b.xl[u][mt] = Xl[((size_t)mt * Kt + kc) * 64];
+      }
+    }
+  };
+  f32x4 acc[NWT][MT];
+#pragma unroll
+  for (int j = 0; j < NWT; ++j)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](const Buf& b, int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool in_k = kt + u * 8 < k1;
+#pragma unroll
+      for (int j = 0; j < NWT; ++j) {
+        const uint4 w1 = in_k ? b.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[j][mt] = mfma_bf16(b.xh[u][mt], w1, acc[j][mt]);
+          acc[j][mt] = mfma_bf16(b.xl[u][mt], w1, acc[j][mt]);
+        }
+      }
+    }
+  };
+  Buf A, B;
+  load(A, min(k0 + kw, k1 - 1));
+  const int n_rows = *a.n_rows;
+  if (n_rows <= mtile0 * 16) return;
+  // (the scheduling barriers keep the compiler from sinking a buffer's loads down to their first use)
+  for (int kt = k0 + kw; kt < k1; kt += 2 * STEP) {
+    load(B, kt + STEP);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(A, kt);
+    __builtin_amdgcn_sched_barrier(0);
+    load(A, kt + 2 * STEP);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(B, kt + STEP);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // the 8 partial accumulators are summed pairwise through LDS: (0+4, 1+5, 2+6, 3+7), (0+2, 1+3), (0+1)
+#pragma unroll
+  for (int half = 4; half >= 1; half >>= 1) {
+    if (kw >= half && kw < 2 * half) {
+      float* dst = red + (size_t)(kw - half) * NI * 64;
+#pragma unroll
+      for (int j = 0; j < NWT; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) dst[((j * MT + mt) * 4 + v) * 64 + lane] = acc[j][mt][v];
+    }
+    __syncthreads();
+    if (kw < half) {
+      const float* src = red + (size_t)kw * NI * 64;
+#pragma unroll
+      for (int j = 0; j < NWT; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) acc[j][mt][v] += src[((j * MT + mt) * 4 + v) * 64 + lane];
+    }
+    __syncthreads();
+  }
+  if (kw != 0) return;
+  float* part = (EPI == EPI_PART) ? a.part + (size_t)sk * a.part_stride : nullptr;
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    if (nt0 + j >= a.n_tiles) break;
+    const int n = (nt0 + j) * 16 + (lane & 15);
+    const float bias = (EPI != EPI_PART && a.bias && n < a.N) ? a.bias[n] : 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int m = (mtile0 + mt) * 16 + (lane >> 4) * 4 + v;
+        if constexpr (EPI == EPI_PART) {
+          if (m < n_rows && n < a.N) part[(size_t)m * a.ldo + n] = acc[j][mt][v];
+        } else {
+          float res = 0.f;
+          if (EPI == EPI_RESID && m < n_rows && n < a.N) res = a.out_f32[(size_t)m * a.ldo + n];
+          gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, acc[j][mt][v], DUAL ? acc[NTW + j][mt][v] : 0.f, bias, res);
+        }
+      }
+  }
+}
+
 // bf16 GEMM for at most 16 rows whose output only has to exist as a sum: O-proj and FFN-down add into the
 // residual stream, and the layer norm that follows reads the whole row anyway.  K is split into SK shares
 // over workgroups (workgroup = NTW column tiles x one share), each share leaves its partial product in
@@ -538,21 +664,29 @@ __global__ __launch_bounds__(256) void k_gemm_f32(GemmArgs a) {
 
 template <int EPI>
 static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
-  // One 16-column tile per workgroup (two per wave for wide outputs at up to 16 rows), K split over its 8
-  // waves; 1, 2 or 4 row tiles per pass over the weights, more rows take further passes.  Above 16 rows the
-  // kernel is bound by the activation traffic from L2: every workgroup reads all rows' activations for its
-  // 16 columns (a 16 x 32 weight tile needs 2 KiB of activations per 16 rows), whatever the rows per pass.
-  // (Measured and dropped for the 16-row case: folding the layer norm into this kernel - every workgroup
+  // Up to 16 rows: one 16-column tile per workgroup (two per wave for wide outputs), K split over its 8 waves.
+  // (Measured and dropped for that case: folding the layer norm into this kernel - every workgroup
   // then normalises the whole activation matrix again, 13.6 us against 5.3 + 5.0 us for norm + GEMM at
-  // d = 1600 - and splitting K over workgroups for narrow outputs - the two device-scope fences of the
-  // last-arriver reduction cost more than the 4 us they save; and a variant that requests all of a wave's
-  // weight and activation tiles up front (K <= 2048) - no faster: these kernels run at the rate the
-  // bytes arrive, not at the length of their dependency chain.)
+  // d = 1600 - and splitting K over workgroups with a last-arriver reduction - its two device-scope fences
+  // cost more than the 4 us they save; and a variant that requests all of a wave's weight and activation
+  // tiles up front (K <= 2048) - no faster.)
+  // 17 .. 64 rows: 2, 3 or 4 row tiles per pass with double-buffered loads; more rows take further passes.
   if (max_rows <= 16 && a.n_tiles >= 256)      // wide outputs: two column tiles per wave share the activation fragments
     hipLaunchKernelGGL((k_gemm_bf16<1, 2, 8, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
   else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
-  else if (max_rows <= 32) hipLaunchKernelGGL((k_gemm_bf16<2, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL((k_gemm_bf16<4, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  else {
+    // column tiles per wave that share the activation fragments: as many as leave about 192 workgroups
+    const int passes = (max_rows + 63) / 64;
+    const int mt = max_rows <= 32 ? 2 : max_rows <= 48 ? 3 : 4;
+    constexpr bool DUAL = EPI == EPI_SWIGLU;
+    const int ntw = (!DUAL && mt > 2 && a.n_tiles / 4 >= 192) ? 4 : (a.n_tiles / 2 >= (DUAL || mt == 2 ? 256 : 128)) ? 2 : 1;
+    const dim3 grid((a.n_tiles + ntw - 1) / ntw, passes, 1);
+#define SPRINTER_ROWS(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI>), grid, dim3(512), 0, s, a)
+    if (ntw == 4) { if (mt == 3) SPRINTER_ROWS(3, 4); else SPRINTER_ROWS(4, 4); }
+    else if (ntw == 2) { if (mt == 2) SPRINTER_ROWS(2, 2); else if (mt == 3) SPRINTER_ROWS(3, 2); else SPRINTER_ROWS(4, 2); }
+    else { if (mt == 2) SPRINTER_ROWS(2, 1); else if (mt == 3) SPRINTER_ROWS(3, 1); else SPRINTER_ROWS(4, 1); }
+#undef SPRINTER_ROWS
+  }
 }
 
 void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane, const int* n_rows,
@@ -583,22 +717,39 @@ void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* 
 }
 
 int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_rows, int N, int K, float* part,
-                     size_t part_stride, int max_shares, hipStream_t s) {
+                     size_t part_stride, int max_shares, int max_rows, hipStream_t s) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
   a.W = W; a.X = X; a.x_plane = x_plane; a.n_rows = n_rows; a.N = N; a.K = K;
   a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16; a.ldo = N;
   a.part = part; a.part_stride = part_stride;
-  // shares: fill the 256 compute units, at least 12 k tiles per share; long K takes two column tiles per wave
-  const bool two = a.Kt >= 128 && a.n_tiles >= 64;
-  const int groups = two ? (a.n_tiles + 1) / 2 : a.n_tiles;
-  int sk = 256 / groups;
-  if (sk > max_shares) sk = max_shares;
-  while (sk > 1 && a.Kt / sk < 12) --sk;
-  if (sk < 1) sk = 1;
+  if (max_rows <= 16) {
+    // shares: fill the 256 compute units, at least 12 k tiles per share; long K takes two column tiles per wave
+    const bool two = a.Kt >= 128 && a.n_tiles >= 64;
+    const int groups = two ? (a.n_tiles + 1) / 2 : a.n_tiles;
+    int sk = 256 / groups;
+    if (sk > max_shares) sk = max_shares;
+    while (sk > 1 && a.Kt / sk < 12) --sk;
+    if (sk < 1) sk = 1;
+    a.SK = sk;
+    if (two) hipLaunchKernelGGL((k_gemm16_part<2>), dim3(groups * sk), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((k_gemm16_part<1>), dim3(groups * sk), dim3(512), 0, s, a);
+    return sk;
+  }
+  // 17+ rows: the workgroup's activation traffic (2 KiB per k tile and 16 rows) is what costs, so a wave takes
+  // four column tiles (two if that leaves too few workgroups) and K is split until about 256 workgroups exist,
+  // with at least two k tiles per wave and share
+  const int passes = (max_rows + 63) / 64;
+  const int mt = max_rows <= 32 ? 2 : max_rows <= 48 ? 3 : 4;
+  const int s_max = std::max(1, std::min(max_shares, a.Kt / 16));
+  int ntw = 4, groups = (a.n_tiles + 3) / 4, sk = std::min(s_max, std::max(1, 256 / groups));
+  if (groups * sk < 192) { ntw = 2; groups = (a.n_tiles + 1) / 2; sk = std::min(s_max, std::max(1, 256 / groups)); }
   a.SK = sk;
-  if (two) hipLaunchKernelGGL((k_gemm16_part<2>), dim3(groups * sk), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL((k_gemm16_part<1>), dim3(groups * sk), dim3(512), 0, s, a);
+  const dim3 grid(groups, passes, sk);
+#define SPRINTER_PART(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI_PART>), grid, dim3(512), 0, s, a)
+  if (ntw == 4) { if (mt == 2) SPRINTER_PART(2, 4); else if (mt == 3) SPRINTER_PART(3, 4); else SPRINTER_PART(4, 4); }
+  else { if (mt == 2) SPRINTER_PART(2, 2); else if (mt == 3) SPRINTER_PART(3, 2); else SPRINTER_PART(4, 2); }
+#undef SPRINTER_PART
   return sk;
 }
 
