@@ -135,7 +135,11 @@ __global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const
 // bf16 output: one row per workgroup, one thread per 8 consecutive columns (= one 16-byte slot of an
 // operand tile per plane), so the row, gain and offset are requested with six 16-byte loads per thread
 // before anything is waited for and the result leaves as two 16-byte stores.  d <= 8192.
-template <int ARCH>
+// NI = 2048-column blocks per row (1, 2 or 4); SH = 0, or the most partial products a pending update of the
+// residual stream may consist of (4 or 8): the row is then h + bias + share 0 + share 1 + ..., added in that
+// order, written back and normalised.  The partial loads are issued with the others, before the row count
+// is known, with clamped share indices and the surplus selected away - no branch, no second memory round.
+template <int ARCH, int NI, int SH>
 __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, const float* __restrict__ g,
                                                    const float* __restrict__ b, float eps, int d,
                                                    const int* __restrict__ n_rows, bf16_t* __restrict__ act_out, size_t plane,
@@ -146,33 +150,42 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
   const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
   const float4* __restrict__ b4 = reinterpret_cast<const float4*>(b);
   const int n_chunks = d >> 3;                       // d is a multiple of 8
-  float x[4][8], gg[4][8], bb[4][8];
+  float x[NI][8], gg[NI][8], bb[NI][8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NI; ++i) {
     const int c = min(tid + i * 256, n_chunks - 1);  // clamped: no branch around the loads
     *reinterpret_cast<float4*>(&x[i][0]) = x4[2 * c]; *reinterpret_cast<float4*>(&x[i][4]) = x4[2 * c + 1];
     *reinterpret_cast<float4*>(&gg[i][0]) = g4[2 * c]; *reinterpret_cast<float4*>(&gg[i][4]) = g4[2 * c + 1];
     if (ARCH == 0) { *reinterpret_cast<float4*>(&bb[i][0]) = b4[2 * c]; *reinterpret_cast<float4*>(&bb[i][4]) = b4[2 * c + 1]; }
   }
+  if (SH > 0) {
+    const float4* __restrict__ pb4 = reinterpret_cast<const float4*>(pend.bias ? pend.bias : g);
+    const bool has_bias = pend.bias != nullptr;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int c = min(tid + i * 256, n_chunks - 1);
+      float4 p0[SH + 1], p1[SH + 1];
+      p0[0] = pb4[2 * c]; p1[0] = pb4[2 * c + 1];
+#pragma unroll
+      for (int q = 0; q < SH; ++q) {
+        const float4* p4 = reinterpret_cast<const float4*>(pend.part + (size_t)min(q, pend.shares - 1) * pend.stride + (size_t)r * d);
+        p0[q + 1] = p4[2 * c]; p1[q + 1] = p4[2 * c + 1];
+      }
+#pragma unroll
+      for (int q = 0; q <= SH; ++q) {                // fixed order: bias, share 0, share 1, ...
+        const bool on = q == 0 ? has_bias : q - 1 < pend.shares;
+        x[i][0] += on ? p0[q].x : 0.f; x[i][1] += on ? p0[q].y : 0.f; x[i][2] += on ? p0[q].z : 0.f; x[i][3] += on ? p0[q].w : 0.f;
+        x[i][4] += on ? p1[q].x : 0.f; x[i][5] += on ? p1[q].y : 0.f; x[i][6] += on ? p1[q].z : 0.f; x[i][7] += on ? p1[q].w : 0.f;
+      }
+    }
+  }
   if (r >= *n_rows) return;
-  if (pend.shares > 0) {
-    // the residual stream's last update is still in pieces: row += bias + share 0 + share 1 + ..., written back
+  if (SH > 0) {
     float* hrow = const_cast<float*>(h) + (size_t)r * d;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NI; ++i) {
       const int c = tid + i * 256;
       if (c < n_chunks) {
-        if (pend.bias) {
-          const float4 b0 = reinterpret_cast<const float4*>(pend.bias)[2 * c], b1 = reinterpret_cast<const float4*>(pend.bias)[2 * c + 1];
-          x[i][0] += b0.x; x[i][1] += b0.y; x[i][2] += b0.z; x[i][3] += b0.w;
-          x[i][4] += b1.x; x[i][5] += b1.y; x[i][6] += b1.z; x[i][7] += b1.w;
-        }
-        for (int q = 0; q < pend.shares; ++q) {
-          const float4* p4 = reinterpret_cast<const float4*>(pend.part + (size_t)q * pend.stride + (size_t)r * d);
-          const float4 p0 = p4[2 * c], p1 = p4[2 * c + 1];
-          x[i][0] += p0.x; x[i][1] += p0.y; x[i][2] += p0.z; x[i][3] += p0.w;
-          x[i][4] += p1.x; x[i][5] += p1.y; x[i][6] += p1.z; x[i][7] += p1.w;
-        }
         *reinterpret_cast<float4*>(hrow + c * 8) = make_float4(x[i][0], x[i][1], x[i][2], x[i][3]);
         *reinterpret_cast<float4*>(hrow + c * 8 + 4) = make_float4(x[i][4], x[i][5], x[i][6], x[i][7]);
       }
@@ -180,7 +193,7 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
   }
   float sum = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NI; ++i) {
     const bool ok = tid + i * 256 < n_chunks;
 #pragma unroll
     for (int e = 0; e < 8; ++e) { x[i][e] = ok ? x[i][e] : 0.f; sum += x[i][e]; }
@@ -189,7 +202,7 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
   if (ARCH == 0) mean = block_sum256(sum, s4) / (float)d;
   float sq = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NI; ++i) {
     const bool ok = tid + i * 256 < n_chunks;
 #pragma unroll
     for (int e = 0; e < 8; ++e) { const float c = ok ? x[i][e] - mean : 0.f; sq += c * c; }
@@ -198,7 +211,7 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
   const float rstd = 1.0f / sqrtf(var + eps);
   const int Kt = (d + 31) >> 5;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < NI; ++i) {
     const int c = tid + i * 256;
     if (c < n_chunks) {
       float o[8];
@@ -224,6 +237,16 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
   }
 }
 
+template <int ARCH, int NI>
+static void launch_norm_bf16(const float* h, const float* g, const float* b, float eps, int d, const int* n_rows,
+                             bf16_t* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s, const NormPending& np) {
+#define SPRINTER_NORM(SH) hipLaunchKernelGGL((k_norm_bf16<ARCH, NI, SH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, act_out, plane, f32_out, np)
+  if (np.shares <= 0) SPRINTER_NORM(0);
+  else if (np.shares <= 4) SPRINTER_NORM(4);
+  else SPRINTER_NORM(8);
+#undef SPRINTER_NORM
+}
+
 void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
                  const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s,
                  const NormPending* pend) {
@@ -234,10 +257,16 @@ void launch_norm(int dtype, int arch, const float* h, const float* g, const floa
   hipLaunchKernelGGL((k_norm<AT, ARCH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (AT*)act_out, plane, f32_out)
   if (dtype == 0) { if (arch == 0) NORM_CASE(float, 0); else NORM_CASE(float, 1); }
   else if (d % 8 == 0 && d <= 8192) {
-    if (arch == 0)
-      hipLaunchKernelGGL((k_norm_bf16<0>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out, np);
-    else
-      hipLaunchKernelGGL((k_norm_bf16<1>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (bf16_t*)act_out, plane, f32_out, np);
+    bf16_t* out = (bf16_t*)act_out;
+    if (arch == 0) {
+      if (d <= 2048) launch_norm_bf16<0, 1>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+      else if (d <= 4096) launch_norm_bf16<0, 2>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+      else launch_norm_bf16<0, 4>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+    } else {
+      if (d <= 2048) launch_norm_bf16<1, 1>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+      else if (d <= 4096) launch_norm_bf16<1, 2>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+      else launch_norm_bf16<1, 4>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+    }
   }
   else            { if (arch == 0) NORM_CASE(bf16_t, 0); else NORM_CASE(bf16_t, 1); }
 #undef NORM_CASE
