@@ -756,7 +756,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
     // shares: fill the 256 compute units, at least 12 k tiles per share; long K takes two column tiles per wave
     const bool two = a.Kt >= 128 && a.n_tiles >= 64;
     const int groups = two ? (a.n_tiles + 1) / 2 : a.n_tiles;
-    int sk = 256 / groups;
+    int sk = std::min(4, 256 / groups);              // (4: the norm kernel's smaller partial-sum variant)
     if (sk > max_shares) sk = max_shares;
     while (sk > 1 && a.Kt / sk < 12) --sk;
     if (sk < 1) sk = 1;
