@@ -17,6 +17,7 @@ import numpy as np
 
 STREAM_DRAFT = 0
 STREAM_TARGET = 1
+STREAM_COIN = 2      # word 0 of block 0 is the accept-with-probability coin of (row, position)
 
 _M0 = np.uint64(0xD2511F53)
 _M1 = np.uint64(0xCD9E8D57)
@@ -58,6 +59,11 @@ def uniforms(words: np.ndarray) -> np.ndarray:
 def gumbel(seed: int, stream: int, b: int, t: int, V: int) -> np.ndarray:
     u = uniforms(random_words(seed, stream, b, t, V))
     return -np.log(-np.log(u))
+
+
+def coin(seed: int, b: int, t: int) -> float:
+    """The uniform of (row b, position t) on the coin stream."""
+    return float(uniforms(random_words(seed, STREAM_COIN, b, t, 1))[0])
 
 
 def sample(logits: np.ndarray, temperature: float, seed: int, stream: int, b: int, t: int):

@@ -26,6 +26,9 @@ Readings of points the paper leaves open (also listed in the design notes):
     id, so every target call is a single-token forward (the cost model of
     Sec. 3.1(c) charges one F_t per rejection).  FULL_PREFIX = the target first
     consumes every committed token it has not seen.
+  * REJECT_SD switches the rejection to the rule of the text (Sec. 3 / Sec. 2, Eq. (1); the coin of
+    Alg. 2): keep the draft token with probability min(1, p(x)/q(x)), otherwise draw from the
+    normalised residual max(0, p - q).  q and p are the softmax of logits / T.
   * the verifier input s(x, prefix) is the draft's final (post-norm) hidden
     state, the vector that also feeds the LM head.
   * a fixed number of tokens is generated; there is no end-of-sequence handling.
@@ -40,6 +43,39 @@ import numpy as np
 from . import philox
 
 CTX_OWN_HISTORY, CTX_FULL_PREFIX = 0, 1
+REJECT_REPLACE, REJECT_SD = 0, 1
+
+
+def log_softmax(a: np.ndarray) -> np.ndarray:
+    a = np.asarray(a, dtype=np.float64)
+    m = a.max()
+    return a - (m + np.log(np.exp(a - m).sum()))
+
+
+def sd_correction(lq, lp, x, temperature, seed, b, t):
+    """What a rejection does under REJECT_SD (Sec. 2: accept x ~ q with probability min(1, p(x)/q(x)),
+    else resample from Eq. (1): norm(max(0, p - q)); Alg. 2 draws the coin c ~ U(0, 1)).
+    The coin comparison and the arg-max of the residual draw are taken on float32 values.
+    Returns a dict: tok (the committed token), kept, coin, log_ratio = ln p(x) - ln q(x) (unclipped),
+    and for a residual draw its top-2 margin plus the two candidates (for tolerance bands)."""
+    if not temperature > 0.0:
+        raise ValueError("the p/q correction needs a temperature > 0")
+    logq, logp = log_softmax(np.asarray(lq, np.float64) / temperature), log_softmax(np.asarray(lp, np.float64) / temperature)
+    log_ratio = float(logp[x] - logq[x])
+    c = philox.coin(seed, b, t)
+    out = dict(coin=c, log_ratio=log_ratio, kept=bool(np.float32(c) <= np.float32(min(1.0, np.exp(log_ratio)))),
+               tok=int(x), margin=np.inf, runner_up=-1, logq=logq, logp=logp)
+    if not out["kept"]:
+        r = np.maximum(0.0, np.exp(logp) - np.exp(logq))
+        with np.errstate(divide="ignore"):
+            z = np.log(r) + philox.gumbel(seed, philox.STREAM_TARGET, b, t, r.shape[0])
+        z32 = z.astype(np.float32)
+        out["tok"] = int(np.argmax(z32))
+        if r.shape[0] > 1:
+            order = np.argsort(z32.astype(np.float64), kind="stable")
+            out["runner_up"] = int(order[-2]) if order[-1] == out["tok"] else int(order[-1])
+            out["margin"] = float(z32[out["tok"]]) - float(z32[out["runner_up"]])
+    return out
 
 
 def top2_margin(y32: np.ndarray) -> float:
@@ -80,14 +116,16 @@ def prefill_whole_prompt(model, prompts, prompt_len):
 
 def generate(draft, target, verifier, prompts, prompt_len, n_gen, tau, temperature, seed,
              ctx_mode=CTX_OWN_HISTORY, forced=None, rows=None, keep_logits=False,
-             draft_caches=None, target_caches=None):
+             draft_caches=None, target_caches=None, reject_mode=REJECT_REPLACE):
     """Run n_gen lock-step decode steps.
 
     draft / target : objects with new_cache() and step(tokens, positions, caches) -> (hf, logits)
     verifier       : callable hf [M, d] -> float32 scores [M]
     rows           : the original batch indices of the given rows (they select the
                      random streams); default 0 .. B-1
-    forced         : None or dict(tok [B, G], accept [B, G]) for replay mode
+    forced         : None or dict(tok [B, G], accept [B, G][, draft_tok [B, G]]) for replay mode
+                     (draft_tok: the draft token the p/q correction of REJECT_SD is applied to)
+    reject_mode    : REJECT_REPLACE (the target's sample replaces the token) or REJECT_SD
     Returns a dict of per-step records (see the end of the function).
     """
     B = len(prompt_len)
@@ -106,6 +144,9 @@ def generate(draft, target, verifier, prompts, prompt_len, n_gen, tau, temperatu
                draft_margin=np.zeros((B, G)), target_margin=np.full((B, G), np.inf),
                rejected=[], target_positions=[[] for _ in range(B)],
                n_target_calls=np.zeros(B, np.int64))
+    if reject_mode == REJECT_SD:
+        rec.update(kept=np.zeros((B, G), np.uint8), coin=np.zeros((B, G)), log_ratio=np.zeros((B, G)),
+                   residual_margin=np.full((B, G), np.inf), residual_band=np.zeros((B, G)))
     if keep_logits:
         rec.update(draft_logits=[], draft_hidden=[], target_logits=[], target_hidden=[])
 
@@ -136,9 +177,23 @@ def generate(draft, target, verifier, prompts, prompt_len, n_gen, tau, temperatu
             hp, lp = target.step([seq[b][-1] for b in rej], [t[b] - 1 for b in rej],
                                  [target_caches[b] for b in rej])
             for i, b in enumerate(rej):
-                yb, y32 = philox.sample(lp[i], temperature, seed, philox.STREAM_TARGET, rows[b], t[b])
+                if reject_mode == REJECT_SD:
+                    x = int(rec["draft_tok"][b, g]) if forced is None or "draft_tok" not in forced \
+                        else int(np.asarray(forced["draft_tok"])[b, g])
+                    sd = sd_correction(lq[b], lp[i], x, temperature, seed, rows[b], t[b])
+                    yb = sd["tok"]
+                    rec["kept"][b, g], rec["coin"][b, g], rec["log_ratio"][b, g] = sd["kept"], sd["coin"], sd["log_ratio"]
+                    if not sd["kept"]:
+                        rec["residual_margin"][b, g] = sd["margin"]
+                        # sensitivity of ln(p_v - q_v) to an error of the two log-probabilities, winner + runner-up
+                        for v in (sd["tok"], sd["runner_up"]):
+                            if v >= 0:
+                                pv, qv = np.exp(sd["logp"][v]), np.exp(sd["logq"][v])
+                                rec["residual_band"][b, g] += (pv + qv) / max(pv - qv, 1e-300)
+                else:
+                    yb, y32 = philox.sample(lp[i], temperature, seed, philox.STREAM_TARGET, rows[b], t[b])
+                    rec["target_margin"][b, g] = top2_margin(y32)
                 rec["target_tok"][b, g] = yb
-                rec["target_margin"][b, g] = top2_margin(y32)
                 rec["target_positions"][b].append(t[b])
                 rec["n_target_calls"][b] += 1
         # 4./5. commit

@@ -225,6 +225,72 @@ def test_replace_mode_output_is_a_mixture_of_draft_and_target_laws():
         assert ((cnt - trials * other) ** 2 / (trials * other)).sum() > stats.chi2.ppf(0.9999, df=7)
 
 
+def test_eq_1_residual_and_acceptance_probability_by_hand():
+    """Sec. 2, Eq. (1) on numbers small enough to do by hand: q = (.5, .3, .2), p = (.2, .3, .5):
+    x = 0 is kept with probability .4, x = 1 and x = 2 always; the residual max(0, p - q) = (0, 0, .3)
+    normalises to a point mass on token 2."""
+    q, p = np.array([.5, .3, .2]), np.array([.2, .3, .5])
+    kept = {0: 0, 1: 0, 2: 0}
+    n = 4000
+    for t in range(n):
+        for x in (0, 1, 2):
+            sd = osp.sd_correction(np.log(q), np.log(p), x, 1.0, 99, 3, t)
+            assert abs(sd["log_ratio"] - np.log(p[x] / q[x])) < 1e-12
+            kept[x] += sd["kept"]
+            assert sd["tok"] == (x if sd["kept"] else 2)
+    assert kept[1] == n and kept[2] == n
+    assert abs(kept[0] / n - 0.4) < 4 * np.sqrt(0.24 / n)
+
+
+def test_sd_correction_returns_the_target_law_and_the_tv_acceptance_rate():
+    """The classic guarantee the rule is built for (Sec. 2): x ~ q, then the p/q coin and the residual
+    of Eq. (1), is distributed exactly as p; the token is kept with probability 1 - d_TV(p, q)
+    (Thm A.1 with a verifier that rejects everything).  Also at a temperature other than 1."""
+    rng = np.random.default_rng(5)
+    for T in (1.0, 0.7):
+        lq, lp = rng.normal(size=8), rng.normal(size=8) * 1.5
+        q, p = np.exp(osp.log_softmax(lq / T)), np.exp(osp.log_softmax(lp / T))
+        trials = 30000
+        cnt, kept = np.zeros(8), 0
+        for t in range(trials):
+            x, _ = philox.sample(lq, T, 17, philox.STREAM_DRAFT, 0, t)
+            sd = osp.sd_correction(lq, lp, x, T, 17, 0, t)
+            cnt[sd["tok"]] += 1
+            kept += sd["kept"]
+        assert ((cnt - trials * p) ** 2 / (trials * p)).sum() < stats.chi2.ppf(0.9999, df=7)
+        assert ((cnt - trials * q) ** 2 / (trials * q)).sum() > stats.chi2.ppf(0.9999, df=7)
+        tv = 0.5 * np.abs(p - q).sum()
+        assert abs(kept / trials - (1 - tv)) < 4 * np.sqrt(0.25 / trials)
+
+
+def test_sd_reject_mode_mixture_law_thm_3_1_and_acceptance_rate_thm_a_1():
+    """The loop with REJECT_SD and a verifier that accepts with probability a independently of the token:
+    the output law is (1 - a) p + a q (Thm 3.1 with eta_FP = a and no true positives to speak of) and a
+    draft token survives with probability 1 - (1 - a) d_TV(p, q) (Thm A.1).  With a = 0 (tau > 1) the
+    law is p itself."""
+    rng = np.random.default_rng(6)
+    lq, lp = rng.normal(size=8), rng.normal(size=8) * 1.5
+    q, p = np.exp(osp.log_softmax(lq)), np.exp(osp.log_softmax(lp))
+    tv = 0.5 * np.abs(p - q).sum()
+    trials = 30000
+    plen = np.full(trials, 1, dtype=np.int32)
+    prompts = np.zeros((trials, 1), dtype=np.int32)
+    for a in (0.65, 0.0):
+        coin = np.random.default_rng(9)
+        ver = lambda hf: (coin.random(hf.shape[0]) < a).astype(np.float32)
+        rec = osp.generate(_ToyModel(lq), _ToyModel(lp), ver, prompts, plen, 1, 0.5, 1.0, 23,
+                           reject_mode=osp.REJECT_SD)
+        cnt = np.bincount(rec["tok"][:, 0], minlength=8)
+        mix = a * q + (1 - a) * p
+        assert ((cnt - trials * mix) ** 2 / (trials * mix)).sum() < stats.chi2.ppf(0.9999, df=7)
+        survived = (rec["tok"][:, 0] == rec["draft_tok"][:, 0]).mean()
+        # (a token can also "survive" by being redrawn: the residual never returns a rejected x, so no)
+        assert abs(survived - (1 - (1 - a) * tv)) < 4 * np.sqrt(0.25 / trials)
+        rej = rec["accept"][:, 0] == 0
+        assert np.array_equal(rec["kept"][rej, 0] == 1, rec["tok"][rej, 0] == rec["draft_tok"][rej, 0])
+        assert np.array_equal(rec["n_target_calls"], rej.astype(np.int64))
+
+
 def test_compaction_brute_force():
     for B in range(1, 11):
         for m in range(1 << B):
