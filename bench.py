@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--target-ctx", choices=("own", "full"), default="own",
                     help="own: single-token target calls on the row's own history (the headline path); "
                          "full: the target first consumes the committed tokens it has not seen")
+    ap.add_argument("--reject-mode", choices=("replace", "sd"), default="replace",
+                    help="replace: the target's sample replaces a rejected token (the headline path); "
+                         "sd: keep it with probability min(1, p/q), else draw from the residual of Eq. (1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
@@ -131,7 +134,8 @@ def main():
     if need > lim:
         raise SystemExit(f"prompt {pmax} + warmup {Wm} + steps {K} exceeds the models' context {lim}")
     cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau,
-                  target_ctx_mode=W.CTX_FULL_PREFIX if args.target_ctx == "full" else W.CTX_OWN_HISTORY)
+                  target_ctx_mode=W.CTX_FULL_PREFIX if args.target_ctx == "full" else W.CTX_OWN_HISTORY,
+                  reject_mode=W.REJECT_SD if args.reject_mode == "sd" else W.REJECT_REPLACE)
 
     t0 = time.time()
     weights = W.make_weights(cfg)
@@ -186,7 +190,8 @@ def main():
         "config": {"workload": f"{cfg.name}: batch {B}, prompt {pmax}, tau {cfg.tau}, T {cfg.temperature}; "
                                f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
                                f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts"
-                               + ("; full-prefix target context" if cfg.target_ctx_mode == 1 else ""),
+                               + ("; full-prefix target context" if cfg.target_ctx_mode == 1 else "")
+                               + ("; p/q coin + residual on rejection" if cfg.reject_mode == 1 else ""),
                    "batch": B, "prompt_len": pmax},
         "target_calls_per_token": float(R.sum() / (B * K)),
         "steps_with_target_frac": float((R > 0).mean()),

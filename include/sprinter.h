@@ -85,7 +85,15 @@ typedef struct {
  *   brings one work-list entry per unseen token and the target pass runs over
  *   the list in chunks of at most max_batch (rounded up) entries.  In this
  *   mode sprinter_step does not produce target_logits / target_hidden (they
- *   must be NULL).  Other values are rejected. */
+ *   must be NULL).  Other values are rejected.
+ *   reject_mode 0 (replace): on a rejection the target's sample replaces the
+ *   draft token (Fig. 2(a)).  reject_mode 1 (p/q correction, Sec. 2 Eq. (1)
+ *   and the coin of Alg. 2): the draft token x is kept with probability
+ *   min(1, p(x)/q(x)) (coin: Philox stream 2 of the row and position),
+ *   otherwise the token is drawn from the normalised residual max(0, p - q)
+ *   (Gumbel-max with the target stream's noise); q and p are the softmax of
+ *   logits / temperature, so temperature must be > 0.  A rejected position
+ *   whose committed token equals its draft token was kept by the coin. */
 typedef struct {
   sprinter_model_cfg draft, target;
   int32_t ver_d_in, ver_d_hidden;
@@ -94,7 +102,7 @@ typedef struct {
   float tau, temperature;
   uint64_t seed;
   int32_t target_ctx_mode;
-  int32_t reserved;
+  int32_t reject_mode;
 } sprinter_cfg;
 
 /* Optional per-step outputs of sprinter_step; every field is a device pointer
@@ -127,7 +135,7 @@ typedef struct {
   int64_t steps_with_target;  /* steps in which at least one row was rejected */
   int64_t sum_rejected;       /* total target row-invocations = sum over steps of R */
   int32_t batch;
-  int32_t reserved;
+  int32_t coin_kept;          /* reject_mode 1: rejected positions whose draft token survived the p/q coin */
 } sprinter_stats;
 
 typedef struct sprinter_ctx sprinter_ctx;

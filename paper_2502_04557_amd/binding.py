@@ -30,7 +30,7 @@ class CfgC(C.Structure):
     _fields_ = [("draft", ModelCfgC), ("target", ModelCfgC), ("ver_d_in", C.c_int32), ("ver_d_hidden", C.c_int32),
                 ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("tau", C.c_float),
                 ("temperature", C.c_float), ("seed", C.c_uint64), ("target_ctx_mode", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("reject_mode", C.c_int32)]
 
 
 class StepOutC(C.Structure):
@@ -40,7 +40,7 @@ class StepOutC(C.Structure):
 
 class StatsC(C.Structure):
     _fields_ = [("steps", C.c_int64), ("steps_with_target", C.c_int64), ("sum_rejected", C.c_int64),
-                ("batch", C.c_int32), ("reserved", C.c_int32)]
+                ("batch", C.c_int32), ("coin_kept", C.c_int32)]
 
 
 _lib = None
@@ -88,7 +88,7 @@ def _model_c(m) -> ModelCfgC:
 
 def cfg_to_c(cfg) -> CfgC:
     return CfgC(_model_c(cfg.draft), _model_c(cfg.target), cfg.ver_d_in, cfg.ver_d_hidden, cfg.dtype,
-                cfg.max_batch, cfg.max_seq, cfg.tau, cfg.temperature, cfg.seed, cfg.target_ctx_mode, 0)
+                cfg.max_batch, cfg.max_seq, cfg.tau, cfg.temperature, cfg.seed, cfg.target_ctx_mode, getattr(cfg, "reject_mode", 0))
 
 
 def _ptr(t):
@@ -224,4 +224,4 @@ class Sprinter:
         calls = (C.c_int64 * max(self.B, 1))()
         self._check(self.lib.sprinter_get_stats(self.ctx, C.byref(st), calls), self.ctx)
         return dict(steps=st.steps, steps_with_target=st.steps_with_target, sum_rejected=st.sum_rejected,
-                    batch=st.batch, target_calls=np.array(calls[:self.B], dtype=np.int64))
+                    batch=st.batch, coin_kept=st.coin_kept, target_calls=np.array(calls[:self.B], dtype=np.int64))

@@ -81,6 +81,8 @@ struct sprinter_ctx {
   unsigned long long* host_counts = nullptr;   // pinned: [0] (ticket << 32) | rejected rows, written by the decide kernel
   unsigned ticket = 0;
   int *ent_off = nullptr, *t_last = nullptr;   // full-prefix mode: work-list prefix sums, last-entry flags of a chunk
+  int* coin_kept = nullptr;                    // reject_mode 1: counter, and the step's logits of both models
+  float *dl = nullptr, *tl = nullptr;
   // persistent decode kernel (bf16 mode)
   bool mega_on = false, mega_built = false;
   int mega_mt = 1, mega_grid = 0;
@@ -164,6 +166,8 @@ int validate_cfg(const sprinter_cfg* c, char* buf, size_t n) {
   if (!(c->tau == c->tau)) BAD("tau is NaN");
   if (c->target_ctx_mode != 0 && c->target_ctx_mode != 1)
     BAD("target_ctx_mode %d is not one of 0 (own history), 1 (full prefix)", c->target_ctx_mode);
+  if (c->reject_mode != 0 && c->reject_mode != 1) BAD("reject_mode %d is not one of 0 (replace), 1 (p/q correction)", c->reject_mode);
+  if (c->reject_mode == 1 && !(c->temperature > 0.f)) BAD("reject_mode 1 needs a temperature > 0");
   for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
     int dh = m->d_model / m->n_head, G = m->n_head / m->n_kv_head;
     size_t lds = (size_t)(G * dh + 2 * dh + 4 * G * dh + G * c->max_seq) * 4;
@@ -278,6 +282,12 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   st.hist = (int*)bump.take((size_t)c.max_batch * st.hist_stride * 4);
   int* ent_off = (int*)bump.take((size_t)(c.max_batch + 1) * 4);
   int* t_last = (int*)bump.take((size_t)rows * 4);
+  int* coin_kept = (int*)bump.take(4);
+  float *dl = nullptr, *tl = nullptr;
+  if (c.reject_mode == 1) {      // both models' logits of the step in flight
+    dl = (float*)bump.take((size_t)c.max_batch * c.draft.vocab * 4);
+    tl = (float*)bump.take((size_t)rows * c.target.vocab * 4);
+  }
   float* tau = (float*)bump.take(4);
   int* draft_tok = (int*)bump.take((size_t)c.max_batch * 4);
   float* score = (float*)bump.take((size_t)c.max_batch * 4);
@@ -334,7 +344,7 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
     ctx->ver_part = ver_part; ctx->ver_chunks = chunks; ctx->st = st; ctx->tau_dev = tau;
     ctx->draft_tok = draft_tok; ctx->score = score; ctx->accept = accept; ctx->rej_idx = rej_idx;
     ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows;
-    ctx->ent_off = ent_off; ctx->t_last = t_last;
+    ctx->ent_off = ent_off; ctx->t_last = t_last; ctx->coin_kept = coin_kept; ctx->dl = dl; ctx->tl = tl;
   }
   (void)scratch_begin; (void)scratch_end;
   return total;
@@ -558,7 +568,9 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
   hipStream_t s = ctx->stream;
   const int B = ctx->B;
   Model &dq = ctx->draft, &tp = ctx->target;
-  forward(ctx, dq, dq.rd(), B, true, 0u, out ? out->draft_logits : nullptr);
+  const bool sd = ctx->cfg.reject_mode == 1;
+  forward(ctx, dq, dq.rd(), B, true, 0u, sd ? ctx->dl : (out ? out->draft_logits : nullptr));
+  if (sd && out && out->draft_logits) launch_copy_f32(ctx->dl, out->draft_logits, dq.rd_n, dq.md.V, B, s);
   if (out && out->draft_hidden) launch_copy_f32(dq.sc.hf, out->draft_hidden, dq.rd_n, dq.md.d, B, s);
   launch_verifier_part(dq.sc.hf, dq.md.d, ctx->cfg.ver_d_hidden, (const float*)ctx->v_w1, (const float*)ctx->v_b1,
                        (const float*)ctx->v_w2, dq.rd_n, ctx->ver_part, B, s);
@@ -599,8 +611,20 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
     }
   }
   if (R < 0 || R > B) return fail(ctx, SPRINTER_E_HIP, "device reported %d rejected rows of %d", R, B);
+  SdArgs sa;
+  memset(&sa, 0, sizeof sa);
+  if (sd) {
+    sa.dl = ctx->dl; sa.tl = ctx->tl; sa.n_rows = tp.rd_n; sa.t_b = tp.rd_b; sa.t_pos = tp.rd_pos;
+    sa.draft_tok = ctx->draft_tok; sa.V = tp.md.V; sa.inv_temperature = 1.0f / ctx->cfg.temperature;
+    sa.seed_lo = (unsigned)(ctx->cfg.seed & 0xFFFFFFFFull); sa.seed_hi = (unsigned)(ctx->cfg.seed >> 32);
+    sa.committed = ctx->committed; sa.coin_kept = ctx->coin_kept;
+  }
   if (R > 0 && mode == 0) {
-    forward(ctx, tp, tp.rd(), R, true, 1u, out ? out->target_logits : nullptr);
+    forward(ctx, tp, tp.rd(), R, true, 1u, sd ? ctx->tl : (out ? out->target_logits : nullptr));
+    if (sd) {
+      launch_sd_correct(sa, R, s);
+      if (out && out->target_logits) launch_copy_f32(ctx->tl, out->target_logits, tp.rd_n, tp.md.V, R, s);
+    }
     if (out && out->target_hidden) launch_copy_f32(tp.sc.hf, out->target_hidden, tp.rd_n, tp.md.d, R, s);
   } else if (R > 0) {
     // full prefix: the work list (E entries, at least one per rejected row) goes through the target in chunks of
@@ -615,9 +639,14 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
       const int n = (int)std::min<long long>(ctx->rows_alloc, E - start);
       ca.start = (int)start; ca.n = n;
       launch_catchup_chunk(ca, s);
-      forward(ctx, tp, tp.rd(), n, true, 1u, nullptr, true);
-      launch_catchup_collect(tp.sc.am_part, tp.sc.n_lm_wg, ctx->rows_alloc, tp.rd_n, tp.rd_b, ctx->t_last, ctx->committed,
-                             n, s);
+      forward(ctx, tp, tp.rd(), n, true, 1u, sd ? ctx->tl : nullptr, true);
+      if (sd) {
+        sa.t_last = ctx->t_last;
+        launch_sd_correct(sa, n, s);
+      } else {
+        launch_catchup_collect(tp.sc.am_part, tp.sc.n_lm_wg, ctx->rows_alloc, tp.rd_n, tp.rd_b, ctx->t_last,
+                               ctx->committed, n, s);
+      }
     }
   }
   FinishArgs fa;
@@ -626,7 +655,7 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
   fa.n_rej = ctx->n_rej; fa.committed = ctx->committed;
   fa.d_n_rows = dq.rd_n; fa.d_b = dq.rd_b; fa.d_tok = dq.rd_tok; fa.d_pos = dq.rd_pos; fa.d_slot = dq.rd_slot;
   fa.o_committed = out ? out->committed_tok : nullptr;
-  fa.ctx_mode = mode;
+  fa.ctx_mode = mode; fa.pre_merged = (mode == 1 || sd) ? 1 : 0;
   fa.n_tokens = n_tokens; fa.g_tok = g_tok; fa.g_accept = g_accept; fa.g_score = g_score; fa.g_draft_tok = g_draft_tok;
   launch_step_finish(fa, s);
   return SPRINTER_OK;
@@ -716,7 +745,7 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     }
     // the persistent kernel is opt-in while the per-operation kernels are the faster path
     const char* on = getenv("SPRINTER_PERSISTENT");
-    if (on && on[0] == '1' && cfg->target_ctx_mode == 0) {
+    if (on && on[0] == '1' && cfg->target_ctx_mode == 0 && cfg->reject_mode == 0) {
       const int rows = ctx->rows_alloc;
       ctx->mega_mt = rows <= 16 ? 1 : rows <= 32 ? 2 : rows <= 64 ? 4 : 8;
       MegaParams& hp = ctx->mega_host;
@@ -837,6 +866,7 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
     forward(ctx, tp, dq.rd(), n_j, false, 1u, nullptr);
   }
   launch_prefill_finish(dev_prompt, max_prompt, B, ctx->st, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos, dq.rd_slot, s);
+  launch_set_i32(ctx->coin_kept, 0, s);
   ctx->prefilled = true;
   return hip_status(ctx, "sprinter_prefill");
 }
@@ -918,7 +948,9 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
   host_out->steps_with_target = c[1];
   host_out->sum_rejected = c[2];
   host_out->batch = ctx->B;
-  host_out->reserved = 0;
+  host_out->coin_kept = 0;
+  if (ctx->prefilled && hipMemcpy(&host_out->coin_kept, ctx->coin_kept, 4, hipMemcpyDeviceToHost) != hipSuccess)
+    return fail(ctx, SPRINTER_E_HIP, "copy of the coin counter failed");
   return SPRINTER_OK;
 }
 

@@ -139,7 +139,8 @@ struct FinishArgs {
   int* o_committed;
   // ... and [B, n_tokens] arrays indexed by the device-side generation counter (generate mode)
   int n_tokens; int* g_tok; unsigned char* g_accept; float* g_score; int* g_draft_tok;
-  int ctx_mode;   // 1: committed[] already holds the target's tokens, and a rejected row's target cache is complete afterwards
+  int ctx_mode;     // 1: a rejected row's target cache is complete afterwards
+  int pre_merged;   // 1: committed[] already holds the rejected rows' tokens (full-prefix collect / p-over-q correction)
 };
 void launch_step_finish(const FinishArgs& a, hipStream_t s);
 
@@ -153,6 +154,17 @@ void launch_catchup_chunk(const CatchupArgs& a, hipStream_t s);
 // After the chunk's forward: the sampled token of every last entry becomes the row's committed token.
 void launch_catchup_collect(const unsigned long long* am_part, int n_lm_wg, int Mpad, const int* n_rows, const int* t_b,
                             const int* t_last, int* committed, int max_rows, hipStream_t s);
+
+// Rejection by the p/q coin and the residual of Eq. (1): one workgroup per row of the target pass.
+struct SdArgs {
+  const float* dl;            // [batch rows][V] draft logits of the step
+  const float* tl;            // [pass rows][V] target logits of the pass
+  const int* n_rows; const int* t_b; const int* t_pos; const int* t_last;   // t_last may be NULL (every row counts)
+  const int* draft_tok; int V; float inv_temperature; unsigned seed_lo, seed_hi;
+  int* committed; int* coin_kept;
+};
+void launch_sd_correct(const SdArgs& a, int max_rows, hipStream_t s);
+void launch_set_i32(int* p, int v, hipStream_t s);
 
 void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const int* prompt_len,
                          int* n_rows, int* rb, int* rtok, int* rpos, int* rslot, hipStream_t s);

@@ -1492,7 +1492,7 @@ __global__ __launch_bounds__(1024) void k_step_finish(FinishArgs a) {
   const int B = a.B, R = *a.n_rej;
   if (tid < B) s_commit[tid] = a.committed[tid];
   __syncthreads();
-  if (a.ctx_mode == 0) {
+  if (!a.pre_merged) {
     for (int i = w; i < R; i += 16) {
       u64 k = merge_partials(a.am_part, a.n_lm_wg, a.Mpad, i, lane);
       if (lane == 0) s_commit[a.rej_idx[i]] = key_index(k);
@@ -1638,6 +1638,61 @@ void launch_catchup_collect(const unsigned long long* am_part, int n_lm_wg, int 
   hipLaunchKernelGGL(k_catchup_collect, dim3((max_rows + 3) / 4), dim3(256), 0, s, am_part, n_lm_wg, Mpad, n_rows, t_b,
                      t_last, committed);
 }
+
+// ===================================== rejection by p/q coin + residual (Sec. 2, Eq. (1))
+// One workgroup per row of the target pass.  q = softmax(draft logits / T), p = softmax(target logits / T):
+// three sweeps over the vocabulary (maxima, sums of exponentials, and - only if the coin rejects - the
+// Gumbel-max draw from max(0, p - q), on ln(p - q) + noise of the target stream).  float32 throughout.
+__global__ __launch_bounds__(256) void k_sd_correct(SdArgs a) {
+  __shared__ float s4[4];
+  __shared__ u64 s_key[4];
+  const int i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
+  if (i >= *a.n_rows) return;
+  if (a.t_last && !a.t_last[i]) return;
+  const int b = a.t_b[i], t = a.t_pos[i] + 1, x = a.draft_tok[b], V = a.V;
+  const float* __restrict__ lq = a.dl + (size_t)b * V;
+  const float* __restrict__ lp = a.tl + (size_t)i * V;
+  const float it = a.inv_temperature;
+  float mq = -INFINITY, mp = -INFINITY;
+  for (int v = tid; v < V; v += 256) { mq = fmaxf(mq, lq[v] * it); mp = fmaxf(mp, lp[v] * it); }
+  mq = block_max256(mq, s4);
+  mp = block_max256(mp, s4);
+  float sq = 0.f, sp = 0.f;
+  for (int v = tid; v < V; v += 256) { sq += expf(lq[v] * it - mq); sp += expf(lp[v] * it - mp); }
+  sq = block_sum256(sq, s4);
+  sp = block_sum256(sp, s4);
+  const float lse_q = mq + logf(sq), lse_p = mp + logf(sp);
+  const float log_ratio = (lp[x] * it - lse_p) - (lq[x] * it - lse_q);
+  const unsigned cw = philox_word(a.seed_lo, a.seed_hi, 2u, (unsigned)b, (unsigned)t, 0u);
+  const float coin = ((float)(cw >> 9) + 0.5f) * 1.1920928955078125e-07f;
+  const bool kept = coin <= fminf(1.0f, expf(log_ratio));       // uniform over the workgroup
+  if (kept) {
+    if (tid == 0) { a.committed[b] = x; atomicAdd(a.coin_kept, 1); }
+    return;
+  }
+  u64 best = 0;
+  for (int v = tid; v < V; v += 256) {
+    const float r = expf(lp[v] * it - lse_p) - expf(lq[v] * it - lse_q);
+    if (r > 0.f) {
+      const float z = logf(r) + gumbel_from_word(philox_word(a.seed_lo, a.seed_hi, 1u, (unsigned)b, (unsigned)t, (unsigned)v));
+      best = umax64(best, pack_key(z, (unsigned)v));
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) best = umax64(best, shfl_xor_u64(best, o));
+  if (lane == 0) s_key[w] = best;
+  __syncthreads();
+  if (tid == 0) {
+    best = umax64(umax64(s_key[0], s_key[1]), umax64(s_key[2], s_key[3]));
+    a.committed[b] = best ? key_index(best) : x;      // (an empty residual cannot occur when the coin rejects)
+  }
+}
+void launch_sd_correct(const SdArgs& a, int max_rows, hipStream_t s) {
+  hipLaunchKernelGGL(k_sd_correct, dim3(max_rows), dim3(256), 0, s, a);
+}
+
+__global__ void k_set_i32(int* p, int v) { *p = v; }
+void launch_set_i32(int* p, int v, hipStream_t s) { hipLaunchKernelGGL(k_set_i32, dim3(1), dim3(1), 0, s, p, v); }
 
 __global__ void k_set_f32(float* p, float v) { *p = v; }
 void launch_set_f32(float* p, float v, hipStream_t s) { hipLaunchKernelGGL(k_set_f32, dim3(1), dim3(1), 0, s, p, v); }

@@ -52,7 +52,8 @@ class Pair:
                           target_caches=osp.prefill_whole_prompt(self.target, pr, pl))
         return osp.generate(self.draft, self.target, self.verifier, pr, pl, n_gen,
                             cfg.tau if tau is None else tau, cfg.temperature, cfg.seed,
-                            ctx_mode=cfg.target_ctx_mode if ctx_mode is None else ctx_mode, forced=forced, rows=rows, keep_logits=keep_logits,
+                            ctx_mode=cfg.target_ctx_mode if ctx_mode is None else ctx_mode,
+                            reject_mode=cfg.reject_mode, forced=forced, rows=rows, keep_logits=keep_logits,
                             **caches)
 
     def gpu_generate(self, n_gen):
@@ -78,7 +79,7 @@ def close_enough(a, b, eps):
     return np.abs(a - b) <= eps * np.maximum(1.0, np.abs(b))
 
 
-def compare_replay(cfg, g, rec, rows=None, tau=None):
+def compare_replay(cfg, g, rec, rows=None, tau=None, check_target=True):
     """g: GPU outputs (tok, accept, score, draft_tok [B,G]); rec: oracle record replayed on the
     GPU's history.  Returns a report dict; raises AssertionError on an untolerated mismatch."""
     eps = eps_of(cfg)
@@ -109,10 +110,41 @@ def compare_replay(cfg, g, rec, rows=None, tau=None):
     # committed tokens: accepted -> the GPU's own draft token; rejected -> the target's sample
     acc = ga.astype(bool)
     assert np.array_equal(gt[acc], gd[acc])
+    rep["n"] = int(ga.size)
+    rep["reject_rate"] = float(1 - ga.mean())
+    if not check_target:
+        return rep
     bad = (~acc) & (gt != rec["target_tok"])
     near = rec["target_margin"] <= 2 * eps / T
     rep["target_tok_flips_tolerated"] = int(bad.sum())
     assert not (bad & ~near).any(), f"target token mismatch outside the band at {np.argwhere(bad & ~near)[:5]}"
     rep["n"] = int(ga.size)
     rep["reject_rate"] = float(1 - ga.mean())
+    return rep
+
+
+def compare_sd(cfg, g, rec):
+    """reject_mode 1: the committed tokens of the rejected positions.  g: GPU outputs [B, G]; rec: the oracle
+    replayed on the GPU's history (forced tok, accept and draft_tok).
+      coin     a kept / not-kept mismatch is tolerated iff |ln coin - ln(p(x)/q(x))| <= 4 eps / T (four
+               logit-sized quantities enter the ratio, each within eps / T)
+      residual a token mismatch is tolerated iff the oracle's top-2 margin of ln(p - q) + noise is within
+               (2 eps / T) * sum over the two candidates of (p + q) / (p - q)   (error of ln(p - q))
+    """
+    eps = eps_of(cfg)
+    T = cfg.temperature
+    rej = g["accept"] == 0
+    kept_g = rej & (g["tok"] == g["draft_tok"])
+    kept_o = rej & (rec["kept"] == 1)
+    with np.errstate(divide="ignore"):                      # (coin is 0 where the verifier accepted)
+        near_coin = np.abs(np.log(rec["coin"]) - rec["log_ratio"]) <= 4 * eps / T
+    bad = kept_g != kept_o
+    rep = dict(rejected=int(rej.sum()), kept=int(kept_g.sum()), coin_flips_tolerated=int(bad.sum()))
+    assert not (bad & ~near_coin).any(), f"p/q coin decision differs outside the band at {np.argwhere(bad & ~near_coin)[:5]}"
+    both = rej & ~kept_g & ~kept_o
+    bad = both & (g["tok"] != rec["target_tok"])
+    near = rec["residual_margin"] <= (2 * eps / T) * rec["residual_band"]
+    rep["residual_flips_tolerated"] = int(bad.sum())
+    rep["residual_draws"] = int(both.sum())
+    assert not (bad & ~near).any(), f"residual draw differs outside the band at {np.argwhere(bad & ~near)[:5]}"
     return rep

@@ -67,6 +67,8 @@ def test_config_validation(lib):
         (replace(base, max_seq=4096), "max_pos"),
         (replace(base, dtype=7), "dtype"),
         (replace(base, target_ctx_mode=2), "target_ctx_mode"),
+        (replace(base, reject_mode=2), "reject_mode"),
+        (replace(base, reject_mode=1, temperature=0.0), "temperature"),
         (replace(base, temperature=-1.0), "temperature"),
         (replace(base, draft=replace(base.draft, arch=5)), "arch"),
         (replace(base, draft=replace(base.draft, d_ff=643)), "multiples of 8"),

@@ -156,6 +156,39 @@ def test_full_prefix_target_context(kind, dtype):
     p.close()
 
 
+@pytest.mark.parametrize("kind,dtype,ctx", [("gpt", W.DT_F32, 0), ("llama", W.DT_F32, 0), ("gpt", W.DT_BF16, 0),
+                                            ("llama", W.DT_BF16, 0), ("llama", W.DT_F32, 1), ("gpt", W.DT_BF16, 1)])
+def test_reject_by_coin_and_residual(kind, dtype, ctx):
+    """reject_mode 1 (Sec. 2, Eq. (1); the coin of Alg. 2): a rejected draft token is kept with probability
+    min(1, p(x)/q(x)), else the token is drawn from the normalised max(0, p - q).  Replay against the oracle
+    on the GPU's history, in both target-context modes; fp32 free-runs must be identical."""
+    from dataclasses import replace
+    from parity_util import compare_replay, compare_sd
+    G = 16
+    cfg = replace(W.mini_config(kind, dtype, n_gen=G), reject_mode=W.REJECT_SD, target_ctx_mode=ctx)
+    p = _pair(cfg, ver_scale=8.0)
+    g, st = p.gpu_generate(G)
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]))
+    rep = compare_replay(cfg, g, rec, check_target=False)
+    rep.update(compare_sd(cfg, g, rec))
+    print(kind, dtype, ctx, rep, flush=True)
+    # both branches of the rule occur, and the counter agrees with the outputs
+    assert rep["kept"] > 0 and rep["residual_draws"] > 0
+    assert st["coin_kept"] == rep["kept"] and st["sum_rejected"] == rep["rejected"]
+    if dtype == W.DT_F32:
+        free = p.oracle(G)
+        for k in ("tok", "accept", "draft_tok"):
+            assert np.array_equal(free[k], g[k]), k
+    # a second run gives the same bits, and the replace rule gives other tokens on these models
+    g2, _ = p.gpu_generate(G)
+    assert np.array_equal(g2["tok"], g["tok"])
+    p.close()
+    p0 = _pair(replace(cfg, reject_mode=W.REJECT_REPLACE), ver_scale=8.0)
+    g0, st0 = p0.gpu_generate(G)
+    assert not np.array_equal(g0["tok"], g["tok"]) and st0["coin_kept"] == 0
+    p0.close()
+
+
 def test_greedy_temperature_zero():
     from dataclasses import replace
     cfg = replace(W.mini_config("llama", W.DT_F32, n_gen=8), temperature=0.0)
@@ -231,14 +264,19 @@ def test_c2_full_prefix_sampled_rows():
     test_c2_full_size_sampled_rows(W.CTX_FULL_PREFIX)
 
 
-def test_c2_full_size_sampled_rows(ctx_mode=W.CTX_OWN_HISTORY):
+def test_c2_coin_and_residual_sampled_rows():
+    """Config 2 at full size with the p/q correction on rejection (vocabulary 50257)."""
+    test_c2_full_size_sampled_rows(W.CTX_OWN_HISTORY, W.REJECT_SD)
+
+
+def test_c2_full_size_sampled_rows(ctx_mode=W.CTX_OWN_HISTORY, reject_mode=W.REJECT_REPLACE):
     """Config 2 at its full size and in the launch configuration the benchmark times
     (GPT-2-small/XL shapes, bf16, batch 16, 128-token Zipf prompts): the oracle replays
     a sample of rows (first, last, two seeded) over the first steps on the GPU's history."""
     import time
     from parity_util import compare_replay
     from dataclasses import replace
-    cfg = replace(W.config("c2"), target_ctx_mode=ctx_mode)
+    cfg = replace(W.config("c2"), target_ctx_mode=ctx_mode, reject_mode=reject_mode)
     t0 = time.time()
     p = _pair(cfg)
     print(f"c2 built in {time.time() - t0:.0f} s", flush=True)
@@ -247,8 +285,13 @@ def test_c2_full_size_sampled_rows(ctx_mode=W.CTX_OWN_HISTORY):
     print(f"gpu done, reject rate {1 - g['accept'].mean():.3f}, steps_with_target {st['steps_with_target']}", flush=True)
     rng = np.random.default_rng(7)
     rows = sorted({0, cfg.batch - 1, *rng.choice(np.arange(1, cfg.batch - 1), 2, replace=False).tolist()})
-    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"]), rows=rows, whole_prompt_prefill=True)
-    rep = compare_replay(cfg, g, rec, rows=rows)
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]), rows=rows,
+                   whole_prompt_prefill=True)
+    rep = compare_replay(cfg, g, rec, rows=rows, check_target=reject_mode == W.REJECT_REPLACE)
+    if reject_mode == W.REJECT_SD:
+        from parity_util import compare_sd
+        rep.update(compare_sd(cfg, {k: v[rows] for k, v in g.items()}, rec))
+        assert st["coin_kept"] == int(((g["accept"] == 0) & (g["tok"] == g["draft_tok"])).sum())
     print("c2 rows", rows, rep, f"total {time.time() - t0:.0f} s", flush=True)
     # properties that hold for every row at any size
     assert np.array_equal(g["accept"], (g["score"] >= np.float32(cfg.tau)).astype(np.uint8))

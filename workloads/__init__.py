@@ -11,7 +11,7 @@ is available here, so the generators below produce random-init weights of the
 same shapes and i.i.d. token-id prompts (uniform or Zipf) that stand in for them.
 """
 from .configs import (ModelCfg, SprinterCfg, ARCH_GPT, ARCH_LLAMA, DT_F32, DT_BF16,
-                      CTX_OWN_HISTORY, CTX_FULL_PREFIX, config, mini_config, CONFIG_NAMES)
+                      CTX_OWN_HISTORY, CTX_FULL_PREFIX, REJECT_REPLACE, REJECT_SD, config, mini_config, CONFIG_NAMES)
 from .synth import (round_bf16, make_model_weights, make_verifier_weights,
                     make_weights, make_prompts, zipf_probs, model_weight_shapes,
                     verifier_weight_shapes)

@@ -8,6 +8,8 @@ ARCH_LLAMA = 1   # RMSNorm, no biases, RoPE (rotate-half), SwiGLU, untied LM hea
 DT_F32 = 0
 DT_BF16 = 1
 CTX_OWN_HISTORY = 0   # target cache = prompt + one entry per earlier target call
+REJECT_REPLACE = 0    # the target's sample replaces a rejected token
+REJECT_SD = 1         # keep it with probability min(1, p/q), else draw from the residual max(0, p - q)
 CTX_FULL_PREFIX = 1   # the target first consumes the committed tokens it has not seen
 
 
@@ -45,6 +47,7 @@ class SprinterCfg:
     temperature: float = 1.0
     seed: int = 0
     target_ctx_mode: int = CTX_OWN_HISTORY
+    reject_mode: int = 0
     # workload description (not part of the C struct)
     name: str = ""
     batch: int = 1
