@@ -66,6 +66,22 @@ def algorithmic_bytes(cfg, plen, accept, first_step, seen_before=None):
     return per_step, R
 
 
+def measured_traffic(cfg):
+    """HBM bytes per decode step from hardware counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known
+    size), collected offline with the native runner on this very workload: profiles/decode_step_c2_hbm_traffic.txt
+    holds the commands and the per-kernel table.  Only the default c2 workload has been measured."""
+    if cfg.name != "c2" or cfg.target_ctx_mode != 0 or cfg.reject_mode != 0:
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "decode_step_c2_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_step"):
+                return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, weights, n_rows, max_seconds=15.0, max_steps=64):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -197,7 +213,7 @@ def main():
         "steps_with_target_frac": float((R > 0).mean()),
         "avg_accepted_run": float(accept.sum() / max(1, (accept == 0).sum())),
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(cfg),
                      "kernel": "one decode step (all kernels of sprinter_step)",
                      "bytes_per_launch": float(per_step_bytes.mean()), "ms_per_launch": step_ms},
     }

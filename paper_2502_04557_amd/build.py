@@ -7,6 +7,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsprinter.so")
+NATIVE_BENCH = os.path.join(PKG, "native_bench")
 SOURCES = ["kernels.hip", "mega.hip", "mega16.hip", "abi.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are kept off on the test machines
@@ -36,6 +37,9 @@ def build_library(verbose: bool = True) -> str:
     with ThreadPoolExecutor(max_workers=len(cmds)) as ex:
         list(ex.map(lambda c: _run(c, verbose), cmds))
     _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], verbose)
+    # the Python-free runner of dumped workloads (hardware-counter runs); it only uses the public C ABI
+    _run(["hipcc", *FLAGS, "-x", "hip", os.path.join(CSRC, "native_bench.cpp"), "-L" + PKG, "-lsprinter",
+          "-Wl,-rpath,$ORIGIN", "-o", NATIVE_BENCH], verbose)
     return LIB
 
 

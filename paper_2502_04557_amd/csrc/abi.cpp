@@ -864,6 +864,10 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
                         dq.rd_slot, s);
     forward(ctx, dq, dq.rd(), n_j, false, 0u, nullptr);
     forward(ctx, tp, dq.rd(), n_j, false, 1u, nullptr);
+    // A long prompt would otherwise leave hundreds of thousands of launches queued (c2: 860 per position);
+    // profiling tools that keep per-dispatch state have died on such a backlog.  Draining every 4 positions
+    // costs nothing measurable.
+    if ((j & 3) == 3 && hipStreamSynchronize(s) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
   }
   launch_prefill_finish(dev_prompt, max_prompt, B, ctx->st, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos, dq.rd_slot, s);
   launch_set_i32(ctx->coin_kept, 0, s);
