@@ -254,6 +254,42 @@ def test_single_token_prompt_and_full_batch():
     p.close()
 
 
+@pytest.mark.parametrize("ctx,rej", [(0, 0), (1, 1)])
+def test_maximum_batch(ctx, rej):
+    """The largest batch the library accepts (1024 rows; the decide / finish kernels then use all 16 waves of
+    their single workgroup, the GEMMs 16 passes of 64 rows) on the smallest models: compaction against the
+    brute-force list for every step, whole-batch rules, and the oracle on the first, the last and 6 seeded rows.
+    Second case: the same with the full-prefix target context and the p/q correction."""
+    from dataclasses import replace
+    from parity_util import compare_replay, compare_sd
+    G = 6
+    cfg = replace(W.mini_config("linear", W.DT_BF16, n_gen=G), batch=1024, max_batch=1024, target_ctx_mode=ctx,
+                  reject_mode=rej)
+    p = _pair(cfg, ver_scale=8.0)
+    assert len(p.plen) == 1024
+    outs, st = p.gpu_steps(G, debug=False)
+    g = {k: np.stack([o[k2] for o in outs], axis=1) for k, k2 in
+         (("tok", "committed_tok"), ("accept", "accept"), ("score", "score"), ("draft_tok", "draft_tok"))}
+    for o in outs:
+        R = int(o["n_rej"][0])
+        want = np.flatnonzero(o["accept"] == 0)
+        assert R == len(want) and np.array_equal(o["rej_idx"][:R], want)
+    acc = g["accept"].astype(bool)
+    assert np.array_equal(g["accept"], (g["score"] >= np.float32(cfg.tau)).astype(np.uint8))
+    assert np.array_equal(g["tok"][acc], g["draft_tok"][acc])
+    assert np.array_equal(st["target_calls"], (~acc).sum(1)) and st["sum_rejected"] == int((~acc).sum())
+    assert 0.1 < 1 - acc.mean() < 0.9 and (~acc).sum(0).max() > 64         # several 64-row passes in the target
+    rows = sorted({0, 1023, *np.random.default_rng(3).choice(np.arange(1, 1023), 6, replace=False).tolist()})
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]), rows=rows)
+    rep = compare_replay(cfg, g, rec, rows=rows, check_target=rej == 0)
+    if rej:
+        rep.update(compare_sd(cfg, {k: v[rows] for k, v in g.items()}, rec))
+    print("batch 1024", ctx, rej, rep, flush=True)
+    g2, _ = p.gpu_generate(G)
+    assert np.array_equal(g2["tok"], g["tok"])
+    p.close()
+
+
 def test_c2_persistent_kernel_sampled_rows(persistent_kernel):
     """Config 2 at full size through the opt-in persistent kernel."""
     test_c2_full_size_sampled_rows()

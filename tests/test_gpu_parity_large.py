@@ -79,8 +79,9 @@ def _replay_segments(side, g, rows, settings):
     (tau, b2): the threshold and the verifier's output bias in force at that step; consecutive
     steps with the same setting are replayed in one oracle call, the caches carry over."""
     from oracle import model as om, sprinter as osp
-    from parity_util import compare_replay
+    from parity_util import compare_replay, compare_sd
     cfg = side.cfg
+    sd = cfg.reject_mode == W.REJECT_SD
     G = len(settings)
     pr, pl = side.prompts[rows], side.plen[rows]
     t = time.time()
@@ -108,12 +109,16 @@ def _replay_segments(side, g, rows, settings):
             prm[i, :len(q)] = q
         pln = np.array([len(q) for q in seqs], np.int32)
         gs = {k: v[:, g0:g1] for k, v in g.items()}
-        forced = dict(tok=gs["tok"][rows], accept=gs["accept"][rows])
+        forced = dict(tok=gs["tok"][rows], accept=gs["accept"][rows], draft_tok=gs["draft_tok"][rows])
         rec = osp.generate(side.draft, side.target, om.Verifier(vw), prm, pln, g1 - g0, tau, cfg.temperature, cfg.seed,
+                           ctx_mode=cfg.target_ctx_mode, reject_mode=cfg.reject_mode,
                            forced=forced, rows=rows, draft_caches=dc, target_caches=tc)
-        rep = compare_replay(cfg, gs, rec, rows=rows, tau=tau)
-        for k in ("flag_flips_tolerated", "draft_tok_flips_tolerated", "target_tok_flips_tolerated", "n"):
-            tot[k] += rep[k]
+        rep = compare_replay(cfg, gs, rec, rows=rows, tau=tau, check_target=not sd)
+        if sd:
+            rep.update(compare_sd(cfg, {k: v[rows] for k, v in gs.items()}, rec))
+        for k in ("flag_flips_tolerated", "draft_tok_flips_tolerated", "target_tok_flips_tolerated", "n",
+                  "kept", "residual_draws", "coin_flips_tolerated", "residual_flips_tolerated"):
+            tot[k] = tot.get(k, 0) + rep.get(k, 0)
         tot["max_score_diff"] = max(tot["max_score_diff"], rep["max_score_diff"])
         tot["rejected"] += int((forced["accept"] == 0).sum())
         for i in range(len(rows)):
@@ -147,13 +152,15 @@ def llama7b():
     del weights, models
 
 
-def test_c3_full_size_sampled_rows(llama7b):
+@pytest.mark.parametrize("ctx,rej", [(W.CTX_OWN_HISTORY, W.REJECT_REPLACE), (W.CTX_FULL_PREFIX, W.REJECT_SD)])
+def test_c3_full_size_sampled_rows(llama7b, ctx, rej):
     """Config 3: batch 32, 256-token Zipf prompts, 2-layer draft / 32-layer d=4096 target.
     Eight steps with the workload's own verifier (which rejects about 1 % at this size), then
     eight with its output bias shifted to a 40 % reject rate so that the target path is
-    exercised on the sampled rows too."""
+    exercised on the sampled rows too.  Second case: the full-prefix target context together with the
+    p/q correction (after eight almost rejection-free steps the first work lists are long)."""
     weights, models = llama7b
-    cfg = replace(W.config("c3"), max_seq=320)
+    cfg = replace(W.config("c3"), max_seq=320, target_ctx_mode=ctx, reject_mode=rej)
     s = Side(cfg, weights, models)
     n1, n2 = 8, 8
     t = time.time()
@@ -171,6 +178,8 @@ def test_c3_full_size_sampled_rows(llama7b):
              f"{1 - o1['accept'].mean():.3f} then {1 - o2['accept'].mean():.3f}")
     _whole_batch_properties(g, st, cfg.tau, cfg.draft.vocab)
     assert 0.2 < 1 - o2["accept"].mean() < 0.6
+    if rej == W.REJECT_SD:
+        assert st["coin_kept"] == int(((g["accept"] == 0) & (g["tok"] == g["draft_tok"])).sum())
     rng = np.random.default_rng(3)
     rows = sorted({0, cfg.batch - 1, int(rng.integers(1, cfg.batch - 1))})
     tot = _replay_segments(s, g, rows, [(cfg.tau, b2_0)] * n1 + [(cfg.tau, b2)] * n2)
