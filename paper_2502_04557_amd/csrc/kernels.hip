@@ -700,7 +700,9 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   // cost more than the 4 us they save; and a variant that requests all of a wave's weight and activation
   // tiles up front (K <= 2048) - no faster.)
   // 17 .. 64 rows: 2, 3 or 4 row tiles per pass with double-buffered loads; more rows take further passes.
-  if (max_rows <= 16 && a.n_tiles >= 256)      // wide outputs: two column tiles per wave share the activation fragments
+  // wide outputs with a short K: two column tiles per wave share the activation fragments (at K = 4096 one tile per
+  // workgroup is faster: QKV 12288x4096 26 against 32 us, FFN-up 2x11008x4096 40 against 48 us)
+  if (max_rows <= 16 && a.n_tiles >= 256 && a.Kt < 100)
     hipLaunchKernelGGL((k_gemm_bf16<1, 2, 8, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
   else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
   else {
@@ -754,7 +756,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
   a.part = part; a.part_stride = part_stride;
   if (max_rows <= 16) {
     // shares: fill the 256 compute units, at least 12 k tiles per share; long K takes two column tiles per wave
-    const bool two = a.Kt >= 128 && a.n_tiles >= 64;
+    const bool two = a.Kt >= 192 && a.n_tiles >= 64;   // (4096x4096: 8.2 us with one tile, 10.5 with two; 4096x11008: 24.1 / 19.8)
     const int groups = two ? (a.n_tiles + 1) / 2 : a.n_tiles;
     int sk = std::min(4, 256 / groups);              // (4: the norm kernel's smaller partial-sum variant)
     if (sk > max_shares) sk = max_shares;
