@@ -710,7 +710,7 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
     const int passes = (max_rows + 63) / 64;
     const int mt = max_rows <= 32 ? 2 : max_rows <= 48 ? 3 : 4;
     constexpr bool DUAL = EPI == EPI_SWIGLU;
-    const int ntw = (!DUAL && mt > 2 && a.n_tiles / 4 >= 192) ? 4 : (a.n_tiles / 2 >= (DUAL || mt == 2 ? 256 : 128)) ? 2 : 1;
+    const int ntw = (!DUAL && mt > 2 && a.n_tiles / 4 >= 192) ? 4 : (a.n_tiles / 2 >= (DUAL ? 256 : 128)) ? 2 : 1;
     const dim3 grid((a.n_tiles + ntw - 1) / ntw, passes, 1);
 #define SPRINTER_ROWS(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI>), grid, dim3(512), 0, s, a)
     if (ntw == 4) { if (mt == 3) SPRINTER_ROWS(3, 4); else SPRINTER_ROWS(4, 4); }
@@ -962,8 +962,12 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   bf16_t* __restrict__ Vc = (bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   const int n_blocks = (slot + KPW - 1) / KPW;                 // blocks of cached keys
   const int n_rounds = (n_blocks + 4 * NB - 1) / (4 * NB);
-  uint4 kb[NB], vb[NB];
-  auto request = [&](int rd) {                                 // clamped addresses, no branches
+  // Two register buffers where the registers are there (head dimension 128, at most 2 query heads per KV head): the
+  // keys and values of round rd + 1 are in flight while round rd is consumed (c4's step 15.5 -> 14.5 ms).  With more
+  // query heads or 64-wide heads the second buffer costs occupancy and measured slower (c5's draft 38.6 -> 45.5 us).
+  constexpr bool TWO_BUFFERS = DH == 128 && G <= 2;
+  uint4 kA[NB], vA[NB], kB[TWO_BUFFERS ? NB : 1], vB[TWO_BUFFERS ? NB : 1];
+  auto request = [&](uint4* kb, uint4* vb, int rd) {           // clamped addresses, no branches
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int key = min(((rd * NB + j) * 4 + w) * KPW + kin, max(slot - 1, 0));
@@ -971,7 +975,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
       vb[j] = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * 8);
     }
   };
-  request(0);
+  request(kA, vA, 0);
   // query heads, new key and new value: this lane's 8 elements (and their rotary partners)
   const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
   const float* __restrict__ cs = a.rope + (size_t)r * DH;
@@ -1042,8 +1046,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
   }
-  for (int rd = 0; rd < n_rounds; ++rd) {
-    if (rd > 0) request(rd);
+  auto consume = [&](const uint4* kb, const uint4* vb, int rd) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int key = ((rd * NB + j) * 4 + w) * KPW + kin;
@@ -1068,6 +1071,23 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vf[e];
       }
+    }
+  };
+  if constexpr (TWO_BUFFERS) {
+    for (int rd = 0; rd < n_rounds; rd += 2) {    // (a round beyond the last one consumes nothing: all its keys are masked)
+      request(kB, vB, rd + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(kA, vA, rd);
+      __builtin_amdgcn_sched_barrier(0);
+      request(kA, vA, rd + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(kB, vB, rd + 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+    for (int rd = 0; rd < n_rounds; ++rd) {
+      if (rd > 0) request(kA, vA, rd);
+      consume(kA, vA, rd);
     }
   }
   // merge the KPW lane groups of the wave
