@@ -5,7 +5,7 @@
 
 A "step" is one pass of the whole hot path over the batch: draft forward, sample,
 verifier, compaction, target forward on the rejected rows, scatter-back.  The
-workload is BASELINE config 2 (GPT-2-small/XL-shaped pair, bf16, batch 16, 128-token
+workload is configuration 2 of the five (GPT-2-small/XL-shaped pair, bf16, batch 16, 128-token
 Zipf prompts, threshold 0.5) with synthetic random-init weights.  Prints one JSON line.
 """
 from __future__ import annotations

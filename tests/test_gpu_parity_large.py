@@ -21,14 +21,16 @@ _T0 = time.time()
 
 
 def progress(msg):
-    """A line that survives pytest's capture: long legs must show that they are alive."""
+    """A line that survives pytest's capture: long legs must show that they are alive.  Also appended to the
+    file named by SPRINTER_PROGRESS_LOG, if set."""
     line = f"[{time.time() - _T0:7.1f} s] {msg}\n"
-    try:
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "test_progress.log"), "a") as f:
-            f.write(line)
-    except OSError:
-        pass
+    path = os.environ.get("SPRINTER_PROGRESS_LOG")
+    if path:
+        try:
+            with open(path, "a") as f:
+                f.write(line)
+        except OSError:
+            pass
     try:
         sys.__stderr__.write(line)
         sys.__stderr__.flush()
