@@ -170,7 +170,8 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
                           const void* const* dev_ptrs, const int64_t* shapes, int n);
 
 /* Starts B rows: resets state and counters and fills both KV caches with
- * positions 0 .. P_b-2 of each prompt; the first decode step then feeds the last
+ * positions 0 .. P_b-2 of each prompt (one pass of the decode kernels per position,
+ * the stream is drained every 4 positions); the first decode step then feeds the last
  * prompt token at position P_b-1.  dev_prompt is [B, max_prompt] int32 (padding
  * is never read), host_prompt_len[B] has 1 <= P_b <= max_prompt.  Errors:
  * B > max_batch, P_b out of range, max_prompt > max_seq (or > max_pos), weights
@@ -179,12 +180,18 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
                      int B, int max_prompt);
 
 /* One decode step for all rows (the steps listed at the top).  out may be NULL.
- * Error if no prefill was done or a row would exceed max_seq / max_pos. */
+ * Error if no prefill was done or a row would exceed max_seq / max_pos.
+ * The calling thread waits inside the call (a few microseconds of polling on a
+ * pinned word the decide kernel writes) until the device has counted the rejected
+ * rows, then launches the target pass for exactly that many rows - or none.  The
+ * rest of the step is only enqueued.  The call can therefore not be recorded into
+ * a HIP graph, and two threads must not drive one context at the same time. */
 int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out);
 
-/* n_tokens decode steps back to back without host synchronisation.  Outputs are
- * [B, n_tokens] row-major device arrays; any of them may be NULL:
- * committed tokens, accept flags, verifier scores, draft tokens. */
+/* n_tokens decode steps back to back (each with the short wait described at
+ * sprinter_step; no stream synchronisation).  Outputs are [B, n_tokens] row-major
+ * device arrays; any of them may be NULL: committed tokens, accept flags, verifier
+ * scores, draft tokens.  The last step's tail is still running when the call returns. */
 int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uint8_t* dev_out_accept,
                       float* dev_out_score, int32_t* dev_out_draft_tok);
 
