@@ -947,12 +947,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 // and the new key by one pass through LDS: a single block-wide synchronisation.
 //   lane = kin * LPK + chunk: LPK = DH / 8 lanes share one key (8 elements each), a wave-wide
 //   16-byte load covers KPW = 64 / LPK consecutive keys; wave w takes key blocks w, w + 4, ...
-template <int DH, int G>
-__global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
+template <int DH, int G, int NW>
+__global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
   constexpr int LPK = DH / 8, KPW = 64 / LPK, HALF = DH / 2;
   constexpr int NB = (G <= 4 && DH == 64) ? 8 : 4;       // key blocks held in registers per round and wave
   constexpr float NEG = -1e30f;
-  __shared__ float s_m[4][G], s_l[4][G], s_o[4][G][DH], s_vnew[DH], s_snew[G];
+  __shared__ float s_m[NW][G], s_l[NW][G], s_o[NW][G][DH], s_vnew[DH], s_snew[G];
   const int r = blockIdx.y;
   if (r >= *a.rd.n_rows) return;
   const int kvh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
@@ -961,7 +961,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   bf16_t* __restrict__ Kc = (bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   bf16_t* __restrict__ Vc = (bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   const int n_blocks = (slot + KPW - 1) / KPW;                 // blocks of cached keys
-  const int n_rounds = (n_blocks + 4 * NB - 1) / (4 * NB);
+  const int n_rounds = (n_blocks + NW * NB - 1) / (NW * NB);
   // Two register buffers where the registers are there (head dimension 128, at most 2 query heads per KV head): the
   // keys and values of round rd + 1 are in flight while round rd is consumed (c4's step 15.5 -> 14.5 ms).  With more
   // query heads or 64-wide heads the second buffer costs occupancy and measured slower (c5's draft 38.6 -> 45.5 us).
@@ -970,7 +970,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   auto request = [&](uint4* kb, uint4* vb, int rd) {           // clamped addresses, no branches
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      const int key = min(((rd * NB + j) * 4 + w) * KPW + kin, max(slot - 1, 0));
+      const int key = min(((rd * NB + j) * NW + w) * KPW + kin, max(slot - 1, 0));
       kb[j] = *reinterpret_cast<const uint4*>(Kc + (size_t)key * DH + chunk * 8);
       vb[j] = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * 8);
     }
@@ -1049,7 +1049,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
   auto consume = [&](const uint4* kb, const uint4* vb, int rd) {
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      const int key = ((rd * NB + j) * 4 + w) * KPW + kin;
+      const int key = ((rd * NB + j) * NW + w) * KPW + kin;
       const bool valid = key < slot;
       const bf16_t* kt = reinterpret_cast<const bf16_t*>(&kb[j]);
       const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vb[j]);
@@ -1110,17 +1110,17 @@ __global__ __launch_bounds__(256) void k_attn_bf16(AttnArgs a) {
     }
   }
   __syncthreads();
-  // merge the 4 waves and the new key; one output element per thread and pass
+  // merge the NW waves and the new key; one output element per thread and pass
   bf16_t* __restrict__ ao = (bf16_t*)a.ao;
-  for (int idx = tid; idx < G * DH; idx += 256) {
+  for (int idx = tid; idx < G * DH; idx += NW * 64) {
     const int g = idx / DH, i = idx % DH;
     const float sn = s_snew[g];
     float mn = sn;
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) mn = fmaxf(mn, s_m[q4][g]);
+    for (int q4 = 0; q4 < NW; ++q4) mn = fmaxf(mn, s_m[q4][g]);
     float den = __expf(sn - mn), num = den * s_vnew[i];
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
+    for (int q4 = 0; q4 < NW; ++q4) {
       const float c = __expf(s_m[q4][g] - mn);
       den += c * s_l[q4][g];
       num += c * s_o[q4][g][i];
@@ -1135,13 +1135,19 @@ static size_t attn_smem_bytes(int DH, int G, int max_seq) {
 
 template <int DH>
 static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, hipStream_t s) {
-  dim3 grid(a.KVH, max_rows), block(256);
+  // NW = waves per workgroup that share one (row, KV head)'s keys: 8 while the launch has fewer workgroups than
+  // the chip has compute units (few rows, long contexts: c5's target pass 20 rows x 8 KV heads), else 4
+  dim3 grid(a.KVH, max_rows);
+  const bool wide = (long long)a.KVH * max_rows <= 256;
+#define SPRINTER_ATTN(G_) do { if (wide) hipLaunchKernelGGL((k_attn_bf16<DH, G_, 8>), grid, dim3(512), 0, s, a); \
+                               else hipLaunchKernelGGL((k_attn_bf16<DH, G_, 4>), grid, dim3(256), 0, s, a); } while (0)
   switch (G) {
-    case 1: hipLaunchKernelGGL((k_attn_bf16<DH, 1>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((k_attn_bf16<DH, 2>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((k_attn_bf16<DH, 4>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((k_attn_bf16<DH, 8>), grid, block, 0, s, a); break;
+    case 1: SPRINTER_ATTN(1); break;
+    case 2: SPRINTER_ATTN(2); break;
+    case 4: SPRINTER_ATTN(4); break;
+    default: hipLaunchKernelGGL((k_attn_bf16<DH, 8, 4>), grid, dim3(256), 0, s, a); break;   // (8 waves would spill)
   }
+#undef SPRINTER_ATTN
 }
 
 template <typename T, int DH>
