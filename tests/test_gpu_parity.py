@@ -254,6 +254,47 @@ def test_single_token_prompt_and_full_batch():
     p.close()
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes(seed):
+    """Seeded random small configurations: architecture pair, widths (not multiples of the 32-wide k tile times 8
+    waves, nor of the 16-column output tile), head counts and grouping, head dimension 64 / 128, odd vocabulary,
+    batch, ragged prompts, verifier kind, dtype and the two mode switches - every row replayed by the oracle."""
+    from dataclasses import replace
+    from parity_util import compare_replay, compare_sd
+    rng = np.random.default_rng(1000 + seed)
+
+    def model(vocab, ctx):
+        arch = int(rng.integers(0, 2))
+        dh = int(rng.choice([64, 128]))
+        kvh = int(rng.choice([1, 2, 3]))
+        grp = int(rng.choice([1, 2, 4])) if arch == W.ARCH_LLAMA else 1
+        H = kvh * grp
+        ff = int(rng.integers(8, 60)) * 8
+        L = int(rng.integers(1, 3))
+        if arch == W.ARCH_LLAMA:
+            return W.ModelCfg(arch, L, H * dh, H, kvh, ff, vocab, ctx, 1e-5, 10000.0)
+        return W.ModelCfg(arch, L, H * dh, H, H, ff, vocab, ctx)
+
+    V = int(rng.integers(40, 900))
+    B = int(rng.choice([1, 2, 7, 17, 33, 70]))
+    G = 5
+    draft, target = model(V, 48), model(V, 48)
+    cfg = W.SprinterCfg(draft, target, int(rng.choice([0, 24, 40])), int(rng.choice([W.DT_F32, W.DT_BF16])), B, 48,
+                        seed=int(rng.integers(0, 1 << 40)), name=f"random-{seed}", batch=B, prompt_len=int(rng.integers(2, 12)),
+                        prompt_len_min=1, n_gen=G, prompt_dist="uniform", weight_seed=300 + seed, prompt_seed=400 + seed,
+                        target_ctx_mode=int(rng.integers(0, 2)), reject_mode=int(rng.integers(0, 2)))
+    p = _pair(cfg, ver_scale=8.0)
+    g, st = p.gpu_generate(G)
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]))
+    rep = compare_replay(cfg, g, rec, check_target=cfg.reject_mode == W.REJECT_REPLACE)
+    if cfg.reject_mode == W.REJECT_SD:
+        rep.update(compare_sd(cfg, g, rec))
+    print(seed, "draft", draft, "target", target, "B", B, "dtype", cfg.dtype, "ctx", cfg.target_ctx_mode, "rej", cfg.reject_mode,
+          rep, flush=True)
+    assert np.array_equal(st["target_calls"], (g["accept"] == 0).sum(1))
+    p.close()
+
+
 @pytest.mark.parametrize("ctx,rej", [(0, 0), (1, 1)])
 def test_maximum_batch(ctx, rej):
     """The largest batch the library accepts (1024 rows; the decide / finish kernels then use all 16 waves of
