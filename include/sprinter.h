@@ -147,8 +147,10 @@ int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes);
 /* Creates a context on the current device.  dev_workspace (256-byte aligned, at
  * least sprinter_workspace_bytes) stays owned by the caller and must outlive the
  * context; hip_stream is a hipStream_t (NULL = the default stream) on which all
- * later work is enqueued.  Errors: NULL pointers, unsupported cfg (see field
- * comments), workspace too small. */
+ * later work is enqueued.  The library allocates no device memory; create
+ * allocates 256 bytes of pinned host memory (the word the host polls for the
+ * number of rejected rows), freed by sprinter_destroy.  Errors: NULL pointers,
+ * unsupported cfg (see field comments), workspace too small. */
 int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes,
                     void* hip_stream, sprinter_ctx** out_ctx);
 
