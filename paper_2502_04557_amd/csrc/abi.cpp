@@ -386,12 +386,12 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
     launch_gemm(dt, EPI_F32, L.wqkv, nullptr, sc.xn, pl_d, rd.n_rows, md.dqkv, md.d, L.bqkv, sc.y, md.dqkv, nullptr, 0,
                 0, max_rows, s);
     if (shared_caches) {
-      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
                        ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 1);
-      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
                        ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 2);
     } else {
-      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->cfg.max_batch,
+      launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
                        ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
     }
     if (!want_head && i + 1 == md.n_layer) break;   // a prefill position only has to fill the caches
@@ -916,7 +916,9 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
     for (int g = 0; g < n_tokens; ++g) {
       rc = enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
       if (rc) return rc;
+      ctx->steps_done += 1;
     }
+    return hip_status(ctx, "sprinter_generate");
   }
   ctx->steps_done += n_tokens;
   return hip_status(ctx, "sprinter_generate");

@@ -1134,11 +1134,12 @@ static size_t attn_smem_bytes(int DH, int G, int max_seq) {
 }
 
 template <int DH>
-static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, hipStream_t s) {
-  // NW = waves per workgroup that share one (row, KV head)'s keys: 8 while the launch has fewer workgroups than
-  // the chip has compute units (few rows, long contexts: c5's target pass 20 rows x 8 KV heads), else 4
+static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, int ctx_bound, hipStream_t s) {
+  // NW = waves per workgroup that share one (row, KV head)'s keys: 8 when the launch has no more workgroups than
+  // the chip has compute units and the contexts are long (c5's target pass: 20 rows x 8 KV heads x 1000+ keys),
+  // else 4 (at c2's 130-400 keys the 8-wave variant takes 9.5 us against 7.8)
   dim3 grid(a.KVH, max_rows);
-  const bool wide = (long long)a.KVH * max_rows <= 256;
+  const bool wide = (long long)a.KVH * max_rows <= 256 && ctx_bound >= 512;
 #define SPRINTER_ATTN(G_) do { if (wide) hipLaunchKernelGGL((k_attn_bf16<DH, G_, 8>), grid, dim3(512), 0, s, a); \
                                else hipLaunchKernelGGL((k_attn_bf16<DH, G_, 4>), grid, dim3(256), 0, s, a); } while (0)
   switch (G) {
@@ -1163,9 +1164,8 @@ static void launch_attn_g(const AttnArgs& a, int G, int max_rows, hipStream_t s)
 }
 
 void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
-                      void* kcache, void* vcache, size_t layer_off, int max_batch, int max_seq, void* ao,
+                      void* kcache, void* vcache, size_t layer_off, int ctx_bound, int max_seq, void* ao,
                       size_t ao_plane, int max_rows, hipStream_t s, int phase) {
-  (void)max_batch;
   AttnArgs a;
   a.phase = phase;
   a.y = y; a.rope = rope; a.rd = rd; a.kcache = kcache; a.vcache = vcache; a.layer_off = layer_off;
@@ -1176,7 +1176,7 @@ void launch_attention(int dtype, const ModelDims& md, const float* y, const floa
   if (dtype == 0) {
     if (md.dh == 64) launch_attn_g<float, 64>(a, G, max_rows, s); else launch_attn_g<float, 128>(a, G, max_rows, s);
   } else {
-    if (md.dh == 64) launch_attn_bf16<64>(a, G, max_rows, s); else launch_attn_bf16<128>(a, G, max_rows, s);
+    if (md.dh == 64) launch_attn_bf16<64>(a, G, max_rows, ctx_bound, s); else launch_attn_bf16<128>(a, G, max_rows, ctx_bound, s);
   }
 }
 
