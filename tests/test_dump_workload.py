@@ -39,3 +39,34 @@ def test_dump_round_trip(tmp_path):
     if not os.path.exists(build.NATIVE_BENCH):
         build.build_library(verbose=False)
     assert os.path.exists(build.NATIVE_BENCH), "the build makes the native runner"
+
+
+import pytest
+
+
+@pytest.mark.gpu
+def test_native_runner_reproduces_the_python_run(tmp_path):
+    """The Python-free runner on a dumped workload makes the same decisions as the binding on the generated one
+    (same weights, prompts and seeds): equal counters after the same number of steps."""
+    import json
+    from dataclasses import replace
+    from paper_2502_04557_amd import binding, build
+    out = tmp_path / "c1.sprw"
+    subprocess.run([sys.executable, "-m", "paper_2502_04557_amd.dump_workload", "--config", "c1", "--steps", "24",
+                    "--warmup", "8", "--out", str(out)], check=True, cwd=ROOT)
+    r = subprocess.run([build.NATIVE_BENCH, str(out), "--steps", "24", "--warmup", "8"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 0, r.stderr
+    nat = json.loads(r.stdout.strip().splitlines()[-1])
+    cfg = W.config("c1")
+    cfg = replace(cfg, max_seq=max(cfg.max_seq, cfg.prompt_len + 32))
+    s = binding.Sprinter(cfg)
+    for which, w in zip((binding.DRAFT, binding.TARGET, binding.VERIFIER), W.make_weights(cfg)):
+        s.load_weights(which, w)
+    s.prefill(*W.make_prompts(cfg))
+    s.generate(32, want=("tok",))
+    st = s.stats()
+    s.close()
+    assert nat["steps_total"] == st["steps"] == 32
+    assert nat["sum_rejected"] == st["sum_rejected"] and nat["steps_with_target"] == st["steps_with_target"]
+    assert nat["ms_per_step"] > 0
