@@ -143,6 +143,20 @@ __device__ __forceinline__ u64 sample_key(float logit, const SamplerArgs& sa, in
   return pack_key(y, (unsigned)n);
 }
 
+// Sum over an aligned group of 8 or 16 consecutive lanes, the total in every lane of the group, through DPP
+// (quad permutes, then the half-row and row mirrors: after the quad steps every lane of a quad holds the quad's
+// sum, so any lane of the other half is a valid partner).  A ds_bpermute butterfly costs about 100 cycles per
+// step in a dependent chain; this is four ordinary VALU adds.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(LANES == 8 || LANES == 16, "one DPP row or half a row");
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));    // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));    // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));   // row_half_mirror
+  if (LANES == 16) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));   // row_mirror
+  return v;
+}
+
 __device__ __forceinline__ f32x4 mfma_bf16(uint4 x, uint4 w, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8*>(&x), *reinterpret_cast<bf16x8*>(&w), c, 0,
                                                  0, 0);

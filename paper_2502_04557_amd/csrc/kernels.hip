@@ -976,39 +976,46 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
     }
   };
   request(kA, vA, 0);
-  // query heads, new key and new value: this lane's 8 elements (and their rotary partners)
+  // Query heads, new key and new value: this lane's 8 elements and their rotary partners.  Everything is requested
+  // up front as unconditional 16-byte loads (2 G + 3 pairs from the projection row, 4 from the cos / sin row) and only
+  // then used: with a branch on the rotary flag between the loads each head paid its own memory round trip (12 us
+  // before the first key at 4 query heads per KV head).  Without rotary the partner values are multiplied by 0.
   const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
-  const float* __restrict__ cs = a.rope + (size_t)r * DH;
-  float cr[8], sr[8];
-  if (a.use_rope) {
-    const int j0 = (chunk % (LPK / 2)) * 8;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { cr[e] = cs[2 * (j0 + e)]; sr[e] = cs[2 * (j0 + e) + 1]; }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { cr[e] = 1.f; sr[e] = 0.f; }
-  }
   const bool upper = chunk >= LPK / 2;
   const int pchunk = chunk ^ (LPK / 2);
-  auto rotated = [&](const float* v, float* out) {            // v: one head's DH values
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float x = v[chunk * 8 + e], xp = a.use_rope ? v[pchunk * 8 + e] : 0.f;
-      out[e] = upper ? x * cr[e] + xp * sr[e] : x * cr[e] - xp * sr[e];
-    }
+  auto load8 = [&](const float* src, float* out) {            // 32-byte aligned: all offsets are multiples of 8 floats
+    const float4 lo = reinterpret_cast<const float4*>(src)[0], hi = reinterpret_cast<const float4*>(src)[1];
+    out[0] = lo.x; out[1] = lo.y; out[2] = lo.z; out[3] = lo.w; out[4] = hi.x; out[5] = hi.y; out[6] = hi.z; out[7] = hi.w;
   };
-  float q[G][8], knew[8], vnew[8];
+  float qx[G][8], qp[G][8], kx[8], kp[8], vnew[8], csr[16];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    rotated(y + (size_t)(kvh * G + g) * DH, q[g]);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) q[g][e] *= a.scale;
+    load8(y + (size_t)(kvh * G + g) * DH + chunk * 8, qx[g]);
+    load8(y + (size_t)(kvh * G + g) * DH + pchunk * 8, qp[g]);
   }
-  rotated(y + (size_t)(a.H + kvh) * DH, knew);
+  load8(y + (size_t)(a.H + kvh) * DH + chunk * 8, kx);
+  load8(y + (size_t)(a.H + kvh) * DH + pchunk * 8, kp);
+  load8(y + (size_t)(a.H + a.KVH + kvh) * DH + chunk * 8, vnew);
+  {
+    const float* __restrict__ cs = a.rope + (size_t)r * DH + 2 * (chunk % (LPK / 2)) * 8;   // (cos, sin) pairs of this lane's 8 angles
+    load8(cs, csr);
+    load8(cs + 8, csr + 8);
+  }
+  float cr[8], sr[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { cr[e] = a.use_rope ? csr[2 * e] : 1.f; sr[e] = a.use_rope ? csr[2 * e + 1] : 0.f; }
+  float q[G][8], knew[8];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      q[g][e] = (upper ? qx[g][e] * cr[e] + qp[g][e] * sr[e] : qx[g][e] * cr[e] - qp[g][e] * sr[e]) * a.scale;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) knew[e] = upper ? kx[e] * cr[e] + kp[e] * sr[e] : kx[e] * cr[e] - kp[e] * sr[e];
   unsigned kpk[4], vpk[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    const float v0 = y[(size_t)(a.H + a.KVH + kvh) * DH + chunk * 8 + 2 * e], v1 = y[(size_t)(a.H + a.KVH + kvh) * DH + chunk * 8 + 2 * e + 1];
+    const float v0 = vnew[2 * e], v1 = vnew[2 * e + 1];
     const bf16_t k0 = f2bf(knew[2 * e]), k1 = f2bf(knew[2 * e + 1]), w0 = f2bf(v0), w1 = f2bf(v1);
     kpk[e] = (unsigned)k0 | ((unsigned)k1 << 16);
     vpk[e] = (unsigned)w0 | ((unsigned)w1 << 16);
@@ -1030,9 +1037,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
     float p = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) p += q[g][e] * knew[e];
-#pragma unroll
-    for (int o = 1; o < LPK; o <<= 1) p += __shfl_xor(p, o);
-    snew[g] = p;
+    snew[g] = group_sum<LPK>(p);
   }
   if (w == 0 && lane == 0) {
 #pragma unroll
@@ -1061,8 +1066,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
         float sc = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) sc += q[g][e] * kf[e];
-#pragma unroll
-        for (int o = 1; o < LPK; o <<= 1) sc += __shfl_xor(sc, o);
+        sc = group_sum<LPK>(sc);
         const float mn = valid ? fmaxf(m[g], sc) : m[g];
         const float corr = __expf(m[g] - mn);
         const float p = valid ? __expf(sc - mn) : 0.f;

@@ -295,6 +295,31 @@ def test_random_shapes(seed):
     p.close()
 
 
+@pytest.mark.parametrize("ctx", [0, 1])
+def test_long_context_few_rows(ctx):
+    """Contexts of 770-900 keys with 3 rows: the attention launch takes its 8-wave variant (few workgroups, long
+    contexts; draft: head dimension 64, 2 query heads per KV head; target: head dimension 128, 4 per KV head).
+    Every row replayed by the oracle; also in full-prefix mode (append-only + attend-only launches)."""
+    from parity_util import compare_replay
+    G = 6
+    draft = W.ModelCfg(W.ARCH_LLAMA, 1, 128, 2, 1, 192, 311, 1024, 1e-5, 10000.0)
+    target = W.ModelCfg(W.ARCH_LLAMA, 2, 512, 4, 1, 320, 311, 1024, 1e-5, 500000.0)
+    cfg = W.SprinterCfg(draft, target, 24, W.DT_BF16, 3, 1024, seed=77, name="long-context", batch=3, prompt_len=900,
+                        prompt_len_min=770, n_gen=G, prompt_dist="zipf", weight_seed=501, prompt_seed=502,
+                        target_ctx_mode=ctx)
+    p = _pair(cfg, ver_scale=8.0)
+    g, st = p.gpu_generate(G)
+    tau = float(np.median(g["score"]))                 # a threshold that splits this workload's scores
+    p.gpu.set_tau(tau)
+    g, st = p.gpu_generate(G)
+    rec = p.oracle(G, tau=tau, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]),
+                   whole_prompt_prefill=True)
+    rep = compare_replay(cfg, g, rec, tau=tau)
+    print("long context", ctx, p.plen, rep, flush=True)
+    assert 0 < (g["accept"] == 0).sum() < g["accept"].size
+    p.close()
+
+
 @pytest.mark.parametrize("ctx,rej", [(0, 0), (1, 1)])
 def test_maximum_batch(ctx, rej):
     """The largest batch the library accepts (1024 rows; the decide / finish kernels then use all 16 waves of
