@@ -293,34 +293,35 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int
 }
 
 
-// bf16 GEMM on MFMA.  512 threads = 8 waves = (8/KW) column groups x KW-way split of K.
-// Each wave owns NTW column tiles (16 columns each) and MT row tiles (16 rows each):
-// D[m][n] += X[m][k] W[n][k]; lane l of an accumulator holds n = l%16, m = (l/16)*4 + v.
-template <int MT, int NTW, int KW, int EPI>
-__global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
+// bf16 GEMM on MFMA for at most 16 rows.  512 threads = 8 waves that split K; each wave owns NTW column tiles
+// (16 columns each): D[m][n] += X[m][k] W[n][k].
+// All 8 waves leave their partial sums in LDS and every thread then finishes ONE output element: it adds the 8
+// partials in fixed order, applies bias / residual / GELU / SwiGLU and stores.  With the element order chosen per
+// output layout the 256 x NTW stores of the workgroup are contiguous: one 32-column operand tile (two planes) for
+// the activation outputs, 64-128 byte runs for float32 rows.  (When wave 0 alone ran the epilogue - 8 tanh and 16
+// scattered 2-byte stores per lane for FFN-up - it took 2.2 of the kernel's 7.1 us.)
+// Accumulator layout of v_mfma_f32_16x16x32: lane l, register v hold n = l % 16, m = (l / 16) * 4 + v.
+template <int NTW, int EPI>
+__global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
   constexpr bool DUAL = (EPI == EPI_SWIGLU);
-  constexpr int NW = 8 / KW;
-  constexpr int NI = NTW * MT * 4;
-  constexpr int NI2 = NI * (DUAL ? 2 : 1);
-  // partial accumulators of the waves with kw > 0, handed to the kw == 0 wave of their column group
-  __shared__ float red[(KW > 1) ? (KW - 1) * NW * NI2 * 64 : 1];
-  const int lane = threadIdx.x & 63, w = wave_index();
-  const int kw = w % KW, ng = w / KW;
-  const int nt0 = (blockIdx.x * NW + ng) * NTW;
+  constexpr bool ACT_OUT = (EPI == EPI_GELU || EPI == EPI_SWIGLU);
+  constexpr int U = 4;      // k tiles per chunk and wave (8 and 16 measured slower)
+  constexpr int NI = NTW * 4, NI2 = NI * (DUAL ? 2 : 1), NOUT = NTW * 256;
+  __shared__ float red[8 * NI2 * 64];
+  const int tid = threadIdx.x, lane = tid & 63, kw = wave_index();
+  const int nt0 = blockIdx.x * NTW;
   const uint4* __restrict__ Wp = (const uint4*)a.W;
   const uint4* __restrict__ W2p = (const uint4*)a.W2;
   const uint4* __restrict__ Xp = (const uint4*)a.X;
   const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   const int Kt = a.Kt;
-  constexpr int U = 4;      // k tiles per chunk and wave (8 and 16 measured slower at one row tile)
-  // Requests that depend on nothing are issued before the row count is even read: this wave's first
-  // weight tiles and, in the wave that finishes the tile, the bias and (residual epilogue) the current
-  // output values of the first row block.  That takes three memory latencies off the kernel's chain.
+  // Requests that depend on nothing are issued before the row count is even read: this wave's first weight
+  // tiles and this thread's bias and (residual epilogue) current output value.
   uint4 wv[U][NTW], wv2[U][DUAL ? NTW : 1];
   auto load_weights = [&](int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      int kc = min(kt + u * KW, Kt - 1);                    // clamped: always a valid tile
+      int kc = min(kt + u * 8, Kt - 1);                     // clamped: always a valid tile
 #pragma unroll
       for (int j = 0; j < NTW; ++j) {
         int nt = min(nt0 + j, a.n_tiles - 1);
@@ -329,122 +330,70 @@ __global__ __launch_bounds__(512) void k_gemm_bf16(GemmArgs a) {
       }
     }
   };
-  // (One row tile only: with two, the extra live registers cost a workgroup per compute unit and
-  // the kernel, which then streams far more weight bytes per launch, measured 25 % slower.)
-  constexpr bool EARLY = MT == 1;
-  float pbias[NTW], pres[NTW][EARLY ? MT : 1][4];
-  if (EARLY) {
-    load_weights(min(kw, Kt - 1));
-#pragma unroll
-    for (int j = 0; j < NTW; ++j) {
-      const int n = (nt0 + j) * 16 + (lane & 15);
-      const bool n_ok = kw == 0 && nt0 + j < a.n_tiles && n < a.N;
-      pbias[j] = (n_ok && a.bias) ? a.bias[n] : 0.f;
-#pragma unroll
-      for (int v = 0; v < 4; ++v)
-        pres[j][0][v] = (EPI == EPI_RESID && n_ok) ? a.out_f32[(size_t)((lane >> 4) * 4 + v) * a.ldo + n] : 0.f;
-    }
-  }
+  load_weights(min(kw, Kt - 1));
+  // this thread's output element: (row m, column c of the workgroup's 16 NTW columns)
+  int m, c;
+  if (ACT_OUT) { m = (tid >> 3) & 15; c = (tid >> 7) * 8 + (tid & 7); }      // operand-tile order: 8 columns, 16 rows, next 8 columns
+  else { m = tid / (16 * NTW); c = tid % (16 * NTW); }                      // row-major
+  const int n = nt0 * 16 + c;
+  const bool n_ok = tid < NOUT && n < a.N;
+  const float pbias = (n_ok && a.bias) ? a.bias[n] : 0.f;
+  const float pres = (EPI == EPI_RESID && n_ok) ? a.out_f32[(size_t)m * a.ldo + n] : 0.f;
   const int n_rows = *a.n_rows;
   if (n_rows <= 0) return;
-  for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
-    const int mt_act = min(MT, (n_rows - m0 + 15) >> 4);
-    const int mtile0 = m0 >> 4;
-    f32x4 acc[NTW][MT], acc2[DUAL ? NTW : 1][MT];
+  f32x4 acc[NTW], acc2[DUAL ? NTW : 1];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if (DUAL) acc2[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+  for (int kt = kw; kt < Kt; kt += 8 * U) {
+    if (kt != kw) load_weights(kt);                         // (the first chunk is already on its way)
+    // Straight-line code: all activation loads of the chunk are issued together, k tiles beyond K are clamped
+    // on load and zeroed as operands.  (A branch per k tile keeps the scheduler from hoisting the loads and
+    // serialises one L2 latency per tile.)
+    uint4 xv[U], xl[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kc = min(kt + u * 8, Kt - 1);
+      xv[u] = Xp[(size_t)kc * 64 + lane];
+      xl[u] = Xl[(size_t)kc * 64 + lane];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool in_k = kt + u * 8 < Kt;
+      const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) {
+        acc[j] = mfma_bf16(ah, wv[u][j], acc[j]);
+        acc[j] = mfma_bf16(al, wv[u][j], acc[j]);
+        if (DUAL) {
+          acc2[j] = mfma_bf16(ah, wv2[u][j], acc2[j]);
+          acc2[j] = mfma_bf16(al, wv2[u][j], acc2[j]);
+        }
+      }
+    }
+  }
+  {
+    float* dst = red + (size_t)kw * NI2 * 64;
 #pragma unroll
     for (int j = 0; j < NTW; ++j)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        if (DUAL) acc2[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int v = 0; v < 4; ++v) {
+        dst[(j * 4 + v) * 64 + lane] = acc[j][v];
+        if (DUAL) dst[(NI + j * 4 + v) * 64 + lane] = acc2[j][v];
       }
-    for (int kt = kw; kt < Kt; kt += KW * U) {
-      if (!EARLY || kt != kw || m0 != 0) load_weights(kt);  // (EARLY: the first chunk is already on its way)
-      // Straight-line code inside the (uniform) row-tile test: all activation loads of the chunk are
-      // issued together, k tiles beyond K are clamped on load and zeroed as operands.  (A branch per
-      // k tile keeps the scheduler from hoisting the loads and serialises one L2 latency per tile.)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        if (mt < mt_act) {
-          uint4 xv[U], xl[U];
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const int kc = min(kt + u * KW, Kt - 1);
-            xv[u] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
-            xl[u] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
-          }
-#pragma unroll
-          for (int u = 0; u < U; ++u) {
-            const bool in_k = kt + u * KW < Kt;
-            const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-            for (int j = 0; j < NTW; ++j) {
-              acc[j][mt] = mfma_bf16(ah, wv[u][j], acc[j][mt]);
-              acc[j][mt] = mfma_bf16(al, wv[u][j], acc[j][mt]);
-              if (DUAL) {
-                acc2[j][mt] = mfma_bf16(ah, wv2[u][j], acc2[j][mt]);
-                acc2[j][mt] = mfma_bf16(al, wv2[u][j], acc2[j][mt]);
-              }
-            }
-          }
-        }
-      }
-    }
-    if (KW > 1) {
-      // sum the KW partial accumulators in a fixed order (kw = 0, 1, ..)
-      if (kw > 0) {
-        float* dst = red + (size_t)(ng * (KW - 1) + kw - 1) * NI2 * 64;
-#pragma unroll
-        for (int j = 0; j < NTW; ++j)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              int it = (j * MT + mt) * 4 + v;
-              dst[it * 64 + lane] = acc[j][mt][v];
-              if (DUAL) dst[(NI + it) * 64 + lane] = acc2[j][mt][v];
-            }
-      }
-      __syncthreads();
-      if (kw == 0) {
-#pragma unroll
-        for (int q = 1; q < KW; ++q) {
-          const float* src = red + (size_t)(ng * (KW - 1) + q - 1) * NI2 * 64;
-#pragma unroll
-          for (int j = 0; j < NTW; ++j)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-              for (int v = 0; v < 4; ++v) {
-                int it = (j * MT + mt) * 4 + v;
-                acc[j][mt][v] += src[it * 64 + lane];
-                if (DUAL) acc2[j][mt][v] += src[(NI + it) * 64 + lane];
-              }
-        }
-      }
-    }
-    if (kw == 0) {
-#pragma unroll
-      for (int j = 0; j < NTW; ++j)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          if (mt < mt_act && nt0 + j < a.n_tiles) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              const int m = m0 + mt * 16 + (lane >> 4) * 4 + v, n = (nt0 + j) * 16 + (lane & 15);
-              float res = 0.f, bias = 0.f;
-              if (EARLY && m0 == 0) {
-                res = pres[j][0][v]; bias = pbias[j];
-              } else if (m < n_rows && n < a.N) {
-                if (EPI == EPI_RESID) res = a.out_f32[(size_t)m * a.ldo + n];
-                if (a.bias) bias = a.bias[n];
-              }
-              gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, acc[j][mt][v], DUAL ? acc2[j][mt][v] : 0.f, bias, res);
-            }
-          }
-    }
-    if (KW > 1) __syncthreads();
   }
+  __syncthreads();
+  if (tid >= NOUT) return;
+  const int it = (c >> 4) * 4 + (m & 3), sl = (m >> 2) * 16 + (c & 15);
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {                             // fixed order: wave 0, 1, ..
+    s1 += red[((size_t)q * NI2 + it) * 64 + sl];
+    if (DUAL) s2 += red[((size_t)q * NI2 + NI + it) * 64 + sl];
+  }
+  gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, s1, s2, pbias, pres);
 }
 
 // bf16 GEMM for 17 .. 64 rows per pass (MT row tiles of 16), one column tile per workgroup, K split over
@@ -581,7 +530,7 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
 template <int NTW>
 __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
   constexpr int U = 4;
-  __shared__ float red[7 * NTW * 4 * 64];
+  __shared__ float red[8 * NTW * 4 * 64];
   const int lane = threadIdx.x & 63, kw = wave_index();
   const int n_groups = (a.n_tiles + NTW - 1) / NTW;
   const int g = blockIdx.x % n_groups, sk = blockIdx.x / n_groups;
@@ -625,31 +574,23 @@ __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
       }
     }
   }
-  if (kw > 0) {
-    float* dst = red + (size_t)(kw - 1) * NTW * 4 * 64;
+  {
+    float* dst = red + (size_t)kw * NTW * 4 * 64;
 #pragma unroll
     for (int j = 0; j < NTW; ++j)
 #pragma unroll
       for (int v = 0; v < 4; ++v) dst[(j * 4 + v) * 64 + lane] = acc[j][v];
   }
   __syncthreads();
-  if (kw != 0) return;
+  // one output element per thread, row-major: the 8 partial sums in fixed order, stores in 64-128 byte runs
+  const int tid = threadIdx.x;
+  if (tid >= NTW * 256) return;
+  const int m = tid / (16 * NTW), c = tid % (16 * NTW), n = nt0 * 16 + c;
+  const int it = (c >> 4) * 4 + (m & 3), sl = (m >> 2) * 16 + (c & 15);
+  float sum = 0.f;
 #pragma unroll
-  for (int q = 0; q < 7; ++q)            // fixed order
-#pragma unroll
-    for (int j = 0; j < NTW; ++j)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) acc[j][v] += red[(size_t)q * NTW * 4 * 64 + (j * 4 + v) * 64 + lane];
-  float* out = a.part + (size_t)sk * a.part_stride;
-#pragma unroll
-  for (int j = 0; j < NTW; ++j) {
-    const int n = (nt0 + j) * 16 + (lane & 15);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int m = (lane >> 4) * 4 + v;
-      if (nt0 + j < a.n_tiles && n < a.N && m < n_rows) out[(size_t)m * a.ldo + n] = acc[j][v];
-    }
-  }
+  for (int q = 0; q < 8; ++q) sum += red[((size_t)q * NTW * 4 + it) * 64 + sl];
+  if (n < a.N && m < n_rows) (a.part + (size_t)sk * a.part_stride)[(size_t)m * a.ldo + n] = sum;
 }
 
 // float32 GEMM on the vector ALU: one wave per output column, 8 rows at a time.
@@ -703,8 +644,8 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   // wide outputs with a short K: two column tiles per wave share the activation fragments (at K = 4096 one tile per
   // workgroup is faster: QKV 12288x4096 26 against 32 us, FFN-up 2x11008x4096 40 against 48 us)
   if (max_rows <= 16 && a.n_tiles >= 256 && a.Kt < 100)
-    hipLaunchKernelGGL((k_gemm_bf16<1, 2, 8, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
-  else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm_bf16<1, 1, 8, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((k_gemm16<2, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
+  else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm16<1, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
   else {
     // column tiles per wave that share the activation fragments: as many as leave about 192 workgroups
     const int passes = (max_rows + 63) / 64;
@@ -1230,7 +1171,7 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
         for (int u = 0; u < U; ++u) wv[u] = Wp[((size_t)nt * Kt + min(kt + u, Kt - 1)) * 64 + lane];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          if (mt < mt_act) {                      // uniform; straight-line code inside (see k_gemm_bf16)
+          if (mt < mt_act) {                      // uniform; straight-line code inside (see k_gemm16)
             uint4 xv[U], xl[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
