@@ -498,26 +498,44 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
     }
     __syncthreads();
   }
-  if (kw != 0) return;
+  // Wave 0 now holds the totals; it hands them to the whole workgroup through LDS and every thread finishes
+  // MT * NTW / 2 (rounded up) output elements, in an order that makes the workgroup's stores contiguous per output layout
+  // (one wave running the epilogue for up to 64 values per lane was a serial tail of several microseconds).
+  if (kw == 0) {
+#pragma unroll
+    for (int j = 0; j < NWT; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[((j * MT + mt) * 4 + v) * 64 + lane] = acc[j][mt][v];
+  }
+  __syncthreads();
+  constexpr bool ACT_OUT = (EPI == EPI_GELU || EPI == EPI_SWIGLU);
   float* part = (EPI == EPI_PART) ? a.part + (size_t)sk * a.part_stride : nullptr;
 #pragma unroll
-  for (int j = 0; j < NTW; ++j) {
-    if (nt0 + j >= a.n_tiles) break;
-    const int n = (nt0 + j) * 16 + (lane & 15);
-    const float bias = (EPI != EPI_PART && a.bias && n < a.N) ? a.bias[n] : 0.f;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int m = (mtile0 + mt) * 16 + (lane >> 4) * 4 + v;
-        if constexpr (EPI == EPI_PART) {
-          if (m < n_rows && n < a.N) part[(size_t)m * a.ldo + n] = acc[j][mt][v];
-        } else {
-          float res = 0.f;
-          if (EPI == EPI_RESID && m < n_rows && n < a.N) res = a.out_f32[(size_t)m * a.ldo + n];
-          gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, acc[j][mt][v], DUAL ? acc[NTW + j][mt][v] : 0.f, bias, res);
-        }
-      }
+  for (int i = 0; i < (MT * NTW + 1) / 2; ++i) {
+    const int o = i * 512 + (int)threadIdx.x;        // element index among the MT*16 x NTW*16 outputs
+    if (o >= 256 * MT * NTW) break;
+    int mt, m16, c;
+    if (ACT_OUT) {                                   // operand-tile order: 8 columns, 16 rows, next 8 columns, next row tile
+      const int rest = o >> 7;
+      m16 = (o >> 3) & 15; c = (rest % (2 * NTW)) * 8 + (o & 7); mt = rest / (2 * NTW);
+    } else {                                         // row-major
+      const int m_all = o / (16 * NTW);
+      c = o % (16 * NTW); mt = m_all >> 4; m16 = m_all & 15;
+    }
+    const int j = c >> 4, n = nt0 * 16 + c, m = (mtile0 + mt) * 16 + m16;
+    const int sl = (m16 >> 2) * 16 + (c & 15), v = m16 & 3;
+    const float s1 = red[((j * MT + mt) * 4 + v) * 64 + sl];
+    const float s2 = DUAL ? red[(((NTW + j) * MT + mt) * 4 + v) * 64 + sl] : 0.f;
+    if (m >= n_rows || n >= a.N) continue;
+    if constexpr (EPI == EPI_PART) {
+      part[(size_t)m * a.ldo + n] = s1;
+    } else {
+      const float bias = a.bias ? a.bias[n] : 0.f;
+      const float res = (EPI == EPI_RESID) ? a.out_f32[(size_t)m * a.ldo + n] : 0.f;
+      gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, s1, s2, bias, res);
+    }
   }
 }
 
