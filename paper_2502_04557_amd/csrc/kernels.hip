@@ -330,7 +330,17 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
       }
     }
   };
+  uint4 xv[U], xl[U];
+  auto load_x = [&](int kt) {                               // row tile 0 always exists: no dependence on the row count
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kc = min(kt + u * 8, Kt - 1);
+      xv[u] = Xp[(size_t)kc * 64 + lane];
+      xl[u] = Xl[(size_t)kc * 64 + lane];
+    }
+  };
   load_weights(min(kw, Kt - 1));
+  load_x(min(kw, Kt - 1));
   // this thread's output element: (row m, column c of the workgroup's 16 NTW columns)
   int m, c;
   if (ACT_OUT) { m = (tid >> 3) & 15; c = (tid >> 7) * 8 + (tid & 7); }      // operand-tile order: 8 columns, 16 rows, next 8 columns
@@ -339,8 +349,9 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
   const bool n_ok = tid < NOUT && n < a.N;
   const float pbias = (n_ok && a.bias) ? a.bias[n] : 0.f;
   const float pres = (EPI == EPI_RESID && n_ok) ? a.out_f32[(size_t)m * a.ldo + n] : 0.f;
+  // (The row count is only needed by the epilogue: launches are sized by the host for rows that exist, so the loop
+  // does not wait for it.)
   const int n_rows = *a.n_rows;
-  if (n_rows <= 0) return;
   f32x4 acc[NTW], acc2[DUAL ? NTW : 1];
 #pragma unroll
   for (int j = 0; j < NTW; ++j) {
@@ -348,17 +359,10 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
     if (DUAL) acc2[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
   for (int kt = kw; kt < Kt; kt += 8 * U) {
-    if (kt != kw) load_weights(kt);                         // (the first chunk is already on its way)
-    // Straight-line code: all activation loads of the chunk are issued together, k tiles beyond K are clamped
-    // on load and zeroed as operands.  (A branch per k tile keeps the scheduler from hoisting the loads and
-    // serialises one L2 latency per tile.)
-    uint4 xv[U], xl[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kc = min(kt + u * 8, Kt - 1);
-      xv[u] = Xp[(size_t)kc * 64 + lane];
-      xl[u] = Xl[(size_t)kc * 64 + lane];
-    }
+    // Straight-line code: all loads of a chunk are issued together, k tiles beyond K are clamped on load and
+    // zeroed as operands.  (A branch per k tile keeps the scheduler from hoisting the loads and serialises one
+    // L2 latency per tile.)
+    if (kt != kw) { load_weights(kt); load_x(kt); }         // (the first chunk is already on its way)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool in_k = kt + u * 8 < Kt;
@@ -461,8 +465,7 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
   };
   Buf A, B;
   load(A, min(k0 + kw, k1 - 1));
-  const int n_rows = *a.n_rows;
-  if (n_rows <= mtile0 * 16) return;
+  const int n_rows = *a.n_rows;                               // only the epilogue needs it (passes are sized by the host)
   // (the scheduling barriers keep the compiler from sinking a buffer's loads down to their first use)
   for (int kt = k0 + kw; kt < k1; kt += 2 * STEP) {
     load(B, kt + STEP);
@@ -566,21 +569,23 @@ __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
       for (int j = 0; j < NTW; ++j) wv[u][j] = Wp[((size_t)min(nt0 + j, a.n_tiles - 1) * Kt + kc) * 64 + lane];
     }
   };
-  load_weights(min(k0 + kw, k1 - 1));                         // before the row count is known
-  const int n_rows = *a.n_rows;
-  if (n_rows <= 0) return;
-  f32x4 acc[NTW];
-#pragma unroll
-  for (int j = 0; j < NTW; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  for (int kt = k0 + kw; kt < k1; kt += 8 * U) {
-    if (kt != k0 + kw) load_weights(kt);
-    uint4 xv[U], xl[U];
+  uint4 xv[U], xl[U];
+  auto load_x = [&](int kt) {                                 // row tile 0 always exists
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int kc = min(kt + u * 8, k1 - 1);
       xv[u] = Xp[(size_t)kc * 64 + lane];
       xl[u] = Xl[(size_t)kc * 64 + lane];
     }
+  };
+  load_weights(min(k0 + kw, k1 - 1));
+  load_x(min(k0 + kw, k1 - 1));
+  const int n_rows = *a.n_rows;                               // only the stores need it
+  f32x4 acc[NTW];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int kt = k0 + kw; kt < k1; kt += 8 * U) {
+    if (kt != k0 + kw) { load_weights(kt); load_x(kt); }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool in_k = kt + u * 8 < k1;
