@@ -189,6 +189,35 @@ def test_reject_by_coin_and_residual(kind, dtype, ctx):
     p0.close()
 
 
+def test_step_outputs_with_coin_and_residual():
+    """sprinter_step's optional outputs in reject_mode 1 (both LM heads write their logits into the library's own
+    buffers there and the caller's copies are made from them), and an empty generate call."""
+    from dataclasses import replace
+    from parity_util import close_enough, eps_of
+    G = 8
+    cfg = replace(W.mini_config("llama", W.DT_BF16, n_gen=G), reject_mode=W.REJECT_SD)
+    p = _pair(cfg, ver_scale=8.0)
+    eps = eps_of(cfg)
+    outs, st = p.gpu_steps(G, debug=True)
+    g = {k: np.stack([o[k2] for o in outs], axis=1) for k, k2 in
+         (("tok", "committed_tok"), ("accept", "accept"), ("score", "score"), ("draft_tok", "draft_tok"))}
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]), keep_logits=True)
+    n_target = 0
+    for s, o in enumerate(outs):
+        R = int(o["n_rej"][0])
+        assert close_enough(o["draft_logits"], rec["draft_logits"][s], eps).all()
+        if R:
+            assert close_enough(o["target_logits"][:R], rec["target_logits"][s], eps).all()
+            assert close_enough(o["target_hidden"][:R], rec["target_hidden"][s], eps).all()
+            n_target += 1
+    assert n_target > 0
+    g2, _ = p.gpu_generate(G)                       # the two entry points agree in this mode too
+    assert np.array_equal(g2["tok"], g["tok"])
+    empty = p.gpu.generate(0)                       # nothing to do: empty outputs, counters untouched
+    assert empty["tok"].shape == (cfg.batch, 0) and p.gpu.stats()["steps"] == G
+    p.close()
+
+
 def test_greedy_temperature_zero():
     from dataclasses import replace
     cfg = replace(W.mini_config("llama", W.DT_F32, n_gen=8), temperature=0.0)
