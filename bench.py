@@ -46,7 +46,8 @@ def algorithmic_bytes(cfg, plen, accept, first_step, seen_before=None):
     rej = (accept == 0)
     len_q = (plen[:, None] - 1) + first_step + np.arange(K)[None, :]          # entries before the step
     calls_before = np.cumsum(rej, axis=1) - rej                                  # target calls before the step
-    len_p = (plen[:, None] - 1) + calls_before
+    base_p = (plen - 1) if seen_before is None else np.asarray(seen_before, dtype=np.int64)   # target cache entries before the timed steps
+    len_p = base_p[:, None] + calls_before
     per_step = np.full(K, float(Wq + Wv))
     per_step += ((len_q + 2) * kq).sum(0)                                         # read len+1, write 1
     R = rej.sum(0)
@@ -175,9 +176,11 @@ def main():
     seen_before = plen.astype(np.int64) - 1
     if Wm:
         wa = s.generate(Wm, want=("tok", "accept"))["accept"].cpu().numpy()
-        for b in range(B):                                    # full-prefix mode: the cache is complete after a rejection
+        for b in range(B):
             r = np.flatnonzero(wa[b] == 0)
-            if len(r):
+            if cfg.target_ctx_mode == 0:                      # own history: one entry per target call
+                seen_before[b] += len(r)
+            elif len(r):                                      # full prefix: the cache is complete after a rejection
                 seen_before[b] = plen[b] - 1 + r[-1] + 1
     tok = torch.zeros(B, K, dtype=torch.int32, device=dev)
     acc = torch.zeros(B, K, dtype=torch.uint8, device=dev)

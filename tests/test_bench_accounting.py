@@ -1,0 +1,62 @@
+"""The algorithmic-bytes figure bench.py divides by the step time, against a brute-force count (CPU only)."""
+import os
+import sys
+from dataclasses import replace
+
+import numpy as np
+import workloads as W
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import bench  # noqa: E402
+
+
+def _brute(cfg, plen, accept, first_step, seen_before):
+    """Per step: every weight matrix of the draft (+ LM head) once, the verifier, the draft's cached K/V of every
+    row (read all, write one), and - if any row was rejected - the target's matrices once plus the cached K/V of
+    the rows (own history) or of every work-list entry (full prefix)."""
+    es = 2 if cfg.dtype == W.DT_BF16 else 4
+
+    def weights(m):
+        per_layer = m.d_qkv * m.d_model + m.d_model * m.n_head * m.d_head + (2 if m.arch == W.ARCH_GPT else 3) * m.d_model * m.d_ff
+        return (m.n_layer * per_layer + m.vocab * m.d_model) * es
+
+    def kv(m):
+        return 2 * m.n_layer * m.n_kv_head * m.d_head * es
+
+    h = cfg.ver_d_hidden
+    ver = ((cfg.ver_d_in * h + 2 * h + 1) if h else (cfg.ver_d_in + 1)) * 4
+    B, K = accept.shape
+    len_q = plen.astype(np.int64) - 1 + first_step
+    len_p = np.array(seen_before, np.int64)
+    out = []
+    for k in range(K):
+        total = weights(cfg.draft) + ver
+        for b in range(B):
+            total += (len_q[b] + 2) * kv(cfg.draft)
+        rej = [b for b in range(B) if accept[b, k] == 0]
+        if rej:
+            total += weights(cfg.target)
+        for b in rej:
+            if cfg.target_ctx_mode == 0:
+                total += (len_p[b] + 2) * kv(cfg.target)      # one entry per earlier target call of the row
+                len_p[b] += 1
+            else:
+                for pos in range(len_p[b], len_q[b] + 1):
+                    total += (pos + 2) * kv(cfg.target)
+                len_p[b] = len_q[b] + 1
+        len_q += 1
+        out.append(float(total))
+    return np.array(out)
+
+
+def test_algorithmic_bytes_match_a_brute_force_count():
+    rng = np.random.default_rng(0)
+    for ctx in (0, 1):
+        cfg = replace(W.mini_config("llama", W.DT_BF16), target_ctx_mode=ctx)
+        _, plen = W.make_prompts(cfg)
+        accept = (rng.random((cfg.batch, 12)) < 0.6).astype(np.uint8)
+        first = 3
+        seen = plen.astype(np.int64) - 1 + rng.integers(0, 3, size=cfg.batch)    # some target calls during warm-up
+        per_step, R = bench.algorithmic_bytes(cfg, plen, accept, first, seen.copy())
+        assert np.array_equal(R, (accept == 0).sum(0))
+        assert np.allclose(per_step, _brute(cfg, plen, accept, first, seen.copy()), rtol=1e-12)
