@@ -1015,29 +1015,50 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
   }
+  // One softmax rescale per round instead of one per key block: the round's scores first, then their maximum, one
+  // correction of the running sums, then the weighted values.
   auto consume = [&](const uint4* kb, const uint4* vb, int rd) {
+    float sc[NB][G];
+    bool valid[NB];
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
       const int key = ((rd * NB + j) * NW + w) * KPW + kin;
-      const bool valid = key < slot;
+      valid[j] = key < slot;
       const bf16_t* kt = reinterpret_cast<const bf16_t*>(&kb[j]);
-      const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vb[j]);
-      float kf[8], vf[8];
+      float kf[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { kf[e] = bf2f(kt[e]); vf[e] = valid ? bf2f(vt[e]) : 0.f; }   // (an empty cache holds no finite data yet)
+      for (int e = 0; e < 8; ++e) kf[e] = bf2f(kt[e]);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float sc = 0.f;
+        float d = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sc += q[g][e] * kf[e];
-        sc = group_sum<LPK>(sc);
-        const float mn = valid ? fmaxf(m[g], sc) : m[g];
-        const float corr = __expf(m[g] - mn);
-        const float p = valid ? __expf(sc - mn) : 0.f;
-        m[g] = mn;
-        l[g] = l[g] * corr + p;
+        for (int e = 0; e < 8; ++e) d += q[g][e] * kf[e];
+        sc[j][g] = group_sum<LPK>(d);
+      }
+    }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vf[e];
+    for (int g = 0; g < G; ++g) {
+      float mn = m[g];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) mn = valid[j] ? fmaxf(mn, sc[j][g]) : mn;
+      const float corr = __expf(m[g] - mn);
+      m[g] = mn;
+      l[g] *= corr;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vb[j]);
+      float vf[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vf[e] = valid[j] ? bf2f(vt[e]) : 0.f;   // (an empty cache holds no finite data yet)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float p = valid[j] ? __expf(sc[j][g] - m[g]) : 0.f;
+        l[g] += p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] += p * vf[e];
       }
     }
   };
