@@ -1175,78 +1175,95 @@ struct LmArgs {
   SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_plane;
 };
 
-// bf16: each workgroup owns a contiguous range of column tiles; its 8 waves take
-// tiles round-robin, keep a running (value, index) maximum per row, and the
-// workgroup writes one partial per row.
+// bf16: each workgroup owns a contiguous range of column tiles; its 8 waves take pairs of adjacent tiles
+// round-robin (the two tiles share the activation fragments: at 16+ rows the activations, 2 KiB per k tile and
+// row tile from L2, outweigh the 1 KiB of weights), keep a running (value, index) maximum per row, and the
+// workgroup writes one partial per row.  The k loop has no branches: two register buffers, tiles and k tiles
+// beyond the end are clamped on load; columns beyond the vocabulary and rows beyond the row count are dropped
+// when the logits are sampled.  More than 16 MT rows take further passes over the workgroup's tiles.
 template <int MT>
 __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
   __shared__ u64 sbest[8][MT * 16];
-  const int n_rows = *a.rd.n_rows;
-  if (n_rows <= 0) return;
+  __shared__ int s_rb[MT * 16], s_rt[MT * 16];
   const int lane = threadIdx.x & 63, w = wave_index();
   const int tpw = (a.n_tiles + gridDim.x - 1) / gridDim.x;
   const int t0 = blockIdx.x * tpw, t1 = min(t0 + tpw, a.n_tiles);
-  const uint4* __restrict__ Wp = (const uint4*)a.W;
-  const uint4* __restrict__ Xp = (const uint4*)a.X;
+  const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
+  const uint4* __restrict__ Xp = (const uint4*)a.X + lane;
   const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   const int Kt = a.Kt;
+  const int n_rows = *a.rd.n_rows;
+  struct Buf { uint4 w[2], xh[MT], xl[MT]; };
   for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
-    const int mt_act = min(MT, (n_rows - m0 + 15) >> 4);
     const int mtile0 = m0 >> 4;
     u64 best[MT][4];
-    int rb[MT][4], rt[MT][4];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        best[mt][v] = 0;
-        int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
-        rb[mt][v] = m < n_rows ? a.rd.b[m] : 0;
-        rt[mt][v] = m < n_rows ? a.rd.pos[m] + 1 : 0;     // the position being generated
-      }
-    for (int nt = t0 + w; nt < t1; nt += 8) {
-      f32x4 acc[MT];
+      for (int v = 0; v < 4; ++v) best[mt][v] = 0;
+    for (int i = threadIdx.x; i < MT * 16; i += 512) {     // the rows' random streams: batch row, position being generated
+      s_rb[i] = m0 + i < n_rows ? a.rd.b[m0 + i] : 0;
+      s_rt[i] = m0 + i < n_rows ? a.rd.pos[m0 + i] + 1 : 0;
+    }
+    __syncthreads();
+    for (int nt = t0 + 2 * w; nt < t1; nt += 16) {
+      const size_t wrow0 = (size_t)nt * Kt * 64, wrow1 = (size_t)min(nt + 1, t1 - 1) * Kt * 64;
+      auto load = [&](Buf& b, int kt) {
+        const int kc = min(kt, Kt - 1);
+        b.w[0] = Wp[wrow0 + (size_t)kc * 64];
+        b.w[1] = Wp[wrow1 + (size_t)kc * 64];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      constexpr int U = 4;
-      for (int kt = 0; kt < Kt; kt += U) {
-        uint4 wv[U];
+        for (int mt = 0; mt < MT; ++mt) {                 // (row tiles beyond the rows hold old data: dropped below)
+          b.xh[mt] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64];
+          b.xl[mt] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64];
+        }
+      };
+      f32x4 acc[2][MT];
 #pragma unroll
-        for (int u = 0; u < U; ++u) wv[u] = Wp[((size_t)nt * Kt + min(kt + u, Kt - 1)) * 64 + lane];
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          if (mt < mt_act) {                      // uniform; straight-line code inside (see k_gemm16)
-            uint4 xv[U], xl[U];
+        for (int mt = 0; mt < MT; ++mt) acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      auto compute = [&](const Buf& b, int kt) {
+        const bool in_k = kt < Kt;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-              const int kc = min(kt + u, Kt - 1);
-              xv[u] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
-              xl[u] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64 + lane];
-            }
+        for (int j = 0; j < 2; ++j) {
+          const uint4 wj = in_k ? b.w[j] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-              const bool in_k = kt + u < Kt;
-              const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
-              acc[mt] = mfma_bf16(ah, wv[u], acc[mt]);
-              acc[mt] = mfma_bf16(al, wv[u], acc[mt]);
-            }
+          for (int mt = 0; mt < MT; ++mt) {
+            acc[j][mt] = mfma_bf16(b.xh[mt], wj, acc[j][mt]);
+            acc[j][mt] = mfma_bf16(b.xl[mt], wj, acc[j][mt]);
           }
+        }
+      };
+      Buf A, B;
+      load(A, 0);
+      for (int kt = 0; kt < Kt; kt += 2) {
+        load(B, kt + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(A, kt);
+        __builtin_amdgcn_sched_barrier(0);
+        load(A, kt + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(B, kt + 1);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      const int n = nt * 16 + (lane & 15);
-      if (n < a.V) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          if (mt < mt_act) {
+      for (int j = 0; j < 2; ++j) {
+        const int n = (nt + j) * 16 + (lane & 15);
+        if (nt + j < t1 && n < a.V) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
               int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
               if (m < n_rows) {
-                float logit = acc[mt][v];
+                float logit = acc[j][mt][v];
                 if (a.logits_out) a.logits_out[(size_t)m * a.V + n] = logit;
-                best[mt][v] = umax64(best[mt][v], sample_key(logit, a.sa, rb[mt][v], rt[mt][v], n));
+                const int mi = mt * 16 + (lane >> 4) * 4 + v;
+                best[mt][v] = umax64(best[mt][v], sample_key(logit, a.sa, s_rb[mi], s_rt[mi], n));
               }
             }
-          }
+        }
       }
     }
 #pragma unroll
@@ -1337,10 +1354,10 @@ void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, cons
     hipLaunchKernelGGL(k_lmhead_bf16<1>, dim3(n_wg), dim3(512), 0, s, a);
   } else if (max_rows <= 32) {
     hipLaunchKernelGGL(k_lmhead_bf16<2>, dim3(n_wg), dim3(512), 0, s, a);
-  } else if (max_rows <= 64) {
+  } else if (max_rows <= 48) {
+    hipLaunchKernelGGL(k_lmhead_bf16<3>, dim3(n_wg), dim3(512), 0, s, a);
+  } else {                                   // 4 row tiles per pass; more rows take further passes inside the kernel
     hipLaunchKernelGGL(k_lmhead_bf16<4>, dim3(n_wg), dim3(512), 0, s, a);
-  } else {
-    hipLaunchKernelGGL(k_lmhead_bf16<8>, dim3(n_wg), dim3(512), 0, s, a);
   }
 }
 
