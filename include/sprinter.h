@@ -214,6 +214,7 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
  * four GEMM kinds), [64..127] the matching event counts.  All zero when off. */
 int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out);
 
+/* Waits for the stream, frees the context and its pinned word; the workspace stays with the caller. */
 void sprinter_destroy(sprinter_ctx* ctx);
 
 /* Text of the last error on ctx (or of the last failed sprinter_create /

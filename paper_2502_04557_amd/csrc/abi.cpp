@@ -972,6 +972,7 @@ int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out) {
 
 void sprinter_destroy(sprinter_ctx* ctx) {
   if (!ctx) return;
+  (void)hipStreamSynchronize(ctx->stream);     // a decide kernel still in flight writes into the pinned word
   if (ctx->host_counts) (void)hipHostFree(ctx->host_counts);
   delete ctx;
 }
