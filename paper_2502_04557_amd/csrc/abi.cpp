@@ -1,6 +1,6 @@
 // C-ABI layer of the SPRINTER decode library: validation, workspace carving,
 // weight intake and the launch sequence of prefill / step / generate.
-// All device work is issued through the launchers in kernels.hip.
+// All device work is issued through the launchers in the k_*.hip files.
 #include "../../include/sprinter.h"
 #include "internal.h"
 

@@ -1,4 +1,4 @@
-// Device-side helpers shared by the per-operation kernels (kernels.hip) and the
+// Device-side helpers shared by the per-operation kernels (k_*.hip) and the
 // persistent decode kernel (mega.hip): bf16 conversion, operand-tile indexing,
 // wave reductions, Philox4x32-10 / Gumbel noise, packed arg-max keys.
 #pragma once

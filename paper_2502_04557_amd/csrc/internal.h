@@ -1,5 +1,5 @@
 // Internal declarations shared by the C-ABI layer (abi.cpp) and the kernel
-// launchers (kernels.hip).  Nothing here is part of the public interface.
+// launchers (k_*.hip).  Nothing here is part of the public interface.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -54,7 +54,7 @@ struct SamplerArgs {
   float inv_temperature;   // 0 = greedy (no noise)
 };
 
-// ---- launchers (kernels.hip) ------------------------------------------------
+// ---- launchers (k_*.hip) ---------------------------------------------------
 void launch_pack_bf16(const void* w, void* out, int N, int K, hipStream_t s);
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
