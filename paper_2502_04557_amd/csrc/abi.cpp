@@ -266,7 +266,9 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   Bump bump(base);
   // full-prefix mode: every committed token reaches the target once, so a step's work list averages one entry
   // per batch row with wide swings; buffers for twice the batch keep most steps to a single pass
-  const int rows = rows_alloc_for(c.target_ctx_mode == 1 ? std::min(2 * c.max_batch, 1024) : c.max_batch);
+  // bf16: at least 64 rows, so that small batches prefill 64 prompt tokens per pass over the weights
+  const int rows = std::max(c.dtype == SPRINTER_BF16 ? 64 : 16,
+                            rows_alloc_for(c.target_ctx_mode == 1 ? std::min(2 * c.max_batch, 1024) : c.max_batch));
   carve_model(bump, c, c.draft, ctx ? &ctx->draft : nullptr, rows);
   carve_model(bump, c, c.target, ctx ? &ctx->target : nullptr, rows);
   int chunks = verifier_num_chunks(c.ver_d_hidden);
@@ -747,7 +749,8 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     const char* on = getenv("SPRINTER_PERSISTENT");
     if (on && on[0] == '1' && cfg->target_ctx_mode == 0 && cfg->reject_mode == 0) {
       const int rows = ctx->rows_alloc;
-      ctx->mega_mt = rows <= 16 ? 1 : rows <= 32 ? 2 : rows <= 64 ? 4 : 8;
+      const int rb = rows_alloc_for(cfg->max_batch);      // row tiles follow the batch; the buffers may hold more rows
+      ctx->mega_mt = rb <= 16 ? 1 : rb <= 32 ? 2 : rb <= 64 ? 4 : 8;
       MegaParams& hp = ctx->mega_host;
       hp.max_seq = cfg->max_seq; hp.max_batch = cfg->max_batch; hp.rows_alloc = rows;
       int grid = 0;
@@ -857,6 +860,32 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
   ctx->max_prompt_len = pmax;
   ctx->steps_done = 0;
   Model &dq = ctx->draft, &tp = ctx->target;
+  if (ctx->cfg.dtype == SPRINTER_BF16) {
+    // Chunked prefill: all (row, position) pairs, row-major, go through both models rows_alloc at a time with the
+    // kernels of the multi-entry target pass (every layer appends the chunk's keys / values, then attends), so the
+    // weights are streamed once per rows_alloc prompt tokens instead of once per position of the batch.
+    std::vector<int> off((size_t)B + 1, 0);
+    for (int b = 0; b < B; ++b) off[b + 1] = off[b] + host_prompt_len[b] - 1;
+    const long long E = off[B];
+    if (hipMemcpyAsync(ctx->ent_off, off.data(), ((size_t)B + 1) * 4, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)                  // (off is a local: the copy must be over before it goes)
+      return fail(ctx, SPRINTER_E_HIP, "copy of the prefill work list failed");
+    launch_prefill_begin(dev_prompt, max_prompt, B, ctx->st, ctx->rej_idx, ctx->n_rej, s);
+    CatchupArgs ca;
+    ca.st = ctx->st; ca.rej_idx = ctx->rej_idx; ca.n_rej = ctx->n_rej; ca.ent_off = ctx->ent_off;
+    ca.t_n_rows = tp.rd_n; ca.t_b = tp.rd_b; ca.t_tok = tp.rd_tok; ca.t_pos = tp.rd_pos; ca.t_slot = tp.rd_slot;
+    ca.t_last = ctx->t_last;
+    int chunk = 0;
+    for (long long start = 0; start < E; start += ctx->rows_alloc, ++chunk) {
+      const int n = (int)std::min<long long>(ctx->rows_alloc, E - start);
+      ca.start = (int)start; ca.n = n;
+      launch_catchup_chunk(ca, s);
+      forward(ctx, dq, tp.rd(), n, false, 0u, nullptr, true);
+      forward(ctx, tp, tp.rd(), n, false, 1u, nullptr, true);
+      // bound the number of launches in flight (tools that keep per-dispatch state have died on long backlogs)
+      if ((chunk & 3) == 3 && hipStreamSynchronize(s) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
+    }
+  } else
   for (int j = 0; j + 1 < pmax; ++j) {
     int n_j = 0;                                   // rows whose prompt still has a token to cache at index j
     for (int b = 0; b < B; ++b) n_j += j < host_prompt_len[b] - 1;

@@ -187,6 +187,24 @@ void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const 
                      rtok, rpos, rslot);
 }
 
+// Chunked prefill: the prompts go into the token history, every row's caches count as empty and every row is
+// listed, so that the full-prefix work-list kernel (k_catchup_chunk) enumerates the prompt positions 0 .. P_b-2
+// in row-major order from the prefix sums the host uploaded.
+__global__ __launch_bounds__(1024) void k_prefill_begin(const int* __restrict__ prompt, int max_prompt, int B, State st,
+                                                        int* rej_idx, int* n_rej) {
+  const int tid = threadIdx.x;
+  if (tid < B) {
+    const int P = st.prompt_len[tid];
+    for (int j = 0; j < P; ++j) st.hist[(size_t)tid * st.hist_stride + j] = prompt[(size_t)tid * max_prompt + j];
+    st.len_p[tid] = 0;
+    rej_idx[tid] = tid;
+  }
+  if (tid == 0) *n_rej = B;
+}
+void launch_prefill_begin(const int* prompt, int max_prompt, int B, State st, int* rej_idx, int* n_rej, hipStream_t s) {
+  hipLaunchKernelGGL(k_prefill_begin, dim3(1), dim3(1024), 0, s, prompt, max_prompt, B, st, rej_idx, n_rej);
+}
+
 __global__ __launch_bounds__(1024) void k_prefill_finish(const int* __restrict__ prompt, int max_prompt, int B,
                                                          State st, int* d_n_rows, int* d_b, int* d_tok, int* d_pos,
                                                          int* d_slot) {
