@@ -266,8 +266,8 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   Bump bump(base);
   // full-prefix mode: every committed token reaches the target once, so a step's work list averages one entry
   // per batch row with wide swings; buffers for twice the batch keep most steps to a single pass
-  // bf16: at least 64 rows, so that small batches prefill 64 prompt tokens per pass over the weights
-  const int rows = std::max(c.dtype == SPRINTER_BF16 ? 64 : 16,
+  // bf16: at least 256 rows, so that prefill runs 256 prompt tokens per pass over the weights (128: 20 % slower, 512: 10 % faster)
+  const int rows = std::max(c.dtype == SPRINTER_BF16 ? 256 : 16,
                             rows_alloc_for(c.target_ctx_mode == 1 ? std::min(2 * c.max_batch, 1024) : c.max_batch));
   carve_model(bump, c, c.draft, ctx ? &ctx->draft : nullptr, rows);
   carve_model(bump, c, c.target, ctx ? &ctx->target : nullptr, rows);
