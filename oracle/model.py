@@ -85,6 +85,13 @@ class KVCache:
     def __len__(self):
         return len(self.positions)
 
+    def truncate(self, n):
+        """Forget every entry after the first n (a speculative window that was not committed)."""
+        for i in range(len(self.K)):
+            del self.K[i][n:]
+            del self.V[i][n:]
+        del self.positions[n:]
+
 
 class Decoder:
     def __init__(self, cfg, weights: dict, store=np.float64):

@@ -52,12 +52,14 @@ def log_softmax(a: np.ndarray) -> np.ndarray:
     return a - (m + np.log(np.exp(a - m).sum()))
 
 
-def sd_correction(lq, lp, x, temperature, seed, b, t):
+def sd_correction(lq, lp, x, temperature, seed, b, t, always_draw=False):
     """What a rejection does under REJECT_SD (Sec. 2: accept x ~ q with probability min(1, p(x)/q(x)),
     else resample from Eq. (1): norm(max(0, p - q)); Alg. 2 draws the coin c ~ U(0, 1)).
     The coin comparison and the arg-max of the residual draw are taken on float32 values.
     Returns a dict: tok (the committed token), kept, coin, log_ratio = ln p(x) - ln q(x) (unclipped),
-    and for a residual draw its top-2 margin plus the two candidates (for tolerance bands)."""
+    and for a residual draw its top-2 margin plus the two candidates (for tolerance bands).
+    always_draw: also report the residual draw (as resid_tok) when the coin keeps x (replay of a history
+    whose coin went the other way)."""
     if not temperature > 0.0:
         raise ValueError("the p/q correction needs a temperature > 0")
     logq, logp = log_softmax(np.asarray(lq, np.float64) / temperature), log_softmax(np.asarray(lp, np.float64) / temperature)
@@ -65,16 +67,18 @@ def sd_correction(lq, lp, x, temperature, seed, b, t):
     c = philox.coin(seed, b, t)
     out = dict(coin=c, log_ratio=log_ratio, kept=bool(np.float32(c) <= np.float32(min(1.0, np.exp(log_ratio)))),
                tok=int(x), margin=np.inf, runner_up=-1, logq=logq, logp=logp)
-    if not out["kept"]:
+    if not out["kept"] or always_draw:
         r = np.maximum(0.0, np.exp(logp) - np.exp(logq))
         with np.errstate(divide="ignore"):
             z = np.log(r) + philox.gumbel(seed, philox.STREAM_TARGET, b, t, r.shape[0])
         z32 = z.astype(np.float32)
-        out["tok"] = int(np.argmax(z32))
+        out["resid_tok"] = int(np.argmax(z32))
+        if not out["kept"]:
+            out["tok"] = out["resid_tok"]
         if r.shape[0] > 1:
             order = np.argsort(z32.astype(np.float64), kind="stable")
-            out["runner_up"] = int(order[-2]) if order[-1] == out["tok"] else int(order[-1])
-            out["margin"] = float(z32[out["tok"]]) - float(z32[out["runner_up"]])
+            out["runner_up"] = int(order[-2]) if order[-1] == out["resid_tok"] else int(order[-1])
+            out["margin"] = float(z32[out["resid_tok"]]) - float(z32[out["runner_up"]])
     return out
 
 
