@@ -93,7 +93,11 @@ typedef struct {
  *   otherwise the token is drawn from the normalised residual max(0, p - q)
  *   (Gumbel-max with the target stream's noise); q and p are the softmax of
  *   logits / temperature, so temperature must be > 0.  A rejected position
- *   whose committed token equals its draft token was kept by the coin. */
+ *   whose committed token equals its draft token was kept by the coin.
+ *   sd_gamma > 0 reserves the buffers of sprinter_sd_generate (standard
+ *   speculative decoding on the same models) for windows of up to sd_gamma
+ *   draft tokens: two arrays of (sd_gamma + 1) * max_batch * vocab floats.
+ *   0 <= sd_gamma <= 16; reserved must be 0. */
 typedef struct {
   sprinter_model_cfg draft, target;
   int32_t ver_d_in, ver_d_hidden;
@@ -103,6 +107,8 @@ typedef struct {
   uint64_t seed;
   int32_t target_ctx_mode;
   int32_t reject_mode;
+  int32_t sd_gamma;
+  int32_t reserved;
 } sprinter_cfg;
 
 /* Optional per-step outputs of sprinter_step; every field is a device pointer
@@ -198,6 +204,35 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out);
  * scores, draft tokens.  The last step's tail is still running when the call returns. */
 int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uint8_t* dev_out_accept,
                       float* dev_out_score, int32_t* dev_out_draft_tok);
+
+/* Standard speculative decoding (Sec. 2 with Eq. (1)) on the same draft / target
+ * pair: the method the paper's speed-ups are measured against.  One round, for
+ * every row: the draft model generates gamma tokens one after the other; the
+ * target model reads the last committed token and those gamma tokens in one pass
+ * (gamma + 1 positions per row); the draft tokens are checked in order, x stays
+ * with probability min(1, p(x)/q(x)), the first that does not is replaced by a
+ * draw from norm(max(0, p - q)) and ends the window; if all stay, one more token
+ * is drawn from the target's last distribution.  A round commits n_acc + 1 tokens
+ * of a row, 0 <= n_acc <= gamma.  Random numbers: as in the decode step, keyed by
+ * (row, sequence position): draft stream for the window, coin stream for the
+ * test, target stream for the residual draw and the extra token.  The verifier
+ * is not used.
+ * Runs n_rounds rounds.  Outputs (device pointers, each may be NULL):
+ *   dev_out_tok [B, tok_stride]   tokens committed by this call, in order;
+ *                                 tok_stride >= n_rounds * (gamma + 1)
+ *   dev_out_n_tok [B]             how many of them per row
+ *   dev_out_n_acc [B, n_rounds]   draft tokens kept per round
+ *   dev_out_draft [B, n_rounds, gamma]  every drafted token
+ * Needs cfg.sd_gamma >= gamma >= 1 and temperature > 0.  Between two prefills a
+ * context runs either decode steps or rounds of this call, not both (error
+ * otherwise).  Error if max_prompt + (rounds so far + n_rounds) * (gamma + 1)
+ * would exceed max_seq.  The calling thread waits once per round (polling a
+ * pinned word, as in sprinter_step) for the size of the next draft pass: after a
+ * fully kept window the draft model has one more token to read than otherwise.
+ * sprinter_get_stats then counts rounds as steps, rows whose window was cut as
+ * sum_rejected and kept draft tokens as coin_kept. */
+int sprinter_sd_generate(sprinter_ctx* ctx, int gamma, int n_rounds, int32_t* dev_out_tok, int tok_stride,
+                         int32_t* dev_out_n_tok, int32_t* dev_out_n_acc, int32_t* dev_out_draft);
 
 /* Replaces the threshold tau (takes effect for steps enqueued afterwards). */
 int sprinter_set_tau(sprinter_ctx* ctx, float tau);

@@ -17,7 +17,7 @@ DRAFT, TARGET, VERIFIER = 0, 1, 2
 F32, BF16 = 0, 1
 
 EXPORTS = ("sprinter_workspace_bytes", "sprinter_create", "sprinter_load_weights", "sprinter_prefill",
-           "sprinter_step", "sprinter_generate", "sprinter_set_tau", "sprinter_get_stats", "sprinter_debug_phase_ticks",
+           "sprinter_step", "sprinter_generate", "sprinter_sd_generate", "sprinter_set_tau", "sprinter_get_stats", "sprinter_debug_phase_ticks",
            "sprinter_destroy", "sprinter_last_error")
 
 
@@ -30,7 +30,7 @@ class CfgC(C.Structure):
     _fields_ = [("draft", ModelCfgC), ("target", ModelCfgC), ("ver_d_in", C.c_int32), ("ver_d_hidden", C.c_int32),
                 ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("tau", C.c_float),
                 ("temperature", C.c_float), ("seed", C.c_uint64), ("target_ctx_mode", C.c_int32),
-                ("reject_mode", C.c_int32)]
+                ("reject_mode", C.c_int32), ("sd_gamma", C.c_int32), ("reserved", C.c_int32)]
 
 
 class StepOutC(C.Structure):
@@ -62,6 +62,7 @@ def load_library(path: str = LIB_PATH):
     lib.sprinter_prefill.argtypes = [vp, vp, C.POINTER(C.c_int32), i32, i32]
     lib.sprinter_step.argtypes = [vp, C.POINTER(StepOutC)]
     lib.sprinter_generate.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.sprinter_sd_generate.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp]
     lib.sprinter_set_tau.argtypes = [vp, C.c_float]
     lib.sprinter_get_stats.argtypes = [vp, C.POINTER(StatsC), C.POINTER(C.c_int64)]
     lib.sprinter_debug_phase_ticks.argtypes = [vp, C.POINTER(C.c_uint64)]
@@ -88,7 +89,8 @@ def _model_c(m) -> ModelCfgC:
 
 def cfg_to_c(cfg) -> CfgC:
     return CfgC(_model_c(cfg.draft), _model_c(cfg.target), cfg.ver_d_in, cfg.ver_d_hidden, cfg.dtype,
-                cfg.max_batch, cfg.max_seq, cfg.tau, cfg.temperature, cfg.seed, cfg.target_ctx_mode, getattr(cfg, "reject_mode", 0))
+                cfg.max_batch, cfg.max_seq, cfg.tau, cfg.temperature, cfg.seed, cfg.target_ctx_mode, getattr(cfg, "reject_mode", 0),
+                getattr(cfg, "sd_gamma", 0), 0)
 
 
 def _ptr(t):
@@ -204,6 +206,24 @@ class Sprinter:
         """As generate(), writing into caller-provided device tensors (no allocation)."""
         self._check(self.lib.sprinter_generate(self.ctx, n_tokens, _ptr(tok), _ptr(accept), _ptr(score),
                                                _ptr(draft_tok)), self.ctx)
+
+    def sd_generate(self, gamma: int, n_rounds: int) -> dict:
+        """n_rounds rounds of standard speculative decoding (sprinter_sd_generate): tok [B, n_rounds * (gamma + 1)]
+        with n_tok [B] valid entries per row, n_acc [B, n_rounds], draft [B, n_rounds, gamma]."""
+        B, dev = self.B, self.device
+        cap = max(1, n_rounds * (gamma + 1))
+        o = dict(tok=torch.full((B, cap), -1, dtype=torch.int32, device=dev),
+                 n_tok=torch.zeros(B, dtype=torch.int32, device=dev),
+                 n_acc=torch.zeros(B, max(1, n_rounds), dtype=torch.int32, device=dev),
+                 draft=torch.zeros(B, max(1, n_rounds), gamma, dtype=torch.int32, device=dev))
+        self._check(self.lib.sprinter_sd_generate(self.ctx, gamma, n_rounds, _ptr(o["tok"]), cap, _ptr(o["n_tok"]),
+                                                  _ptr(o["n_acc"]), _ptr(o["draft"])), self.ctx)
+        return o
+
+    def sd_generate_into(self, gamma: int, n_rounds: int, tok=None, tok_stride=0, n_tok=None, n_acc=None, draft=None):
+        """As sd_generate(), writing into caller-provided device tensors (no allocation)."""
+        self._check(self.lib.sprinter_sd_generate(self.ctx, gamma, n_rounds, _ptr(tok), tok_stride, _ptr(n_tok),
+                                                  _ptr(n_acc), _ptr(draft)), self.ctx)
 
     def set_tau(self, tau: float):
         self._check(self.lib.sprinter_set_tau(self.ctx, tau), self.ctx)

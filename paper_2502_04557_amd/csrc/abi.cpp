@@ -83,6 +83,12 @@ struct sprinter_ctx {
   int *ent_off = nullptr, *t_last = nullptr;   // full-prefix mode: work-list prefix sums, last-entry flags of a chunk
   int* coin_kept = nullptr;                    // reject_mode 1: counter, and the step's logits of both models
   float *dl = nullptr, *tl = nullptr;
+  // speculative-decoding baseline (cfg.sd_gamma > 0): device state, the second set of draft row descriptors
+  SdBase sd;
+  RowDescW sd_rd2{nullptr, nullptr, nullptr, nullptr, nullptr};
+  int sd_next_entries = 0;       // entries of the next round's first draft pass, once known
+  unsigned sd_wait_ticket = 0;   // != 0: the last round's finish kernel will report them under this ticket
+  int run_kind = 0;              // since the last prefill: 0 nothing, 1 decode steps, 2 speculative-decoding rounds
   // persistent decode kernel (bf16 mode)
   bool mega_on = false, mega_built = false;
   int mega_mt = 1, mega_grid = 0;
@@ -168,6 +174,8 @@ int validate_cfg(const sprinter_cfg* c, char* buf, size_t n) {
     BAD("target_ctx_mode %d is not one of 0 (own history), 1 (full prefix)", c->target_ctx_mode);
   if (c->reject_mode != 0 && c->reject_mode != 1) BAD("reject_mode %d is not one of 0 (replace), 1 (p/q correction)", c->reject_mode);
   if (c->reject_mode == 1 && !(c->temperature > 0.f)) BAD("reject_mode 1 needs a temperature > 0");
+  if (c->sd_gamma < 0 || c->sd_gamma > 16) BAD("sd_gamma %d outside [0, 16]", c->sd_gamma);
+  if (c->reserved != 0) BAD("reserved field must be 0");
   for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
     int dh = m->d_model / m->n_head, G = m->n_head / m->n_kv_head;
     size_t lds = (size_t)(G * dh + 2 * dh + 4 * G * dh + G * c->max_seq) * 4;
@@ -290,6 +298,30 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
     dl = (float*)bump.take((size_t)c.max_batch * c.draft.vocab * 4);
     tl = (float*)bump.take((size_t)rows * c.target.vocab * 4);
   }
+  SdBase sd;
+  memset(&sd, 0, sizeof sd);
+  RowDescW rd2{nullptr, nullptr, nullptr, nullptr, nullptr};
+  if (c.sd_gamma > 0) {
+    const size_t B = c.max_batch, G = c.sd_gamma;
+    sd.len_dc = (int*)bump.take(B * 4);
+    sd.win = (int*)bump.take(B * G * 4);
+    sd.qrow = (int*)bump.take(B * G * 4);
+    sd.kept = (unsigned char*)bump.take(B * G);
+    sd.alt = (int*)bump.take(B * (G + 1) * 4);
+    sd.d0_n = (int*)bump.take(4);
+    sd.d0_b = (int*)bump.take(2 * B * 4);
+    sd.d0_tok = (int*)bump.take(2 * B * 4);
+    sd.d0_pos = (int*)bump.take(2 * B * 4);
+    sd.d0_last = (int*)bump.take(2 * B * 4);
+    sd.o_cnt = (int*)bump.take(B * 4);
+    sd.dlw = (float*)bump.take((G + 1) * B * c.draft.vocab * 4);
+    sd.tlw = (float*)bump.take((G + 1) * B * c.target.vocab * 4);
+    rd2.n_rows = (int*)bump.take(4);
+    rd2.b = (int*)bump.take(B * 4);
+    rd2.tok = (int*)bump.take(B * 4);
+    rd2.pos = (int*)bump.take(B * 4);
+    rd2.slot = (int*)bump.take(B * 4);
+  }
   float* tau = (float*)bump.take(4);
   int* draft_tok = (int*)bump.take((size_t)c.max_batch * 4);
   float* score = (float*)bump.take((size_t)c.max_batch * 4);
@@ -347,6 +379,10 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
     ctx->draft_tok = draft_tok; ctx->score = score; ctx->accept = accept; ctx->rej_idx = rej_idx;
     ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows;
     ctx->ent_off = ent_off; ctx->t_last = t_last; ctx->coin_kept = coin_kept; ctx->dl = dl; ctx->tl = tl;
+    sd.st = st; sd.coin_kept = coin_kept; sd.V = c.target.vocab;
+    sd.seed_lo = (unsigned)(c.seed & 0xFFFFFFFFull); sd.seed_hi = (unsigned)(c.seed >> 32);
+    sd.inv_temperature = c.temperature > 0.f ? 1.0f / c.temperature : 0.f;
+    ctx->sd = sd; ctx->sd_rd2 = rd2;
   }
   (void)scratch_begin; (void)scratch_end;
   return total;
@@ -565,6 +601,24 @@ int check_room(sprinter_ctx* ctx, long long extra_steps) {
   return SPRINTER_OK;
 }
 
+// Polls a pinned word a kernel stores (ticket << 32) | value into; after 2 s without the ticket it falls back to
+// a stream synchronisation.
+int wait_ticket(sprinter_ctx* ctx, volatile unsigned long long* word, unsigned ticket, int* value, const char* what) {
+  const auto t0 = std::chrono::steady_clock::now();
+  for (unsigned spin = 0;; ++spin) {
+    const unsigned long long v = *word;
+    if ((unsigned)(v >> 32) == ticket) { *value = (int)(unsigned)(v & 0xFFFFFFFFull); return SPRINTER_OK; }
+    if ((spin & 0xFFF) == 0xFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+      if (hipStreamSynchronize(ctx->stream) != hipSuccess)
+        return fail(ctx, SPRINTER_E_HIP, "waiting for the device failed: %s", hipGetErrorString(hipGetLastError()));
+      const unsigned long long v2 = *word;
+      if ((unsigned)(v2 >> 32) != ticket) return fail(ctx, SPRINTER_E_HIP, "%s", what);
+      *value = (int)(unsigned)(v2 & 0xFFFFFFFFull);
+      return SPRINTER_OK;
+    }
+  }
+}
+
 int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, int32_t* g_tok, uint8_t* g_accept,
                   float* g_score, int32_t* g_draft_tok) {
   hipStream_t s = ctx->stream;
@@ -597,20 +651,8 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
   // microseconds; after 2 s without the ticket it falls back to a stream synchronisation.
   int R = -1;
   {
-    volatile unsigned long long* word = ctx->host_counts;
-    const auto t0 = std::chrono::steady_clock::now();
-    for (unsigned spin = 0;; ++spin) {
-      const unsigned long long v = *word;
-      if ((unsigned)(v >> 32) == da.ticket) { R = (int)(unsigned)(v & 0xFFFFFFFFull); break; }
-      if ((spin & 0xFFF) == 0xFFF && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
-        if (hipStreamSynchronize(s) != hipSuccess)
-          return fail(ctx, SPRINTER_E_HIP, "waiting for the draft pass failed: %s", hipGetErrorString(hipGetLastError()));
-        const unsigned long long v2 = *word;
-        if ((unsigned)(v2 >> 32) != da.ticket) return fail(ctx, SPRINTER_E_HIP, "the draft pass did not report its rejected rows");
-        R = (int)(unsigned)(v2 & 0xFFFFFFFFull);
-        break;
-      }
-    }
+    int rc = wait_ticket(ctx, ctx->host_counts, da.ticket, &R, "the draft pass did not report its rejected rows");
+    if (rc) return rc;
   }
   if (R < 0 || R > B) return fail(ctx, SPRINTER_E_HIP, "device reported %d rejected rows of %d", R, B);
   SdArgs sa;
@@ -859,6 +901,7 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
   ctx->B = B;
   ctx->max_prompt_len = pmax;
   ctx->steps_done = 0;
+  ctx->run_kind = 0; ctx->sd_wait_ticket = 0;
   Model &dq = ctx->draft, &tp = ctx->target;
   if (ctx->cfg.dtype == SPRINTER_BF16) {
     // Chunked prefill: all (row, position) pairs, row-major, go through both models rows_alloc at a time with the
@@ -910,6 +953,8 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
   if (rc) return rc;
   rc = check_room(ctx, 1);
   if (rc) return rc;
+  if (ctx->run_kind == 2) return fail(ctx, SPRINTER_E_STATE, "speculative-decoding rounds were run since the last prefill");
+  ctx->run_kind = 1;
   if (ctx->cfg.target_ctx_mode == 1 && out && (out->target_logits || out->target_hidden))
     return fail(ctx, SPRINTER_E_CONFIG, "target_logits / target_hidden are not produced with the full-prefix target context");
   rc = build_mega(ctx);
@@ -933,6 +978,8 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
   if (rc) return rc;
   rc = check_room(ctx, n_tokens);
   if (rc) return rc;
+  if (ctx->run_kind == 2) return fail(ctx, SPRINTER_E_STATE, "speculative-decoding rounds were run since the last prefill");
+  if (n_tokens > 0) ctx->run_kind = 1;
   rc = build_mega(ctx);
   if (rc) return rc;
   launch_reset_gen_idx(ctx->st.counters, ctx->stream);
@@ -951,6 +998,85 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
   }
   ctx->steps_done += n_tokens;
   return hip_status(ctx, "sprinter_generate");
+}
+
+int sprinter_sd_generate(sprinter_ctx* ctx, int gamma, int n_rounds, int32_t* dev_out_tok, int tok_stride,
+                         int32_t* dev_out_n_tok, int32_t* dev_out_n_acc, int32_t* dev_out_draft) {
+  if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_sd_generate: NULL context");
+  int rc = check_ready(ctx);
+  if (rc) return rc;
+  if (!ctx->prefilled) return fail(ctx, SPRINTER_E_STATE, "no prefill has been done");
+  if (ctx->cfg.sd_gamma <= 0) return fail(ctx, SPRINTER_E_CONFIG, "the context was created with sd_gamma = 0");
+  if (gamma < 1 || gamma > ctx->cfg.sd_gamma)
+    return fail(ctx, SPRINTER_E_RANGE, "gamma %d outside [1, sd_gamma = %d]", gamma, ctx->cfg.sd_gamma);
+  if (!(ctx->cfg.temperature > 0.f)) return fail(ctx, SPRINTER_E_CONFIG, "speculative decoding needs a temperature > 0");
+  if (n_rounds < 0) return fail(ctx, SPRINTER_E_RANGE, "n_rounds %d < 0", n_rounds);
+  if (dev_out_tok && tok_stride < n_rounds * (gamma + 1))
+    return fail(ctx, SPRINTER_E_RANGE, "tok_stride %d < n_rounds * (gamma + 1) = %d", tok_stride, n_rounds * (gamma + 1));
+  if (ctx->run_kind == 1) return fail(ctx, SPRINTER_E_STATE, "decode steps were run since the last prefill");
+  if ((long long)ctx->max_prompt_len - 1 + ctx->steps_done + (long long)n_rounds * (gamma + 1) > ctx->cfg.max_seq)
+    return fail(ctx, SPRINTER_E_RANGE, "prompt length %d + %lld tokens so far + %d rounds of up to %d exceeds max_seq %d",
+                ctx->max_prompt_len, ctx->steps_done, n_rounds, gamma + 1, ctx->cfg.max_seq);
+  hipStream_t s = ctx->stream;
+  const int B = ctx->B, rows = ctx->rows_alloc;
+  Model &dq = ctx->draft, &tp = ctx->target;
+  const size_t Vd = dq.md.V, Vt = tp.md.V;
+  SdBase sd = ctx->sd;
+  sd.B = B; sd.gamma = gamma;
+  volatile unsigned long long* word = ctx->host_counts + 2;
+  const bool fresh = ctx->run_kind == 0;
+  launch_sd_begin(sd, fresh ? 1 : 0, s);       // clears the per-call token counts; fresh: one draft entry per row
+  if (fresh) { ctx->sd_next_entries = B; ctx->sd_wait_ticket = 0; }
+  if (n_rounds > 0) ctx->run_kind = 2;
+  const RowDescW D[2] = {RowDescW{dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos, dq.rd_slot}, ctx->sd_rd2};
+  const RowDescW T{tp.rd_n, tp.rd_b, tp.rd_tok, tp.rd_pos, tp.rd_slot};
+  auto ro = [](const RowDescW& w) { return RowDesc{w.n_rows, w.b, w.tok, w.pos, w.slot}; };
+  for (int r = 0; r < n_rounds; ++r) {
+    // entries of the first draft pass: the previous round's finish kernel reports them (B plus the rows whose
+    // window was kept whole)
+    if (ctx->sd_wait_ticket) {
+      int e0 = -1;
+      rc = wait_ticket(ctx, word, ctx->sd_wait_ticket, &e0, "the previous round did not report its draft entries");
+      if (rc) return rc;
+      ctx->sd_wait_ticket = 0;
+      ctx->sd_next_entries = e0;
+    }
+    const int E0 = ctx->sd_next_entries;
+    if (E0 < B || E0 > 2 * B) return fail(ctx, SPRINTER_E_HIP, "device reported %d draft entries for %d rows", E0, B);
+    ctx->steps_done += gamma + 1;
+    // 1. gamma draft passes; the first may carry two entries for some rows (in list order, so that the second
+    //    finds the first one cached)
+    for (int start = 0; start < E0; start += rows) {
+      const int n = std::min(rows, E0 - start);
+      launch_sd_take_chunk(sd, start, n, D[0], ctx->t_last, s);
+      forward(ctx, dq, ro(D[0]), n, true, 0u, sd.dlw + (size_t)start * Vd, E0 > B);
+      launch_sd_draft_next(sd, 0, dq.sc.am_part, dq.sc.n_lm_wg, rows, ro(D[0]), ctx->t_last, start, D[1], n, s);
+    }
+    for (int j = 1; j < gamma; ++j) {
+      const RowDescW &in = D[j & 1], &out = D[(j + 1) & 1];
+      const int base = 2 * B + (j - 1) * B;
+      forward(ctx, dq, ro(in), B, true, 0u, sd.dlw + (size_t)base * Vd, false);
+      launch_sd_draft_next(sd, j, dq.sc.am_part, dq.sc.n_lm_wg, rows, ro(in), nullptr, base, out, B, s);
+    }
+    // 2. the target over gamma + 1 positions of every row, 3. coin / residual / extra token per entry
+    const int E = B * (gamma + 1);
+    for (int start = 0; start < E; start += rows) {
+      const int n = std::min(rows, E - start);
+      launch_sd_target_list(sd, start, n, T, s);
+      forward(ctx, tp, tp.rd(), n, true, 1u, sd.tlw + (size_t)start * Vt, true);
+      launch_sd_window_check(sd, start, n, tp.sc.am_part, tp.sc.n_lm_wg, rows, s);
+    }
+    // 4. commit
+    SdFinishArgs fa;
+    fa.round = r; fa.n_rounds = n_rounds; fa.tok_stride = tok_stride;
+    fa.o_tok = dev_out_tok; fa.o_n_tok = dev_out_n_tok; fa.o_n_acc = dev_out_n_acc; fa.o_draft = dev_out_draft;
+    fa.host_word = ctx->host_counts + 2;
+    fa.ticket = ++ctx->ticket;
+    if (fa.ticket == 0) fa.ticket = ++ctx->ticket;
+    launch_sd_round_finish(sd, fa, s);
+    ctx->sd_wait_ticket = fa.ticket;
+  }
+  return hip_status(ctx, "sprinter_sd_generate");
 }
 
 int sprinter_set_tau(sprinter_ctx* ctx, float tau) {

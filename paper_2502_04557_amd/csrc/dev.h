@@ -136,6 +136,15 @@ __device__ __forceinline__ u64 pack_key(float y, unsigned n) {
 }
 __device__ __forceinline__ int key_index(u64 k) { return (int)(0xFFFFFFFFu - (unsigned)(k & 0xFFFFFFFFull)); }
 
+// Largest key of row m over the per-workgroup partial results part[n_wg][Mpad] (all 64 lanes get it).
+__device__ __forceinline__ u64 merge_partials(const u64* part, int n_wg, int Mpad, int m, int lane) {
+  u64 k = 0;
+  for (int i = lane; i < n_wg; i += 64) k = umax64(k, part[(size_t)i * Mpad + m]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) k = umax64(k, shfl_xor_u64(k, o));
+  return k;
+}
+
 __device__ __forceinline__ u64 sample_key(float logit, const SamplerArgs& sa, int b, int t, int n) {
   float y = logit;
   if (sa.inv_temperature > 0.0f)

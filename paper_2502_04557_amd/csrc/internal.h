@@ -166,6 +166,46 @@ struct SdArgs {
 void launch_sd_correct(const SdArgs& a, int max_rows, hipStream_t s);
 void launch_set_i32(int* p, int v, hipStream_t s);
 
+// ---- standard speculative decoding (Sec. 2, Eq. (1)) on the same models: k_sd.hip -------------------
+struct RowDescW { int* n_rows; int* b; int* tok; int* pos; int* slot; };   // a writable RowDesc
+struct SdBase {
+  State st;
+  int B, gamma, V;
+  int* len_dc;            // [B] entries in the draft cache (one behind len_q after a window that was kept whole)
+  int* win;               // [B][gamma] the round's draft tokens
+  int* qrow;              // [B][gamma] row of dlw with the draft logits behind win[b][j]
+  unsigned char* kept;    // [B][gamma] outcome of the p/q coin
+  int* alt;               // [B][gamma + 1] residual draw where the coin failed; [gamma]: the extra token
+  // work list of a round's first draft pass: 1 or 2 entries per row (row-major, ascending position)
+  int* d0_n; int* d0_b; int* d0_tok; int* d0_pos; int* d0_last;
+  float* dlw;             // draft logits: rows [0, 2B) first pass (by entry), then B rows per further pass
+  float* tlw;             // target logits by entry b * (gamma + 1) + j
+  int* o_cnt;             // [B] tokens written to the caller's array so far
+  unsigned seed_lo, seed_hi; float inv_temperature;
+  int* coin_kept;
+};
+// Start of a call: clears the per-call token counts; fresh (first rounds after a prefill): the draft cache is level
+// with the target's, one entry per row.
+void launch_sd_begin(const SdBase& a, int fresh, hipStream_t s);
+// Entries [start, start + n) of the first-pass work list become row descriptors (is_last[i]: last entry of its row).
+void launch_sd_take_chunk(const SdBase& a, int start, int n, RowDescW out, int* is_last, hipStream_t s);
+// After draft pass j over the rows of `in`: the sampled token of every (last) entry joins the window and the
+// token history and becomes the row's input of the next pass (`out`, one entry per batch row).
+void launch_sd_draft_next(const SdBase& a, int j, const unsigned long long* am_part, int n_lm_wg, int Mpad, RowDesc in,
+                          const int* is_last, int logits_row_base, RowDescW out, int max_rows, hipStream_t s);
+// Entries [start, start + n) of the target pass: entry e = b * (gamma + 1) + j reads position len_q[b] + j.
+void launch_sd_target_list(const SdBase& a, int start, int n, RowDescW out, hipStream_t s);
+// One workgroup per entry of the chunk: the p/q coin and, where it fails, the residual draw; entry gamma of a
+// row takes the target's own sample (the extra token).
+void launch_sd_window_check(const SdBase& a, int start, int n, const unsigned long long* am_part, int n_lm_wg, int Mpad,
+                            hipStream_t s);
+struct SdFinishArgs {
+  int round, n_rounds, tok_stride;
+  int* o_tok; int* o_n_tok; int* o_n_acc; int* o_draft;
+  unsigned long long* host_word; unsigned ticket;   // receives (ticket << 32) | entries of the next first draft pass
+};
+void launch_sd_round_finish(const SdBase& a, const SdFinishArgs& f, hipStream_t s);
+
 void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const int* prompt_len,
                          int* n_rows, int* rb, int* rtok, int* rpos, int* rslot, hipStream_t s);
 void launch_prefill_begin(const int* prompt, int max_prompt, int B, State st, int* rej_idx, int* n_rej, hipStream_t s);

@@ -7,14 +7,6 @@
 namespace sprinter {
 
 // ====================================== decide: arg-max merge, threshold, compaction
-__device__ __forceinline__ u64 merge_partials(const u64* part, int n_wg, int Mpad, int m, int lane) {
-  u64 k = 0;
-  for (int i = lane; i < n_wg; i += 64) k = umax64(k, part[(size_t)i * Mpad + m]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) k = umax64(k, shfl_xor_u64(k, o));
-  return k;
-}
-
 // Single workgroup of 1024 threads (B <= 1024).  accept <=> sigmoid(logit) >= tau in float32.
 // Rejected rows are listed in ascending order: ballot + popcount inside each wave,
 // wave totals prefix-summed through LDS.

@@ -148,3 +148,58 @@ def compare_sd(cfg, g, rec):
     rep["residual_draws"] = int(both.sum())
     assert not (bad & ~near).any(), f"residual draw differs outside the band at {np.argwhere(bad & ~near)[:5]}"
     return rep
+
+
+def sd_rounds_to_lists(g):
+    """GPU outputs of sd_generate -> (token lists per row, n_acc [B, R], draft [B, R, gamma]); checks the
+    bookkeeping every run must satisfy exactly: counts add up and kept draft tokens are the committed ones."""
+    tok, n_tok, n_acc, draft = g["tok"], g["n_tok"], g["n_acc"], g["draft"]
+    B, R, G = draft.shape
+    assert (n_acc >= 0).all() and (n_acc <= G).all()
+    assert np.array_equal(n_tok, (n_acc + 1).sum(1))
+    lists = []
+    for b in range(B):
+        row = [int(x) for x in tok[b, :n_tok[b]]]
+        assert (tok[b, n_tok[b]:] == -1).all()               # nothing written past the count
+        at = 0
+        for r in range(R):
+            k = int(n_acc[b, r])
+            assert row[at:at + k] == [int(x) for x in draft[b, r, :k]]
+            at += k + 1
+        lists.append(row)
+    return lists, n_acc, draft
+
+
+def compare_sd_rounds(cfg, g, rec, rows=None):
+    """Standard speculative decoding: GPU outputs against the oracle replayed on the GPU's history.
+      draft    token mismatch tolerated iff the oracle's top-2 margin <= 2 eps / T
+      coin     kept / not-kept mismatch tolerated iff |ln coin - ln(p(x)/q(x))| <= 4 eps / T
+      last     (residual draw or extra token) mismatch tolerated iff the oracle's top-2 margin is within
+               (2 eps / T) * band, band = sum over the two candidates of (p + q) / (p - q) for a residual draw, 1 for
+               the extra token."""
+    eps, T = eps_of(cfg), cfg.temperature
+    lists, n_acc, draft = sd_rounds_to_lists(g)
+    sel = list(range(len(lists))) if rows is None else list(rows)
+    B, R, G = len(sel), n_acc.shape[1], draft.shape[2]
+    rep = dict(rounds=B * R, tokens=int(sum(len(lists[b]) for b in sel)), draft_flips=0, coin_flips=0, last_flips=0,
+               mean_kept=float(n_acc[sel].mean()))
+    for i, b in enumerate(sel):
+        at = 0
+        for r in range(R):
+            k = int(n_acc[b, r])
+            for j in range(G):
+                if draft[b, r, j] != rec["own_draft"][i, r, j]:
+                    assert rec["draft_margin"][i, r, j] <= 2 * eps / T, ("draft token", b, r, j)
+                    rep["draft_flips"] += 1
+            for j in range(min(k + 1, G)):
+                assert rec["checked"][i, r, j]
+                kept_gpu = j < k
+                if kept_gpu != bool(rec["kept"][i, r, j]):
+                    assert abs(np.log(rec["coin"][i, r, j]) - rec["log_ratio"][i, r, j]) <= 4 * eps / T, ("coin", b, r, j)
+                    rep["coin_flips"] += 1
+            last = lists[b][at + k]
+            if last != rec["last_tok"][i, r]:
+                assert rec["last_margin"][i, r] <= (2 * eps / T) * rec["last_band"][i, r], ("window end", b, r, k)
+                rep["last_flips"] += 1
+            at += k + 1
+    return rep

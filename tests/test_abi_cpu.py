@@ -31,7 +31,7 @@ def test_exports_every_declared_symbol(lib):
 def test_struct_layout_matches_header():
     from paper_2502_04557_amd import binding
     assert C.sizeof(binding.ModelCfgC) == 40
-    assert C.sizeof(binding.CfgC) == 2 * 40 + 5 * 4 + 2 * 4 + 8 + 2 * 4 + 4   # incl. 4 bytes padding before seed
+    assert C.sizeof(binding.CfgC) == 2 * 40 + 5 * 4 + 2 * 4 + 8 + 4 * 4 + 4   # incl. 4 bytes padding before seed
     assert binding.CfgC.seed.offset % 8 == 0
     assert C.sizeof(binding.StepOutC) == 10 * 8 and C.sizeof(binding.StatsC) == 32
 
@@ -68,6 +68,8 @@ def test_config_validation(lib):
         (replace(base, dtype=7), "dtype"),
         (replace(base, target_ctx_mode=2), "target_ctx_mode"),
         (replace(base, reject_mode=2), "reject_mode"),
+        (replace(base, sd_gamma=17), "sd_gamma"),
+        (replace(base, sd_gamma=-1), "sd_gamma"),
         (replace(base, reject_mode=1, temperature=0.0), "temperature"),
         (replace(base, temperature=-1.0), "temperature"),
         (replace(base, draft=replace(base.draft, arch=5)), "arch"),
@@ -86,3 +88,4 @@ def test_config_validation(lib):
     assert lib.sprinter_step(None, None) == -1
     assert lib.sprinter_generate(None, 4, None, None, None, None) == -1
     assert lib.sprinter_prefill(None, None, None, 1, 1) == -1
+    assert lib.sprinter_sd_generate(None, 2, 1, None, 0, None, None, None) == -1

@@ -48,6 +48,7 @@ class SprinterCfg:
     seed: int = 0
     target_ctx_mode: int = CTX_OWN_HISTORY
     reject_mode: int = 0
+    sd_gamma: int = 0            # > 0: buffers for the speculative-decoding baseline with windows up to this size
     # workload description (not part of the C struct)
     name: str = ""
     batch: int = 1
