@@ -116,6 +116,116 @@ def cpu_baseline(cfg, weights, n_rows, max_seconds=15.0, max_steps=64):
                        f"in {dt:.1f} s (NumPy float64, os.cpu_count()={os.cpu_count()})")
 
 
+def cpu_baseline_sd(cfg, weights, n_rows, gamma, max_seconds=15.0, max_rounds=16):
+    """The speculative-decoding oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import workloads as W
+    from oracle import model as om, sprinter as osp, sd_baseline as osd
+    dw, tw, _ = weights
+    d, t = om.Decoder(cfg.draft, dw), om.Decoder(cfg.target, tw)
+    prompts, plen = W.make_prompts(cfg)
+    seqs = [list(map(int, prompts[b, :2])) for b in range(n_rows)]
+    rounds, toks, t0 = 0, 0, time.perf_counter()
+    dc = tc = None
+    while rounds < max_rounds and time.perf_counter() - t0 < max_seconds:
+        # one call per round so that the run can stop on the time bound; the caches carry over
+        m = max(len(q) for q in seqs)
+        pr = np.array([q + [0] * (m - len(q)) for q in seqs], dtype=np.int32)
+        pl = np.array([len(q) for q in seqs], np.int32)
+        if dc is None:
+            dc, tc = osp.prefill(d, pr, pl), osp.prefill(t, pr, pl)
+        rec = osd.sd_generate(d, t, pr, pl, 1, gamma, cfg.temperature, cfg.seed, draft_caches=dc, target_caches=tc)
+        for b in range(n_rows):
+            seqs[b].extend(rec["tok"][b])
+            toks += len(rec["tok"][b])
+        rounds += 1
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=toks / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"{cfg.name}: first {n_rows} rows, prompts cut to 2 tokens, {rounds} rounds of gamma = {gamma} "
+                       f"in {dt:.1f} s (NumPy float64, os.cpu_count()={os.cpu_count()})")
+
+
+def bench_sd(args, base):
+    """Standard speculative decoding on the same workload: a step is one round (gamma draft passes, one target
+    pass over gamma + 1 positions per row, the p/q check)."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2502_04557_amd import binding
+    K, Wm, G = args.steps, args.warmup, args.gamma
+    pmax = base.prompt_len
+    need = pmax + (Wm + K) * (G + 1)
+    lim = min(m.max_pos for m in (base.draft, base.target))
+    if need > lim:
+        raise SystemExit(f"prompt {pmax} + {Wm + K} rounds of up to {G + 1} tokens exceeds the models' context {lim}")
+    cfg = replace(base, max_seq=max(base.max_seq, need), sd_gamma=G)
+    t0 = time.time()
+    weights = W.make_weights(cfg)
+    prompts, plen = W.make_prompts(cfg)
+    print(f"[bench] {cfg.name}: weights generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    s = binding.Sprinter(cfg, "cuda:0")
+    for which, w in zip((binding.DRAFT, binding.TARGET, binding.VERIFIER), weights):
+        s.load_weights(which, w)
+    B, dev = len(plen), s.device
+    s.prefill(prompts, plen)
+    lens = plen.astype(np.int64).copy()
+    if Wm:
+        lens += s.sd_generate(G, Wm)["n_tok"].cpu().numpy()
+    n_tok = torch.zeros(B, dtype=torch.int32, device=dev)
+    n_acc = torch.zeros(B, K, dtype=torch.int32, device=dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(s.stream)
+    s.sd_generate_into(G, K, n_tok=n_tok, n_acc=n_acc)
+    ev1.record(s.stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    na = n_acc.cpu().numpy().astype(np.int64)
+    tokens = int(n_tok.cpu().numpy().sum())
+    # bytes a round must move: the draft's weights gamma times, the target's once; every draft pass reads the row's
+    # cache and writes one entry; the target pass reads the row's cache once for its gamma + 1 positions and
+    # writes their entries
+    es = 4 if cfg.dtype == 0 else 2
+    Wq, Wp = model_bytes(cfg.draft, es), model_bytes(cfg.target, es)
+    kq, kp = kv_bytes_per_token(cfg.draft, es), kv_bytes_per_token(cfg.target, es)
+    L = lens[:, None] + np.concatenate([np.zeros((B, 1), np.int64), np.cumsum(na + 1, 1)[:, :-1]], 1)   # tokens before round
+    per_round = np.full(K, float(G * Wq + Wp))
+    for j in range(G):
+        per_round += ((L + j + 1) * kq).sum(0)
+    per_round += ((L + 2 * (G + 1)) * kp).sum(0)
+    round_ms = ev_ms / K
+    achieved = per_round.mean() / (round_ms * 1e-3) / 1e9
+    out = {
+        "metric": "generated tokens/sec at batch B (1 GPU)",
+        "value": tokens / wall, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": wall * 1e3 / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: standard speculative decoding, gamma {G}; batch {B}, prompt {pmax}, "
+                               f"T {cfg.temperature}; draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target "
+                               f"L{cfg.target.n_layer} d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init "
+                               f"weights, Zipf(1.1) prompts", "batch": B, "prompt_len": pmax, "gamma": G},
+        "tokens_per_round": tokens / (B * K),
+        "target_calls_per_token": B * K / tokens,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "one round (all kernels of sprinter_sd_generate)",
+                     "bytes_per_launch": float(per_round.mean()), "ms_per_launch": round_ms},
+    }
+    s.close()
+    del s
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_sd(cfg, weights, B, G)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +239,10 @@ def main():
     ap.add_argument("--reject-mode", choices=("replace", "sd"), default="replace",
                     help="replace: the target's sample replaces a rejected token (the headline path); "
                          "sd: keep it with probability min(1, p/q), else draw from the residual of Eq. (1)")
+    ap.add_argument("--method", choices=("sprinter", "sd"), default="sprinter",
+                    help="sprinter: the decode step of the paper's method (the headline); sd: standard speculative "
+                         "decoding on the same models (Sec. 2), one round per step")
+    ap.add_argument("--gamma", type=int, default=4, help="--method sd: draft tokens per round")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
@@ -146,6 +260,8 @@ def main():
     base = W.config(args.config)
     K, Wm = args.steps, args.warmup
     pmax = base.prompt_len
+    if args.method == "sd":
+        return bench_sd(args, base)
     need = pmax + Wm + K
     lim = min(m.max_pos for m in (base.draft, base.target))
     if need > lim:

@@ -12,7 +12,9 @@ generator; Gumbel-max chi-square against softmax; transformer special cases
 repeated heads, cached == uncached forward); the five loop invariants (accept
 rule, target placement, lengths, tau=0 == pure draft, tau>1 == pure target);
 run-length law and stopping time of Thm 3.2 / Thm 3.3 with an i.i.d. verifier;
-output mixture law; brute-force compaction.
+output mixture law; brute-force compaction; for standard speculative decoding
+(sd_baseline.py): tokens-per-round closed form, target-chain law, stream pattern
+with identical models, uncached re-derivation of every committed token.
 Parity unpinned: the FLOP counts of Table 5 and the latencies of Table 2 (the
 paper does not state the accounting / hardware); they are not computed here.
 """
