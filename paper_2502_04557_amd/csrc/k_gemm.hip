@@ -405,8 +405,10 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm16<1, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
   else {
     // column tiles per wave that share the activation fragments: as many as leave about 192 workgroups
-    const int passes = (max_rows + 63) / 64;
-    const int mt = max_rows <= 32 ? 2 : max_rows <= 48 ? 3 : 4;
+    // as few passes over the weights as 4 row tiles per pass allow, the row tiles spread evenly over them
+    // (80 rows: 2 passes of 3 tiles, not 4 + 1)
+    const int row_tiles = (max_rows + 15) / 16, passes = (row_tiles + 3) / 4;
+    const int mt = std::max(2, (row_tiles + passes - 1) / passes);
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     const int ntw = (!DUAL && mt > 2 && a.n_tiles / 4 >= 192) ? 4 : (a.n_tiles / 2 >= (DUAL ? 256 : 128)) ? 2 : 1;
     const dim3 grid((a.n_tiles + ntw - 1) / ntw, passes, 1);
@@ -468,8 +470,8 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
   // 17+ rows: the workgroup's activation traffic (2 KiB per k tile and 16 rows) is what costs, so a wave takes
   // four column tiles (two if that leaves too few workgroups) and K is split until about 256 workgroups exist,
   // with at least two k tiles per wave and share
-  const int passes = (max_rows + 63) / 64;
-  const int mt = max_rows <= 32 ? 2 : max_rows <= 48 ? 3 : 4;
+  const int row_tiles = (max_rows + 15) / 16, passes = (row_tiles + 3) / 4;
+  const int mt = std::max(2, (row_tiles + passes - 1) / passes);
   const int s_max = std::max(1, std::min(max_shares, a.Kt / 16));
   int ntw = 4, groups = (a.n_tiles + 3) / 4, sk = std::min(s_max, std::max(1, 256 / groups));
   if (groups * sk < 192) { ntw = 2; groups = (a.n_tiles + 1) / 2; sk = std::min(s_max, std::max(1, 256 / groups)); }
