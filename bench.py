@@ -163,7 +163,7 @@ def bench_sd(args, base):
     lim = min(m.max_pos for m in (base.draft, base.target))
     if need > lim:
         raise SystemExit(f"prompt {pmax} + {Wm + K} rounds of up to {G + 1} tokens exceeds the models' context {lim}")
-    cfg = replace(base, max_seq=max(base.max_seq, need), sd_gamma=G)
+    cfg = replace(base, max_seq=max(base.max_seq, need), sd_gamma=G, chunk_rows=args.chunk_rows)
     t0 = time.time()
     weights = W.make_weights(cfg)
     prompts, plen = W.make_prompts(cfg)
@@ -243,6 +243,8 @@ def main():
                     help="sprinter: the decode step of the paper's method (the headline); sd: standard speculative "
                          "decoding on the same models (Sec. 2), one round per step")
     ap.add_argument("--gamma", type=int, default=4, help="--method sd: draft tokens per round")
+    ap.add_argument("--chunk-rows", type=int, default=0,
+                    help="entries per pass of a multi-entry forward (prefill chunks, work lists); 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
@@ -268,7 +270,8 @@ def main():
         raise SystemExit(f"prompt {pmax} + warmup {Wm} + steps {K} exceeds the models' context {lim}")
     cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau,
                   target_ctx_mode=W.CTX_FULL_PREFIX if args.target_ctx == "full" else W.CTX_OWN_HISTORY,
-                  reject_mode=W.REJECT_SD if args.reject_mode == "sd" else W.REJECT_REPLACE)
+                  reject_mode=W.REJECT_SD if args.reject_mode == "sd" else W.REJECT_REPLACE,
+                  chunk_rows=args.chunk_rows)
 
     t0 = time.time()
     weights = W.make_weights(cfg)
@@ -288,7 +291,11 @@ def main():
         s.load_weights(which, w)
     B = len(plen)
     dev = s.device
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     s.prefill(prompts, plen)
+    torch.cuda.synchronize()
+    print(f"[bench] prefill of {int(plen.sum())} prompt tokens: {(time.perf_counter() - t0) * 1e3:.1f} ms", file=sys.stderr, flush=True)
     seen_before = plen.astype(np.int64) - 1
     if Wm:
         wa = s.generate(Wm, want=("tok", "accept"))["accept"].cpu().numpy()

@@ -97,7 +97,11 @@ typedef struct {
  *   sd_gamma > 0 reserves the buffers of sprinter_sd_generate (standard
  *   speculative decoding on the same models) for windows of up to sd_gamma
  *   draft tokens: two arrays of (sd_gamma + 1) * max_batch * vocab floats.
- *   0 <= sd_gamma <= 16; reserved must be 0. */
+ *   0 <= sd_gamma <= 16.
+ *   chunk_rows: rows of the activation buffers = entries one pass over the
+ *   weights takes in a multi-entry forward (prefill, full-prefix work lists,
+ *   speculative-decoding windows).  0 = default (bf16: 1024; float32: 16); else a
+ *   multiple of 64 in [64, 4096].  Never below max_batch rounded up. */
 typedef struct {
   sprinter_model_cfg draft, target;
   int32_t ver_d_in, ver_d_hidden;
@@ -108,7 +112,7 @@ typedef struct {
   int32_t target_ctx_mode;
   int32_t reject_mode;
   int32_t sd_gamma;
-  int32_t reserved;
+  int32_t chunk_rows;
 } sprinter_cfg;
 
 /* Optional per-step outputs of sprinter_step; every field is a device pointer
@@ -180,7 +184,7 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
 /* Starts B rows: resets state and counters and fills both KV caches with
  * positions 0 .. P_b-2 of each prompt; the first decode step then feeds the last
  * prompt token at position P_b-1.  bf16: all (row, position) pairs go through both
- * models in row-major chunks of up to 256 tokens per pass over the weights (the
+ * models in row-major chunks of cfg.chunk_rows tokens per pass over the weights (the
  * kernels of the multi-entry target pass); float32: one pass per position.  The
  * stream is drained every 4 passes.  dev_prompt is [B, max_prompt] int32 (padding
  * is never read), host_prompt_len[B] has 1 <= P_b <= max_prompt.  Errors:

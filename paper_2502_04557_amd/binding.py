@@ -30,7 +30,7 @@ class CfgC(C.Structure):
     _fields_ = [("draft", ModelCfgC), ("target", ModelCfgC), ("ver_d_in", C.c_int32), ("ver_d_hidden", C.c_int32),
                 ("dtype", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("tau", C.c_float),
                 ("temperature", C.c_float), ("seed", C.c_uint64), ("target_ctx_mode", C.c_int32),
-                ("reject_mode", C.c_int32), ("sd_gamma", C.c_int32), ("reserved", C.c_int32)]
+                ("reject_mode", C.c_int32), ("sd_gamma", C.c_int32), ("chunk_rows", C.c_int32)]
 
 
 class StepOutC(C.Structure):
@@ -90,7 +90,7 @@ def _model_c(m) -> ModelCfgC:
 def cfg_to_c(cfg) -> CfgC:
     return CfgC(_model_c(cfg.draft), _model_c(cfg.target), cfg.ver_d_in, cfg.ver_d_hidden, cfg.dtype,
                 cfg.max_batch, cfg.max_seq, cfg.tau, cfg.temperature, cfg.seed, cfg.target_ctx_mode, getattr(cfg, "reject_mode", 0),
-                getattr(cfg, "sd_gamma", 0), 0)
+                getattr(cfg, "sd_gamma", 0), getattr(cfg, "chunk_rows", 0))
 
 
 def _ptr(t):

@@ -135,6 +135,7 @@ size_t act_elems(int dtype, int rows, int K) { return act_plane(dtype, rows, K) 
 size_t packed_elems(int N, int K) { return (size_t)round_up(N, 16) * round_up(K, 32); }
 
 constexpr int MEGA_MAX_WG = 512;
+constexpr int DEFAULT_CHUNK_ROWS = 1024;
 
 const char* check_model(const sprinter_model_cfg& m, const char* who, char* buf, size_t n) {
 #define BAD(...) do { snprintf(buf, n, __VA_ARGS__); return buf; } while (0)
@@ -175,7 +176,8 @@ int validate_cfg(const sprinter_cfg* c, char* buf, size_t n) {
   if (c->reject_mode != 0 && c->reject_mode != 1) BAD("reject_mode %d is not one of 0 (replace), 1 (p/q correction)", c->reject_mode);
   if (c->reject_mode == 1 && !(c->temperature > 0.f)) BAD("reject_mode 1 needs a temperature > 0");
   if (c->sd_gamma < 0 || c->sd_gamma > 16) BAD("sd_gamma %d outside [0, 16]", c->sd_gamma);
-  if (c->reserved != 0) BAD("reserved field must be 0");
+  if (c->chunk_rows != 0 && (c->chunk_rows < 64 || c->chunk_rows > 4096 || c->chunk_rows % 64 != 0))
+    BAD("chunk_rows %d is not 0 or a multiple of 64 in [64, 4096]", c->chunk_rows);
   for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
     int dh = m->d_model / m->n_head, G = m->n_head / m->n_kv_head;
     size_t lds = (size_t)(G * dh + 2 * dh + 4 * G * dh + G * c->max_seq) * 4;
@@ -269,14 +271,28 @@ void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc
   }
 }
 
+// The persistent decode kernel is opt-in (environment, read when the workspace is sized and when the context is
+// created): only then are its per-layer activation buffers part of the workspace.
+bool persistent_requested(const sprinter_cfg& c) {
+  const char* on = getenv("SPRINTER_PERSISTENT");
+  return on && on[0] == '1' && c.dtype == SPRINTER_BF16 && c.target_ctx_mode == 0 && c.reject_mode == 0;
+}
+
+// Rows the activation buffers hold = entries one pass of a multi-entry forward takes (prefill chunks, full-prefix
+// work lists, speculative-decoding windows).
+int chunk_rows_of(const sprinter_cfg& c) {
+  const int batch_rows = rows_alloc_for(c.target_ctx_mode == 1 ? std::min(2 * c.max_batch, 1024) : c.max_batch);
+  const int want = c.chunk_rows > 0 ? c.chunk_rows : (c.dtype == SPRINTER_BF16 ? DEFAULT_CHUNK_ROWS : 16);
+  return std::max(want, batch_rows);
+}
+
 // Lays the whole workspace out; ctx == nullptr only measures.  Returns total bytes.
 size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scratch_begin, size_t* scratch_end) {
   Bump bump(base);
   // full-prefix mode: every committed token reaches the target once, so a step's work list averages one entry
-  // per batch row with wide swings; buffers for twice the batch keep most steps to a single pass
-  // bf16: at least 256 rows, so that prefill runs 256 prompt tokens per pass over the weights (128: 20 % slower, 512: 10 % faster)
-  const int rows = std::max(c.dtype == SPRINTER_BF16 ? 256 : 16,
-                            rows_alloc_for(c.target_ctx_mode == 1 ? std::min(2 * c.max_batch, 1024) : c.max_batch));
+  // per batch row with wide swings; buffers for twice the batch keep most steps to a single pass.
+  // bf16: a prefill pass takes DEFAULT_CHUNK_ROWS prompt tokens per pass over the weights unless cfg.chunk_rows says otherwise
+  const int rows = chunk_rows_of(c);
   carve_model(bump, c, c.draft, ctx ? &ctx->draft : nullptr, rows);
   carve_model(bump, c, c.target, ctx ? &ctx->target : nullptr, rows);
   int chunks = verifier_num_chunks(c.ver_d_hidden);
@@ -334,7 +350,7 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   memset(&mp, 0, sizeof mp);
   LayerW *lw_q = nullptr, *lw_p = nullptr;
   MegaParams* mp_dev = nullptr;
-  if (c.dtype == SPRINTER_BF16) {
+  if (persistent_requested(c)) {
     int which = 0;
     for (const sprinter_model_cfg* mc : {&c.draft, &c.target}) {
       MegaModel& mm = which == 0 ? mp.draft : mp.target;
@@ -768,7 +784,7 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     return fail(nullptr, SPRINTER_E_HIP, "allocation of the pinned count buffer failed");
   }
   memset(ctx->host_counts, 0, 256);
-  if (cfg->dtype == SPRINTER_BF16) {
+  if (persistent_requested(*cfg)) {
     // operand-tile planes of the persistent kernel: padding lanes must read as zero
     for (MegaModel* mm : {&ctx->mega_host.draft, &ctx->mega_host.target}) {
       const int L = mm->md.n_layer;
@@ -788,8 +804,7 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
       if (!(pp && pp[0] == '1')) ctx->mega_host.prof = nullptr;
     }
     // the persistent kernel is opt-in while the per-operation kernels are the faster path
-    const char* on = getenv("SPRINTER_PERSISTENT");
-    if (on && on[0] == '1' && cfg->target_ctx_mode == 0 && cfg->reject_mode == 0) {
+    {
       const int rows = ctx->rows_alloc;
       const int rb = rows_alloc_for(cfg->max_batch);      // row tiles follow the batch; the buffers may hold more rows
       ctx->mega_mt = rb <= 16 ? 1 : rb <= 32 ? 2 : rb <= 64 ? 4 : 8;

@@ -276,6 +276,140 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
   }
 }
 
+// bf16 GEMM for 128+ rows (prefill chunks, long work lists): the 8 waves of a workgroup split the COLUMNS (NTW
+// column tiles each; SwiGLU: one gate + one up tile) and share the activations of 8 row tiles (128 rows) through LDS,
+// so a k tile costs the workgroup 16 KiB of activations (both planes, once) + 8 * NWT KiB of weights for
+// 8 * NWT * 16 MFMAs - a third of the bytes per MFMA of the K-split kernel above, which reads every operand per wave.
+// Two k tiles per stage, two LDS stages: the global loads of stage c + 1 (4 activation fragments per thread into
+// registers, the wave's own weight tiles) are in flight while the MFMAs of stage c run; one barrier per stage.
+// blockIdx.y = group of 128 rows, blockIdx.z = K share (EPI_PART).  The activation buffer must hold every row
+// tile the grid covers (the launcher checks it against the plane size).
+template <int NTW, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
+  constexpr bool DUAL = (EPI == EPI_SWIGLU);
+  constexpr int NWT = NTW * (DUAL ? 2 : 1), MT = 8, KU = 2;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ u32x4 xs[2][KU * 2][MT][64];               // [stage][k tile, plane][row tile][lane]: 64 KiB
+  const int lane = threadIdx.x & 63, w = wave_index();
+  const int Kt = a.Kt, mtile0 = blockIdx.y * MT, nt0 = (blockIdx.x * 8 + w) * NTW;
+  const int sk = (EPI == EPI_PART) ? blockIdx.z : 0, SK = (EPI == EPI_PART) ? gridDim.z : 1;
+  const int k0 = (int)((long long)Kt * sk / SK), k1 = (int)((long long)Kt * (sk + 1) / SK);
+  const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
+  const uint4* __restrict__ W2p = DUAL ? (const uint4*)a.W2 + lane : nullptr;
+  // staging: wave w fetches row tile w of every (k tile, plane) of the stage
+  const u32x4* __restrict__ Xh = (const u32x4*)a.X + (size_t)(mtile0 + w) * Kt * 64 + lane;
+  const u32x4* __restrict__ Xl = Xh + a.x_plane / 8;
+  size_t wrow[NTW];
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt0 + j, a.n_tiles - 1) * Kt * 64;
+  static_assert(KU == 2, "the staging registers are named one by one");
+  struct Regs { u32x4 x0, x1, x2, x3; uint4 w[KU][NWT]; };
+  auto gload = [&](Regs& r, int kt) {
+    const int ka = min(kt, k1 - 1), kb = min(kt + 1, k1 - 1);   // clamped: always a tile of this share
+    r.x0 = Xh[(size_t)ka * 64];
+    r.x1 = Xl[(size_t)ka * 64];
+    r.x2 = Xh[(size_t)kb * 64];
+    r.x3 = Xl[(size_t)kb * 64];
+#pragma unroll
+    for (int u = 0; u < KU; ++u) {
+      const int kc = u ? kb : ka;
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) {
+        r.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
+        if (DUAL) r.w[u][NTW + j] = W2p[wrow[j] + (size_t)kc * 64];
+      }
+    }
+  };
+  auto sstore = [&](int stage, const Regs& r) {
+    xs[stage][0][w][lane] = r.x0;
+    xs[stage][1][w][lane] = r.x1;
+    xs[stage][2][w][lane] = r.x2;
+    xs[stage][3][w][lane] = r.x3;
+  };
+  f32x4 acc[NWT][MT];
+#pragma unroll
+  for (int j = 0; j < NWT; ++j)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  auto compute = [&](int stage, const Regs& r, int kt) {
+#pragma unroll
+    for (int u = 0; u < KU; ++u) {
+      const bool in_k = kt + u < k1;
+      uint4 wv[NWT];
+#pragma unroll
+      for (int j = 0; j < NWT; ++j) wv[j] = in_k ? r.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const u32x4 h = xs[stage][u * 2][mt][lane], l = xs[stage][u * 2 + 1][mt][lane];
+        const uint4 xh = make_uint4(h.x, h.y, h.z, h.w), xl = make_uint4(l.x, l.y, l.z, l.w);
+#pragma unroll
+        for (int j = 0; j < NWT; ++j) {
+          acc[j][mt] = mfma_bf16(xh, wv[j], acc[j][mt]);
+          acc[j][mt] = mfma_bf16(xl, wv[j], acc[j][mt]);
+        }
+      }
+    }
+  };
+  Regs A, B;
+  gload(A, k0);
+  sstore(0, A);
+  const int n_rows = *a.n_rows;                          // only the epilogue needs it
+  __syncthreads();
+  for (int kt = k0; kt < k1; kt += 2 * KU) {
+    gload(B, kt + KU);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(0, A, kt);
+    sstore(1, B);
+    __syncthreads();
+    gload(A, kt + 2 * KU);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(1, B, kt + KU);
+    sstore(0, A);
+    __syncthreads();
+  }
+  // every wave stores its own 128 x 16 NTW block straight from the accumulators (lane l, register v: column l % 16,
+  // row (l / 16) * 4 + v)
+  float* part = (EPI == EPI_PART) ? a.part + (size_t)sk * a.part_stride : nullptr;
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    const int n = (nt0 + j) * 16 + (lane & 15);
+    if (n >= a.N) continue;
+    const float bias = (EPI != EPI_PART && a.bias) ? a.bias[n] : 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int m = (mtile0 + mt) * 16 + (lane >> 4) * 4 + v;
+        if (m >= n_rows) continue;
+        const float s1 = acc[j][mt][v], s2 = DUAL ? acc[NTW + j][mt][v] : 0.f;
+        if constexpr (EPI == EPI_PART) {
+          part[(size_t)m * a.ldo + n] = s1;
+        } else {
+          const float res = (EPI == EPI_RESID) ? a.out_f32[(size_t)m * a.ldo + n] : 0.f;
+          gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, s1, s2, bias, res);
+        }
+      }
+  }
+}
+
+// Launches k_gemm_wide if the row count calls for it and the activation buffer holds every row tile of the grid.
+template <int EPI>
+static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s) {
+  if (max_rows < 128) return false;
+  const int row_groups = (max_rows + 127) / 128;
+  if ((size_t)row_groups * 128 * a.Kt * 32 > a.x_plane) return false;
+  constexpr bool DUAL = EPI == EPI_SWIGLU;
+  const int g2 = (a.n_tiles + 15) / 16, g1 = (a.n_tiles + 7) / 8;
+  if constexpr (!DUAL) {
+    if (g2 * row_groups * sk >= 160) {
+      hipLaunchKernelGGL((k_gemm_wide<2, EPI>), dim3(g2, row_groups, sk), dim3(512), 0, s, a);
+      return true;
+    }
+  }
+  hipLaunchKernelGGL((k_gemm_wide<1, EPI>), dim3(g1, row_groups, sk), dim3(512), 0, s, a);
+  return true;
+}
+
 // bf16 GEMM for at most 16 rows whose output only has to exist as a sum: O-proj and FFN-down add into the
 // residual stream, and the layer norm that follows reads the whole row anyway.  K is split into SK shares
 // over workgroups (workgroup = NTW column tiles x one share), each share leaves its partial product in
@@ -403,6 +537,7 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   if (max_rows <= 16 && a.n_tiles >= 256 && a.Kt < 100)
     hipLaunchKernelGGL((k_gemm16<2, EPI>), dim3((a.n_tiles + 1) / 2), dim3(512), 0, s, a);
   else if (max_rows <= 16) hipLaunchKernelGGL((k_gemm16<1, EPI>), dim3(a.n_tiles), dim3(512), 0, s, a);
+  else if (try_gemm_wide<EPI>(a, max_rows, 1, s)) return;
   else {
     // column tiles per wave that share the activation fragments: as many as leave about 192 workgroups
     // as few passes over the weights as 4 row tiles per pass allow, the row tiles spread evenly over them
@@ -470,6 +605,12 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
   // 17+ rows: the workgroup's activation traffic (2 KiB per k tile and 16 rows) is what costs, so a wave takes
   // four column tiles (two if that leaves too few workgroups) and K is split until about 256 workgroups exist,
   // with at least two k tiles per wave and share
+  if (max_rows >= 128) {           // 128+ rows: column-split workgroups, K shares until about 256 of them exist
+    const int row_groups = (max_rows + 127) / 128, col_groups = (a.n_tiles + 15) / 16;
+    int sk = std::max(1, std::min(std::min(max_shares, a.Kt / 16), (256 + col_groups * row_groups - 1) / (col_groups * row_groups)));
+    a.SK = sk;
+    if (try_gemm_wide<EPI_PART>(a, max_rows, sk, s)) return sk;
+  }
   const int row_tiles = (max_rows + 15) / 16, passes = (row_tiles + 3) / 4;
   const int mt = std::max(2, (row_tiles + passes - 1) / passes);
   const int s_max = std::max(1, std::min(max_shares, a.Kt / 16));

@@ -70,6 +70,8 @@ def test_config_validation(lib):
         (replace(base, reject_mode=2), "reject_mode"),
         (replace(base, sd_gamma=17), "sd_gamma"),
         (replace(base, sd_gamma=-1), "sd_gamma"),
+        (replace(base, chunk_rows=100), "chunk_rows"),
+        (replace(base, chunk_rows=8192), "chunk_rows"),
         (replace(base, reject_mode=1, temperature=0.0), "temperature"),
         (replace(base, temperature=-1.0), "temperature"),
         (replace(base, draft=replace(base.draft, arch=5)), "arch"),

@@ -116,13 +116,13 @@ def test_full_prefix_target_context(kind, dtype):
     """target_ctx_mode 1: before the target scores a rejected position it first consumes the committed tokens
     it has not seen (Sec. 2: p(. | prefix); Alg. 2 runs M_p on Prefix).  The GPU's work list against the oracle
     replayed on the GPU's history.  Segments: the configured threshold; tau = 0 (every row accepts, so every
-    target cache falls behind); tau > 1 (every row rejects: the work list has 16 entries per row - with 19 rows more
-    than the 256 entries of one chunk, rows split over chunk borders); the configured threshold again."""
+    target cache falls behind); tau > 1 (every row rejects: the work list has 16 entries per row - with chunk_rows = 64
+    that is several passes, rows split over chunk borders); the configured threshold again."""
     from dataclasses import replace
     from parity_util import compare_replay
     segments = [(None, 6), (0.0, 15), (1.5, 2), (None, 6)]
     G = sum(n for _, n in segments)
-    cfg = replace(W.mini_config(kind, dtype, n_gen=G), target_ctx_mode=W.CTX_FULL_PREFIX)
+    cfg = replace(W.mini_config(kind, dtype, n_gen=G), target_ctx_mode=W.CTX_FULL_PREFIX, chunk_rows=64)
     p = _pair(cfg, ver_scale=8.0)
     p.gpu.prefill(p.prompts, p.plen)
     parts = []
@@ -144,9 +144,8 @@ def test_full_prefix_target_context(kind, dtype):
         print(kind, dtype, "steps", t0, "..", t0 + n - 1, rep, flush=True)
         t0 += n
     assert np.array_equal(st["target_calls"], (~acc).sum(1))
-    # the first all-reject step has 16 entries per row: with 19 rows that is more than one chunk of 256
-    if cfg.batch == 19:
-        assert 16 * cfg.batch > 256
+    # the first all-reject step has 16 entries per row: more than one pass of 64 entries for either batch (5, 19)
+    assert 16 * cfg.batch > 64
     # after a rejection the row's target cache is complete: the oracle's caches end where its last rejection was
     last_rej = np.array([max(t for t in range(G) if not acc[b, t]) for b in range(cfg.batch)])
     assert np.array_equal(rec["len_p"], p.plen + last_rej)

@@ -49,6 +49,7 @@ class SprinterCfg:
     target_ctx_mode: int = CTX_OWN_HISTORY
     reject_mode: int = 0
     sd_gamma: int = 0            # > 0: buffers for the speculative-decoding baseline with windows up to this size
+    chunk_rows: int = 0          # entries per pass of a multi-entry forward (0 = the library's default)
     # workload description (not part of the C struct)
     name: str = ""
     batch: int = 1
