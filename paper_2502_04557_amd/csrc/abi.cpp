@@ -406,9 +406,10 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
 
 // One model forward over the rows described by rd (device-side count).
 // shared_caches: several rows of rd may belong to one batch row (consecutive positions): every layer appends all
-// new keys / values first and attends in a second launch.
+// new keys / values first and attends in a second launch.  long_runs: those entries come in long runs of
+// consecutive positions (prefill), so the attending launch lets 8 queries share one pass over the row's cache.
 void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool want_head, unsigned stream_id,
-             float* logits_out, bool shared_caches = false) {
+             float* logits_out, bool shared_caches = false, bool long_runs = false) {
   const int dt = ctx->cfg.dtype;
   const ModelDims& md = m.md;
   hipStream_t s = ctx->stream;
@@ -443,7 +444,7 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
                        ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 1);
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 2);
+                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, long_runs ? 3 : 2);
     } else {
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
                        ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
@@ -938,8 +939,8 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
       const int n = (int)std::min<long long>(ctx->rows_alloc, E - start);
       ca.start = (int)start; ca.n = n;
       launch_catchup_chunk(ca, s);
-      forward(ctx, dq, tp.rd(), n, false, 0u, nullptr, true);
-      forward(ctx, tp, tp.rd(), n, false, 1u, nullptr, true);
+      forward(ctx, dq, tp.rd(), n, false, 0u, nullptr, true, true);
+      forward(ctx, tp, tp.rd(), n, false, 1u, nullptr, true, true);
       // bound the number of launches in flight (tools that keep per-dispatch state have died on long backlogs)
       if ((chunk & 3) == 3 && hipStreamSynchronize(s) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
     }

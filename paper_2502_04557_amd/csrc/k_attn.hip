@@ -14,7 +14,7 @@ struct AttnArgs {
   void* kcache; void* vcache; size_t layer_off;
   int H, KVH, dqkv, max_seq, use_rope; float scale;
   void* ao; int ao_K; size_t ao_plane;
-  int phase;   // 0 append + attend, 1 append only, 2 attend only
+  int phase;   // 0 append + attend, 1 append only, 2 attend only, 3 attend only over long runs of one row (launcher only)
 };
 
 template <typename T, int DH, int G>
@@ -375,6 +375,170 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
   }
 }
 
+// Attention for a multi-entry pass whose entries come in long runs of consecutive positions of one batch row (prefill):
+// every key and value of the pass is already in the cache (the append-only launch ran before), so a workgroup takes QB
+// consecutive entries x the GH query heads of one KV head (QB * GH = 8 queries) and streams the row's keys and values
+// ONCE for all of them - each query masks the keys beyond its own position.  A block that straddles two batch rows
+// handles them one after the other.  Same lane layout and online softmax as k_attn_bf16 with 8 query heads.
+template <int DH, int GH, int QB>
+__global__ __launch_bounds__(256) void k_attn_block_bf16(AttnArgs a) {
+  constexpr int NW = 4, VQ = GH * QB, LPK = DH / 8, KPW = 64 / LPK, NB = 4;
+  constexpr float NEG = -1e30f;
+  __shared__ float s_m[NW][VQ], s_l[NW][VQ], s_o[NW][VQ][DH];
+  const int n_rows = *a.rd.n_rows, r0 = blockIdx.y * QB;
+  if (r0 >= n_rows) return;
+  const int kvh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
+  const int chunk = lane % LPK, kin = lane / LPK, S = a.max_seq;
+  const bool upper = chunk >= LPK / 2;
+  const int pchunk = chunk ^ (LPK / 2);
+  const int n_here = min(QB, n_rows - r0);
+  for (int s0 = 0; s0 < n_here;) {
+    const int b = a.rd.b[r0 + s0];
+    int s1 = s0 + 1;
+    while (s1 < n_here && a.rd.b[r0 + s1] == b) ++s1;          // entries s0 .. s1-1 of the block belong to row b
+    const bf16_t* __restrict__ Kc = (const bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+    const bf16_t* __restrict__ Vc = (const bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+    int slot[QB], max_slot = 0;
+#pragma unroll
+    for (int e = 0; e < QB; ++e) {
+      slot[e] = (e >= s0 && e < s1) ? a.rd.slot[r0 + e] : -1;  // -1: not a query of this pass, every key masked
+      max_slot = max(max_slot, slot[e]);
+    }
+    const int n_blocks = (max_slot + 1 + KPW - 1) / KPW;        // a query's own key sits at its slot
+    const int n_rounds = (n_blocks + NW * NB - 1) / (NW * NB);
+    uint4 kA[NB], vA[NB];
+    auto request = [&](int rd) {
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int key = min(((rd * NB + j) * NW + w) * KPW + kin, max_slot);
+        kA[j] = *reinterpret_cast<const uint4*>(Kc + (size_t)key * DH + chunk * 8);
+        vA[j] = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * 8);
+      }
+    };
+    request(0);
+    // the queries: this lane's 8 elements of every (entry, head), rotated by the entry's own angles
+    float q[VQ][8];
+#pragma unroll
+    for (int e = 0; e < QB; ++e) {
+      const int re = r0 + min(max(e, s0), s1 - 1);              // entries outside the run re-read a row of the run
+      const float* __restrict__ y = a.y + (size_t)re * a.dqkv;
+      const float* __restrict__ cs = a.rope + (size_t)re * DH + 2 * (chunk % (LPK / 2)) * 8;
+      float csr[16];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float4 t = reinterpret_cast<const float4*>(cs)[i];
+        csr[4 * i] = t.x; csr[4 * i + 1] = t.y; csr[4 * i + 2] = t.z; csr[4 * i + 3] = t.w;
+      }
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        const float* qs = y + (size_t)(kvh * GH + g) * DH;
+        float qx[8], qp[8];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const float4 t = reinterpret_cast<const float4*>(qs + chunk * 8)[i], u = reinterpret_cast<const float4*>(qs + pchunk * 8)[i];
+          qx[4 * i] = t.x; qx[4 * i + 1] = t.y; qx[4 * i + 2] = t.z; qx[4 * i + 3] = t.w;
+          qp[4 * i] = u.x; qp[4 * i + 1] = u.y; qp[4 * i + 2] = u.z; qp[4 * i + 3] = u.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float c = a.use_rope ? csr[2 * i] : 1.f, sn = a.use_rope ? csr[2 * i + 1] : 0.f;
+          q[e * GH + g][i] = (upper ? qx[i] * c + qp[i] * sn : qx[i] * c - qp[i] * sn) * a.scale;
+        }
+      }
+    }
+    float m[VQ], l[VQ], acc[VQ][8];
+#pragma unroll
+    for (int v = 0; v < VQ; ++v) {
+      m[v] = NEG; l[v] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[v][i] = 0.f;
+    }
+    for (int rd = 0; rd < n_rounds; ++rd) {
+      if (rd > 0) request(rd);
+      float sc[NB][VQ];
+      int keyj[NB];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        keyj[j] = ((rd * NB + j) * NW + w) * KPW + kin;
+        const bf16_t* kt = reinterpret_cast<const bf16_t*>(&kA[j]);
+        float kf[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) kf[i] = bf2f(kt[i]);
+#pragma unroll
+        for (int v = 0; v < VQ; ++v) {
+          float d = 0.f;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) d += q[v][i] * kf[i];
+          sc[j][v] = group_sum<LPK>(d);
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < VQ; ++v) {
+        float mn = m[v];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) mn = keyj[j] <= slot[v / GH] ? fmaxf(mn, sc[j][v]) : mn;
+        const float corr = __expf(m[v] - mn);
+        m[v] = mn;
+        l[v] *= corr;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[v][i] *= corr;
+      }
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vA[j]);
+        float vf[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) vf[i] = bf2f(vt[i]);
+#pragma unroll
+        for (int v = 0; v < VQ; ++v) {
+          const float p = keyj[j] <= slot[v / GH] ? __expf(sc[j][v] - m[v]) : 0.f;
+          l[v] += p;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[v][i] += p * vf[i];
+        }
+      }
+    }
+    // merge the KPW lane groups of the wave, then the waves through LDS
+#pragma unroll
+    for (int v = 0; v < VQ; ++v) {
+#pragma unroll
+      for (int o = LPK; o < 64; o <<= 1) {
+        const float mo = __shfl_xor(m[v], o), lo = __shfl_xor(l[v], o);
+        const float mn = fmaxf(m[v], mo);
+        const float c1 = __expf(m[v] - mn), c2 = __expf(mo - mn);
+        l[v] = l[v] * c1 + lo * c2;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[v][i] = acc[v][i] * c1 + __shfl_xor(acc[v][i], o) * c2;
+        m[v] = mn;
+      }
+      if (kin == 0) {
+        if (chunk == 0) { s_m[w][v] = m[v]; s_l[w][v] = l[v]; }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s_o[w][v][chunk * 8 + i] = acc[v][i];
+      }
+    }
+    __syncthreads();
+    bf16_t* __restrict__ ao = (bf16_t*)a.ao;
+    for (int idx = tid; idx < VQ * DH; idx += NW * 64) {
+      const int v = idx / DH, i = idx % DH, e = v / GH, g = v % GH;
+      if (e < s0 || e >= s1) continue;
+      float mn = s_m[0][v];
+#pragma unroll
+      for (int q4 = 1; q4 < NW; ++q4) mn = fmaxf(mn, s_m[q4][v]);
+      float den = 0.f, num = 0.f;
+#pragma unroll
+      for (int q4 = 0; q4 < NW; ++q4) {
+        const float c = __expf(s_m[q4][v] - mn);
+        den += c * s_l[q4][v];
+        num += c * s_o[q4][v][i];
+      }
+      act_store<bf16_t>(ao, a.ao_plane, r0 + e, (kvh * GH + g) * DH + i, a.ao_K, num / den);
+    }
+    __syncthreads();                                            // LDS is reused by the block's next run
+    s0 = s1;
+  }
+}
+
 static size_t attn_smem_bytes(int DH, int G, int max_seq) {
   return (size_t)(G * DH + 2 * DH + 4 * G * DH + G * max_seq) * sizeof(float);
 }
@@ -384,6 +548,20 @@ static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, int ctx_bou
   // NW = waves per workgroup that share one (row, KV head)'s keys: 8 when the launch has no more workgroups than
   // the chip has compute units and the contexts are long (c5's target pass: 20 rows x 8 KV heads x 1000+ keys),
   // else 4 (at c2's 130-400 keys the 8-wave variant takes 9.5 us against 7.8)
+  if (a.phase == 3) {
+    // attend-only over long runs of consecutive positions: 8 queries share a key stream.  Used at head dimension 64
+    // (c2's prefill 66 -> 58 ms); at 128 the kernel is bound by its dot products, not by the key stream, and the
+    // 8-query variant measured slower (c3's prefill 290 -> 317 ms), as it would with 8 query heads per KV head.
+    if constexpr (DH == 64) {
+      if (G == 1) { hipLaunchKernelGGL((k_attn_block_bf16<DH, 1, 8>), dim3(a.KVH, (max_rows + 7) / 8), dim3(256), 0, s, a); return; }
+      if (G == 2) { hipLaunchKernelGGL((k_attn_block_bf16<DH, 2, 4>), dim3(a.KVH, (max_rows + 3) / 4), dim3(256), 0, s, a); return; }
+      if (G == 4) { hipLaunchKernelGGL((k_attn_block_bf16<DH, 4, 2>), dim3(a.KVH, (max_rows + 1) / 2), dim3(256), 0, s, a); return; }
+    }
+    AttnArgs b = a;
+    b.phase = 2;
+    launch_attn_bf16<DH>(b, G, max_rows, ctx_bound, s);
+    return;
+  }
   dim3 grid(a.KVH, max_rows);
   const bool wide = (long long)a.KVH * max_rows <= 256 && ctx_bound >= 512;
 #define SPRINTER_ATTN(G_) do { if (wide) hipLaunchKernelGGL((k_attn_bf16<DH, G_, 8>), grid, dim3(512), 0, s, a); \
@@ -413,7 +591,7 @@ void launch_attention(int dtype, const ModelDims& md, const float* y, const floa
                       void* kcache, void* vcache, size_t layer_off, int ctx_bound, int max_seq, void* ao,
                       size_t ao_plane, int max_rows, hipStream_t s, int phase) {
   AttnArgs a;
-  a.phase = phase;
+  a.phase = (phase == 3 && dtype == 0) ? 2 : phase;      // the run-sharing kernel exists for bf16 only
   a.y = y; a.rope = rope; a.rd = rd; a.kcache = kcache; a.vcache = vcache; a.layer_off = layer_off;
   a.H = md.H; a.KVH = md.KVH; a.dqkv = md.dqkv; a.max_seq = max_seq; a.use_rope = md.arch == 1;
   a.scale = 1.0f / sqrtf((float)md.dh);
