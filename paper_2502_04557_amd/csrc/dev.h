@@ -166,6 +166,15 @@ __device__ __forceinline__ float group_sum(float v) {
   return v;
 }
 
+// Maximum over an aligned group of 16 consecutive lanes (one DPP row), in every lane of the group.
+__device__ __forceinline__ float group_max16(float v) {
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true)));
+  return v;
+}
+
 __device__ __forceinline__ f32x4 mfma_bf16(uint4 x, uint4 w, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8*>(&x), *reinterpret_cast<bf16x8*>(&w), c, 0,
                                                  0, 0);

@@ -375,166 +375,147 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
   }
 }
 
-// Attention for a multi-entry pass whose entries come in long runs of consecutive positions of one batch row (prefill):
-// every key and value of the pass is already in the cache (the append-only launch ran before), so a workgroup takes QB
-// consecutive entries x the GH query heads of one KV head (QB * GH = 8 queries) and streams the row's keys and values
-// ONCE for all of them - each query masks the keys beyond its own position.  A block that straddles two batch rows
-// handles them one after the other.  Same lane layout and online softmax as k_attn_bf16 with 8 query heads.
-template <int DH, int GH, int QB>
-__global__ __launch_bounds__(256) void k_attn_block_bf16(AttnArgs a) {
-  constexpr int NW = 4, VQ = GH * QB, LPK = DH / 8, KPW = 64 / LPK, NB = 4;
+// Causal attention on the matrix cores for a multi-entry pass whose entries come in runs of consecutive positions of
+// one batch row (prefill); every key and value of the pass is already cached (the append-only launch ran before).
+// One wave per (block of 16 entries, query head).  Per block of 32 keys: S = Q K^T (16 x 32 scores, Q as hi + lo bf16
+// planes so that it enters at float32 precision, K straight from the cache in operand layout), causal mask per
+// query, online softmax in float32 on the accumulator layout (a query's 16 keys of a tile sit in one DPP row),
+// P through LDS into operand layout (hi + lo), V through LDS transposed (the MFMA wants 8 consecutive keys per
+// lane), O += P V.  A block that straddles two batch rows handles its runs one after the other.
+template <int DH>
+__global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
+  constexpr int T = DH / 32, CT = DH / 16, VS = DH + 8, PS = 36;
   constexpr float NEG = -1e30f;
-  __shared__ float s_m[NW][VQ], s_l[NW][VQ], s_o[NW][VQ][DH];
-  const int n_rows = *a.rd.n_rows, r0 = blockIdx.y * QB;
+  __shared__ __attribute__((aligned(16))) bf16_t lds_v[32 * VS];
+  __shared__ __attribute__((aligned(16))) float lds_p[16 * PS];
+  const int n_rows = *a.rd.n_rows, r0 = blockIdx.y * 16;
   if (r0 >= n_rows) return;
-  const int kvh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
-  const int chunk = lane % LPK, kin = lane / LPK, S = a.max_seq;
-  const bool upper = chunk >= LPK / 2;
-  const int pchunk = chunk ^ (LPK / 2);
-  const int n_here = min(QB, n_rows - r0);
+  const int h = blockIdx.x, kvh = h / (a.H / a.KVH), lane = threadIdx.x, l16 = lane & 15, lq = lane >> 4, S = a.max_seq;
+  const int n_here = min(16, n_rows - r0);
   for (int s0 = 0; s0 < n_here;) {
     const int b = a.rd.b[r0 + s0];
     int s1 = s0 + 1;
-    while (s1 < n_here && a.rd.b[r0 + s1] == b) ++s1;          // entries s0 .. s1-1 of the block belong to row b
+    while (s1 < n_here && a.rd.b[r0 + s1] == b) ++s1;            // entries s0 .. s1-1 belong to batch row b
     const bf16_t* __restrict__ Kc = (const bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
     const bf16_t* __restrict__ Vc = (const bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
-    int slot[QB], max_slot = 0;
+    int max_slot = 0;
+    for (int e = s0; e < s1; ++e) max_slot = max(max_slot, a.rd.slot[r0 + e]);
+    int slot[4];                                                 // of this lane's 4 accumulator rows (queries)
 #pragma unroll
-    for (int e = 0; e < QB; ++e) {
-      slot[e] = (e >= s0 && e < s1) ? a.rd.slot[r0 + e] : -1;  // -1: not a query of this pass, every key masked
-      max_slot = max(max_slot, slot[e]);
+    for (int v = 0; v < 4; ++v) {
+      const int e = lq * 4 + v;
+      slot[v] = (e >= s0 && e < s1) ? a.rd.slot[r0 + e] : -1;    // -1: not a query of this run, every key masked
     }
-    const int n_blocks = (max_slot + 1 + KPW - 1) / KPW;        // a query's own key sits at its slot
-    const int n_rounds = (n_blocks + NW * NB - 1) / (NW * NB);
-    uint4 kA[NB], vA[NB];
-    auto request = [&](int rd) {
+    // Q in operand layout: row l16 of the block, elements t * 32 + lq * 8 .. + 8, rotated and scaled
+    uint4 qh[T], ql[T];
+    {
+      const int re = r0 + min(max(l16, s0), s1 - 1);
+      const float* __restrict__ y = a.y + (size_t)re * a.dqkv + (size_t)h * DH;
+      const float* __restrict__ rp = a.rope + (size_t)re * DH;
 #pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        const int key = min(((rd * NB + j) * NW + w) * KPW + kin, max_slot);
-        kA[j] = *reinterpret_cast<const uint4*>(Kc + (size_t)key * DH + chunk * 8);
-        vA[j] = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * 8);
-      }
-    };
-    request(0);
-    // the queries: this lane's 8 elements of every (entry, head), rotated by the entry's own angles
-    float q[VQ][8];
-#pragma unroll
-    for (int e = 0; e < QB; ++e) {
-      const int re = r0 + min(max(e, s0), s1 - 1);              // entries outside the run re-read a row of the run
-      const float* __restrict__ y = a.y + (size_t)re * a.dqkv;
-      const float* __restrict__ cs = a.rope + (size_t)re * DH + 2 * (chunk % (LPK / 2)) * 8;
-      float csr[16];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float4 t = reinterpret_cast<const float4*>(cs)[i];
-        csr[4 * i] = t.x; csr[4 * i + 1] = t.y; csr[4 * i + 2] = t.z; csr[4 * i + 3] = t.w;
-      }
-#pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        const float* qs = y + (size_t)(kvh * GH + g) * DH;
-        float qx[8], qp[8];
+      for (int t = 0; t < T; ++t) {
+        const int d0 = t * 32 + lq * 8, p0 = d0 ^ (DH / 2);
+        const bool upper = d0 >= DH / 2;
+        float x[8], xp[8], cs[16], qv[8];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          const float4 t = reinterpret_cast<const float4*>(qs + chunk * 8)[i], u = reinterpret_cast<const float4*>(qs + pchunk * 8)[i];
-          qx[4 * i] = t.x; qx[4 * i + 1] = t.y; qx[4 * i + 2] = t.z; qx[4 * i + 3] = t.w;
-          qp[4 * i] = u.x; qp[4 * i + 1] = u.y; qp[4 * i + 2] = u.z; qp[4 * i + 3] = u.w;
+          const float4 u = reinterpret_cast<const float4*>(y + d0)[i], w = reinterpret_cast<const float4*>(y + p0)[i];
+          x[4 * i] = u.x; x[4 * i + 1] = u.y; x[4 * i + 2] = u.z; x[4 * i + 3] = u.w;
+          xp[4 * i] = w.x; xp[4 * i + 1] = w.y; xp[4 * i + 2] = w.z; xp[4 * i + 3] = w.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 u = reinterpret_cast<const float4*>(rp + 2 * (d0 % (DH / 2)))[i];
+          cs[4 * i] = u.x; cs[4 * i + 1] = u.y; cs[4 * i + 2] = u.z; cs[4 * i + 3] = u.w;
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const float c = a.use_rope ? csr[2 * i] : 1.f, sn = a.use_rope ? csr[2 * i + 1] : 0.f;
-          q[e * GH + g][i] = (upper ? qx[i] * c + qp[i] * sn : qx[i] * c - qp[i] * sn) * a.scale;
+          const float c = a.use_rope ? cs[2 * i] : 1.f, sn = a.use_rope ? cs[2 * i + 1] : 0.f;
+          qv[i] = (upper ? x[i] * c + xp[i] * sn : x[i] * c - xp[i] * sn) * a.scale;
+        }
+        split2(qv[0], qv[1], qh[t].x, ql[t].x);
+        split2(qv[2], qv[3], qh[t].y, ql[t].y);
+        split2(qv[4], qv[5], qh[t].z, ql[t].z);
+        split2(qv[6], qv[7], qh[t].w, ql[t].w);
+      }
+    }
+    f32x4 O[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) O[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_run[4] = {NEG, NEG, NEG, NEG}, l_run[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int kb = 0; kb <= max_slot; kb += 32) {
+      // stage V[kb .. kb+31][0 .. DH) in LDS (rows beyond the run's last key as zeros: they may hold anything)
+#pragma unroll
+      for (int i = 0; i < DH / 16; ++i) {
+        const int u = lane + 64 * i, key = u / (DH / 8), piece = u % (DH / 8);
+        uint4 val = *reinterpret_cast<const uint4*>(Vc + (size_t)min(kb + key, max_slot) * DH + piece * 8);
+        if (kb + key > max_slot) val = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4*>(lds_v + key * VS + piece * 8) = val;
+      }
+      // scores of the two 16-key tiles
+      f32x4 sc[2];
+#pragma unroll
+      for (int tile = 0; tile < 2; ++tile) {
+        sc[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        const bf16_t* kr = Kc + (size_t)min(kb + tile * 16 + l16, max_slot) * DH + lq * 8;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+          const uint4 kf = *reinterpret_cast<const uint4*>(kr + t * 32);
+          sc[tile] = mfma_bf16(qh[t], kf, sc[tile]);
+          sc[tile] = mfma_bf16(ql[t], kf, sc[tile]);
         }
       }
+      // online softmax: accumulator register v of lane (lq, l16) is query lq * 4 + v, key kb + tile * 16 + l16
+      float p[2][4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const bool ok0 = kb + l16 <= slot[v], ok1 = kb + 16 + l16 <= slot[v];
+        const float mx = group_max16(fmaxf(ok0 ? sc[0][v] : NEG, ok1 ? sc[1][v] : NEG));
+        const float mn = fmaxf(m_run[v], mx);
+        const float corr = __expf(m_run[v] - mn);
+        p[0][v] = ok0 ? __expf(sc[0][v] - mn) : 0.f;
+        p[1][v] = ok1 ? __expf(sc[1][v] - mn) : 0.f;
+        l_run[v] = l_run[v] * corr + group_sum<16>(p[0][v] + p[1][v]);
+        m_run[v] = mn;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) O[ct][v] *= corr;
+        lds_p[(lq * 4 + v) * PS + l16] = p[0][v];
+        lds_p[(lq * 4 + v) * PS + 16 + l16] = p[1][v];
+      }
+      __syncthreads();
+      // P in operand layout: query l16, keys lq * 8 .. + 8 of the block
+      uint4 ph, pl;
+      {
+        const float4 u = *reinterpret_cast<const float4*>(lds_p + l16 * PS + lq * 8);
+        const float4 w = *reinterpret_cast<const float4*>(lds_p + l16 * PS + lq * 8 + 4);
+        split2(u.x, u.y, ph.x, pl.x);
+        split2(u.z, u.w, ph.y, pl.y);
+        split2(w.x, w.y, ph.z, pl.z);
+        split2(w.z, w.w, ph.w, pl.w);
+      }
+#pragma unroll
+      for (int ct = 0; ct < CT; ++ct) {
+        // V^T in operand layout: column ct * 16 + l16, keys lq * 8 .. + 8
+        const bf16_t* vr = lds_v + (lq * 8) * VS + ct * 16 + l16;
+        uint4 vf;
+        vf.x = (unsigned)vr[0] | ((unsigned)vr[VS] << 16);
+        vf.y = (unsigned)vr[2 * VS] | ((unsigned)vr[3 * VS] << 16);
+        vf.z = (unsigned)vr[4 * VS] | ((unsigned)vr[5 * VS] << 16);
+        vf.w = (unsigned)vr[6 * VS] | ((unsigned)vr[7 * VS] << 16);
+        O[ct] = mfma_bf16(ph, vf, O[ct]);
+        O[ct] = mfma_bf16(pl, vf, O[ct]);
+      }
+      __syncthreads();                                           // LDS is rewritten by the next key block
     }
-    float m[VQ], l[VQ], acc[VQ][8];
-#pragma unroll
-    for (int v = 0; v < VQ; ++v) {
-      m[v] = NEG; l[v] = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[v][i] = 0.f;
-    }
-    for (int rd = 0; rd < n_rounds; ++rd) {
-      if (rd > 0) request(rd);
-      float sc[NB][VQ];
-      int keyj[NB];
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        keyj[j] = ((rd * NB + j) * NW + w) * KPW + kin;
-        const bf16_t* kt = reinterpret_cast<const bf16_t*>(&kA[j]);
-        float kf[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) kf[i] = bf2f(kt[i]);
-#pragma unroll
-        for (int v = 0; v < VQ; ++v) {
-          float d = 0.f;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) d += q[v][i] * kf[i];
-          sc[j][v] = group_sum<LPK>(d);
-        }
-      }
-#pragma unroll
-      for (int v = 0; v < VQ; ++v) {
-        float mn = m[v];
-#pragma unroll
-        for (int j = 0; j < NB; ++j) mn = keyj[j] <= slot[v / GH] ? fmaxf(mn, sc[j][v]) : mn;
-        const float corr = __expf(m[v] - mn);
-        m[v] = mn;
-        l[v] *= corr;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[v][i] *= corr;
-      }
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vA[j]);
-        float vf[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) vf[i] = bf2f(vt[i]);
-#pragma unroll
-        for (int v = 0; v < VQ; ++v) {
-          const float p = keyj[j] <= slot[v / GH] ? __expf(sc[j][v] - m[v]) : 0.f;
-          l[v] += p;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) acc[v][i] += p * vf[i];
-        }
-      }
-    }
-    // merge the KPW lane groups of the wave, then the waves through LDS
-#pragma unroll
-    for (int v = 0; v < VQ; ++v) {
-#pragma unroll
-      for (int o = LPK; o < 64; o <<= 1) {
-        const float mo = __shfl_xor(m[v], o), lo = __shfl_xor(l[v], o);
-        const float mn = fmaxf(m[v], mo);
-        const float c1 = __expf(m[v] - mn), c2 = __expf(mo - mn);
-        l[v] = l[v] * c1 + lo * c2;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[v][i] = acc[v][i] * c1 + __shfl_xor(acc[v][i], o) * c2;
-        m[v] = mn;
-      }
-      if (kin == 0) {
-        if (chunk == 0) { s_m[w][v] = m[v]; s_l[w][v] = l[v]; }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s_o[w][v][chunk * 8 + i] = acc[v][i];
-      }
-    }
-    __syncthreads();
     bf16_t* __restrict__ ao = (bf16_t*)a.ao;
-    for (int idx = tid; idx < VQ * DH; idx += NW * 64) {
-      const int v = idx / DH, i = idx % DH, e = v / GH, g = v % GH;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int e = lq * 4 + v;
       if (e < s0 || e >= s1) continue;
-      float mn = s_m[0][v];
+      const float inv = 1.0f / l_run[v];
 #pragma unroll
-      for (int q4 = 1; q4 < NW; ++q4) mn = fmaxf(mn, s_m[q4][v]);
-      float den = 0.f, num = 0.f;
-#pragma unroll
-      for (int q4 = 0; q4 < NW; ++q4) {
-        const float c = __expf(s_m[q4][v] - mn);
-        den += c * s_l[q4][v];
-        num += c * s_o[q4][v][i];
-      }
-      act_store<bf16_t>(ao, a.ao_plane, r0 + e, (kvh * GH + g) * DH + i, a.ao_K, num / den);
+      for (int ct = 0; ct < CT; ++ct) act_store<bf16_t>(ao, a.ao_plane, r0 + e, h * DH + ct * 16 + l16, a.ao_K, O[ct][v] * inv);
     }
-    __syncthreads();                                            // LDS is reused by the block's next run
     s0 = s1;
   }
 }
@@ -548,18 +529,8 @@ static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, int ctx_bou
   // NW = waves per workgroup that share one (row, KV head)'s keys: 8 when the launch has no more workgroups than
   // the chip has compute units and the contexts are long (c5's target pass: 20 rows x 8 KV heads x 1000+ keys),
   // else 4 (at c2's 130-400 keys the 8-wave variant takes 9.5 us against 7.8)
-  if (a.phase == 3) {
-    // attend-only over long runs of consecutive positions: 8 queries share a key stream.  Used at head dimension 64
-    // (c2's prefill 66 -> 58 ms); at 128 the kernel is bound by its dot products, not by the key stream, and the
-    // 8-query variant measured slower (c3's prefill 290 -> 317 ms), as it would with 8 query heads per KV head.
-    if constexpr (DH == 64) {
-      if (G == 1) { hipLaunchKernelGGL((k_attn_block_bf16<DH, 1, 8>), dim3(a.KVH, (max_rows + 7) / 8), dim3(256), 0, s, a); return; }
-      if (G == 2) { hipLaunchKernelGGL((k_attn_block_bf16<DH, 2, 4>), dim3(a.KVH, (max_rows + 3) / 4), dim3(256), 0, s, a); return; }
-      if (G == 4) { hipLaunchKernelGGL((k_attn_block_bf16<DH, 4, 2>), dim3(a.KVH, (max_rows + 1) / 2), dim3(256), 0, s, a); return; }
-    }
-    AttnArgs b = a;
-    b.phase = 2;
-    launch_attn_bf16<DH>(b, G, max_rows, ctx_bound, s);
+  if (a.phase == 3) {          // attend-only over runs of consecutive positions of one row: the matrix-core kernel
+    hipLaunchKernelGGL((k_attn_mfma_bf16<DH>), dim3(a.H, (max_rows + 15) / 16), dim3(64), 0, s, a);
     return;
   }
   dim3 grid(a.KVH, max_rows);
