@@ -375,6 +375,49 @@ __global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
   }
 }
 
+// Append-only launch of a multi-entry pass: rotate the new key, round key and value to bf16 and write them to the
+// entry's cache slot - what k_attn_bf16 does in its prologue, without the attention around it.  One 64-lane
+// workgroup per (entry, KV head): the first DH / 8 lanes take the key, the next DH / 8 the value, 8 elements each.
+template <int DH>
+__global__ __launch_bounds__(64) void k_kv_append_bf16(AttnArgs a) {
+  constexpr int LPK = DH / 8;
+  const int r = blockIdx.y, lane = threadIdx.x;
+  if (r >= *a.rd.n_rows || lane >= 2 * LPK) return;
+  const int kvh = blockIdx.x, b = a.rd.b[r], slot = a.rd.slot[r], S = a.max_seq;
+  const bool is_v = lane >= LPK;
+  const int chunk = lane % LPK, pchunk = chunk ^ (LPK / 2);
+  const bool upper = chunk >= LPK / 2;
+  const float* __restrict__ y = a.y + (size_t)r * a.dqkv + (size_t)(a.H + (is_v ? a.KVH : 0) + kvh) * DH;
+  const float* __restrict__ cs = a.rope + (size_t)r * DH + 2 * (chunk % (LPK / 2)) * 8;
+  float x[8], xp[8], c16[16];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float4 u = reinterpret_cast<const float4*>(y + chunk * 8)[i], w = reinterpret_cast<const float4*>(y + pchunk * 8)[i];
+    x[4 * i] = u.x; x[4 * i + 1] = u.y; x[4 * i + 2] = u.z; x[4 * i + 3] = u.w;
+    xp[4 * i] = w.x; xp[4 * i + 1] = w.y; xp[4 * i + 2] = w.z; xp[4 * i + 3] = w.w;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 u = reinterpret_cast<const float4*>(cs)[i];
+    c16[4 * i] = u.x; c16[4 * i + 1] = u.y; c16[4 * i + 2] = u.z; c16[4 * i + 3] = u.w;
+  }
+  const bool rot = a.use_rope && !is_v;
+  unsigned pk[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float v2[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int e = 2 * i + j;
+      const float c = rot ? c16[2 * e] : 1.f, sn = rot ? c16[2 * e + 1] : 0.f;
+      v2[j] = upper ? x[e] * c + xp[e] * sn : x[e] * c - xp[e] * sn;
+    }
+    pk[i] = (unsigned)f2bf(v2[0]) | ((unsigned)f2bf(v2[1]) << 16);
+  }
+  bf16_t* __restrict__ dst = (bf16_t*)(is_v ? a.vcache : a.kcache) + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
+  *reinterpret_cast<uint4*>(dst + (size_t)slot * DH + chunk * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+}
+
 // Causal attention on the matrix cores for a multi-entry pass whose entries come in runs of consecutive positions of
 // one batch row (prefill); every key and value of the pass is already cached (the append-only launch ran before).
 // One wave per (block of 16 entries, query head).  Per block of 32 keys: S = Q K^T (16 x 32 scores, Q as hi + lo bf16
@@ -529,6 +572,10 @@ static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, int ctx_bou
   // NW = waves per workgroup that share one (row, KV head)'s keys: 8 when the launch has no more workgroups than
   // the chip has compute units and the contexts are long (c5's target pass: 20 rows x 8 KV heads x 1000+ keys),
   // else 4 (at c2's 130-400 keys the 8-wave variant takes 9.5 us against 7.8)
+  if (a.phase == 1) {          // append only
+    hipLaunchKernelGGL((k_kv_append_bf16<DH>), dim3(a.KVH, max_rows), dim3(64), 0, s, a);
+    return;
+  }
   if (a.phase == 3) {          // attend-only over runs of consecutive positions of one row: the matrix-core kernel
     hipLaunchKernelGGL((k_attn_mfma_bf16<DH>), dim3(a.H, (max_rows + 15) / 16), dim3(64), 0, s, a);
     return;

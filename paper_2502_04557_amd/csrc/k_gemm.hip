@@ -400,6 +400,9 @@ static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s
   if ((size_t)row_groups * 128 * a.Kt * 32 > a.x_plane) return false;
   constexpr bool DUAL = EPI == EPI_SWIGLU;
   const int g2 = (a.n_tiles + 15) / 16, g1 = (a.n_tiles + 7) / 8;
+  // too few workgroups for the chip (a 128-row decode batch on a narrow model: 18 column groups): the K-split
+  // kernels, which put every column tile in a workgroup of its own, do better there
+  if (g1 * row_groups * sk < 128) return false;
   if constexpr (!DUAL) {
     if (g2 * row_groups * sk >= 160) {
       hipLaunchKernelGGL((k_gemm_wide<2, EPI>), dim3(g2, row_groups, sk), dim3(512), 0, s, a);
