@@ -33,6 +33,24 @@ def kv_bytes_per_token(m, es):
     return 2 * m.n_layer * m.n_kv_head * m.d_head * es
 
 
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def prefill_flops(cfg, plen):
+    """Floating-point operations prefill must do: positions 0 .. P_b-2 of every row through both models (the last
+    layer stops after its attention: only the caches are needed), matrices + causal attention."""
+    import numpy as np
+    total = 0.0
+    n_tok = float((plen - 1).sum())
+    pairs = float(sum(int(p - 1) * int(p) // 2 for p in plen))          # sum over cached positions of (pos + 1)
+    for m in (cfg.draft, cfg.target):
+        d, ff = m.d_model, m.d_ff
+        per_layer = m.d_qkv * d + d * m.n_head * m.d_head + (2 if m.arch == 0 else 3) * d * ff
+        total += 2.0 * n_tok * ((m.n_layer - 1) * per_layer + m.d_qkv * d)
+        total += 4.0 * m.n_head * m.d_head * pairs * m.n_layer
+    return total
+
+
 def algorithmic_bytes(cfg, plen, accept, first_step, seen_before=None):
     """Bytes the method must move per step, from the actual accept flags:
     draft weights + draft KV (read len+1, write 1) + verifier + [R>0](target weights + target KV of the R rows)."""
@@ -295,7 +313,8 @@ def main():
     t0 = time.perf_counter()
     s.prefill(prompts, plen)
     torch.cuda.synchronize()
-    print(f"[bench] prefill of {int(plen.sum())} prompt tokens: {(time.perf_counter() - t0) * 1e3:.1f} ms", file=sys.stderr, flush=True)
+    prefill_ms = (time.perf_counter() - t0) * 1e3
+    print(f"[bench] prefill of {int(plen.sum())} prompt tokens: {prefill_ms:.1f} ms", file=sys.stderr, flush=True)
     seen_before = plen.astype(np.int64) - 1
     if Wm:
         wa = s.generate(Wm, want=("tok", "accept"))["accept"].cpu().numpy()
@@ -343,6 +362,11 @@ def main():
                      "kernel": "one decode step (all kernels of sprinter_step)",
                      "bytes_per_launch": float(per_step_bytes.mean()), "ms_per_launch": step_ms},
     }
+    # the prompt pass that precedes the timed steps (not part of `value`): useful operations against the matrix-core peak
+    pf = prefill_flops(cfg, plen) / (prefill_ms * 1e-3) / 1e12
+    out["prefill"] = {"tokens": int(plen.sum()), "ms": prefill_ms,
+                      "roofline": {"bound": "mfma", "achieved": pf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": pf / MFMA_PEAK_TFLOPS}}
     s.close()
     del s
     torch.cuda.empty_cache()
