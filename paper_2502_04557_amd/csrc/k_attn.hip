@@ -429,6 +429,7 @@ template <int DH>
 __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
   constexpr int T = DH / 32, CT = DH / 16, VS = DH + 8, PS = 36;
   constexpr float NEG = -1e30f;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   __shared__ __attribute__((aligned(16))) bf16_t lds_v[32 * VS];
   __shared__ __attribute__((aligned(16))) float lds_p[16 * PS];
   const int n_rows = *a.rd.n_rows, r0 = blockIdx.y * 16;
@@ -486,24 +487,40 @@ __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) O[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m_run[4] = {NEG, NEG, NEG, NEG}, l_run[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int kb = 0; kb <= max_slot; kb += 32) {
+    // Two register buffers: the keys (operand fragments) and values (staging pieces) of block kb + 32 are requested
+    // before block kb is worked on.  Addresses are clamped to the run's last key, so a block beyond it loads valid
+    // memory, has every key masked and every value zeroed, and changes nothing.
+    struct Blk { u32x4 k[2][T]; u32x4 v[DH / 16]; };
+    auto fetch = [&](Blk& B, int kb) {
+#pragma unroll
+      for (int tile = 0; tile < 2; ++tile) {
+        const bf16_t* kr = Kc + (size_t)min(kb + tile * 16 + l16, max_slot) * DH + lq * 8;
+#pragma unroll
+        for (int t = 0; t < T; ++t) B.k[tile][t] = *reinterpret_cast<const u32x4*>(kr + t * 32);
+      }
+#pragma unroll
+      for (int i = 0; i < DH / 16; ++i) {
+        const int u = lane + 64 * i, key = u / (DH / 8), piece = u % (DH / 8);
+        B.v[i] = *reinterpret_cast<const u32x4*>(Vc + (size_t)min(kb + key, max_slot) * DH + piece * 8);
+      }
+    };
+    auto step = [&](const Blk& B, int kb) {
       // stage V[kb .. kb+31][0 .. DH) in LDS (rows beyond the run's last key as zeros: they may hold anything)
 #pragma unroll
       for (int i = 0; i < DH / 16; ++i) {
         const int u = lane + 64 * i, key = u / (DH / 8), piece = u % (DH / 8);
-        uint4 val = *reinterpret_cast<const uint4*>(Vc + (size_t)min(kb + key, max_slot) * DH + piece * 8);
-        if (kb + key > max_slot) val = make_uint4(0u, 0u, 0u, 0u);
-        *reinterpret_cast<uint4*>(lds_v + key * VS + piece * 8) = val;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(lds_v + key * VS + piece * 8) = (kb + key > max_slot) ? z : B.v[i];
       }
       // scores of the two 16-key tiles
       f32x4 sc[2];
 #pragma unroll
       for (int tile = 0; tile < 2; ++tile) {
         sc[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        const bf16_t* kr = Kc + (size_t)min(kb + tile * 16 + l16, max_slot) * DH + lq * 8;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-          const uint4 kf = *reinterpret_cast<const uint4*>(kr + t * 32);
+          const u32x4 kk = B.k[tile][t];
+          const uint4 kf = make_uint4(kk.x, kk.y, kk.z, kk.w);
           sc[tile] = mfma_bf16(qh[t], kf, sc[tile]);
           sc[tile] = mfma_bf16(ql[t], kf, sc[tile]);
         }
@@ -549,6 +566,16 @@ __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
         O[ct] = mfma_bf16(pl, vf, O[ct]);
       }
       __syncthreads();                                           // LDS is rewritten by the next key block
+    };
+    Blk A, B;
+    fetch(A, 0);
+    for (int kb = 0; kb <= max_slot; kb += 64) {
+      fetch(B, kb + 32);
+      __builtin_amdgcn_sched_barrier(0);
+      step(A, kb);
+      fetch(A, kb + 64);
+      __builtin_amdgcn_sched_barrier(0);
+      step(B, kb + 32);
     }
     bf16_t* __restrict__ ao = (bf16_t*)a.ao;
 #pragma unroll
