@@ -280,14 +280,15 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
 // column tiles each; SwiGLU: one gate + one up tile) and share the activations of 8 row tiles (128 rows) through LDS,
 // so a k tile costs the workgroup 16 KiB of activations (both planes, once) + 8 * NWT KiB of weights for
 // 8 * NWT * 16 MFMAs - a third of the bytes per MFMA of the K-split kernel above, which reads every operand per wave.
-// Two k tiles per stage, two LDS stages: the global loads of stage c + 1 (4 activation fragments per thread into
+// Two k tiles per stage (one with four weight tiles per wave), two LDS stages: the global loads of stage c + 1 (4 activation fragments per thread into
 // registers, the wave's own weight tiles) are in flight while the MFMAs of stage c run; one barrier per stage.
 // blockIdx.y = group of 128 rows, blockIdx.z = K share (EPI_PART).  The activation buffer must hold every row
 // tile the grid covers (the launcher checks it against the plane size).
 template <int NTW, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
   constexpr bool DUAL = (EPI == EPI_SWIGLU);
-  constexpr int NWT = NTW * (DUAL ? 2 : 1), MT = 8, KU = 2;
+  constexpr int NWT = NTW * (DUAL ? 2 : 1), MT = 8;
+  constexpr int KU = NWT >= 4 ? 1 : 2;                 // k tiles per stage (four weight tiles per wave leave registers for one)
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   __shared__ u32x4 xs[2][KU * 2][MT][64];               // [stage][k tile, plane][row tile][lane]: 64 KiB
   const int lane = threadIdx.x & 63, w = wave_index();
@@ -302,17 +303,13 @@ __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
   size_t wrow[NTW];
 #pragma unroll
   for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt0 + j, a.n_tiles - 1) * Kt * 64;
-  static_assert(KU == 2, "the staging registers are named one by one");
-  struct Regs { u32x4 x0, x1, x2, x3; uint4 w[KU][NWT]; };
+  struct Regs { u32x4 x[KU * 2]; uint4 w[KU][NWT]; };
   auto gload = [&](Regs& r, int kt) {
-    const int ka = min(kt, k1 - 1), kb = min(kt + 1, k1 - 1);   // clamped: always a tile of this share
-    r.x0 = Xh[(size_t)ka * 64];
-    r.x1 = Xl[(size_t)ka * 64];
-    r.x2 = Xh[(size_t)kb * 64];
-    r.x3 = Xl[(size_t)kb * 64];
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
-      const int kc = u ? kb : ka;
+      const int kc = min(kt + u, k1 - 1);                // clamped: always a tile of this share
+      r.x[u * 2] = Xh[(size_t)kc * 64];
+      r.x[u * 2 + 1] = Xl[(size_t)kc * 64];
 #pragma unroll
       for (int j = 0; j < NTW; ++j) {
         r.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
@@ -321,10 +318,8 @@ __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
     }
   };
   auto sstore = [&](int stage, const Regs& r) {
-    xs[stage][0][w][lane] = r.x0;
-    xs[stage][1][w][lane] = r.x1;
-    xs[stage][2][w][lane] = r.x2;
-    xs[stage][3][w][lane] = r.x3;
+#pragma unroll
+    for (int i = 0; i < KU * 2; ++i) xs[stage][i][w][lane] = r.x[i];
   };
   f32x4 acc[NWT][MT];
 #pragma unroll
@@ -403,7 +398,19 @@ static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s
   // too few workgroups for the chip (a 128-row decode batch on a narrow model: 18 column groups): the K-split
   // kernels, which put every column tile in a workgroup of its own, do better there
   if (g1 * row_groups * sk < 128) return false;
-  if constexpr (!DUAL) {
+  // four weight tiles per wave (SwiGLU: two gate + two up) halve the LDS reads per MFMA, which at two tiles take as
+  // long as the MFMAs themselves; two or one tile per wave where that would leave too few workgroups
+  const int g4 = (a.n_tiles + 31) / 32;
+  if constexpr (DUAL) {
+    if (g2 * row_groups * sk >= 160) {
+      hipLaunchKernelGGL((k_gemm_wide<2, EPI>), dim3(g2, row_groups, sk), dim3(512), 0, s, a);
+      return true;
+    }
+  } else {
+    if (g4 * row_groups * sk >= 160) {
+      hipLaunchKernelGGL((k_gemm_wide<4, EPI>), dim3(g4, row_groups, sk), dim3(512), 0, s, a);
+      return true;
+    }
     if (g2 * row_groups * sk >= 160) {
       hipLaunchKernelGGL((k_gemm_wide<2, EPI>), dim3(g2, row_groups, sk), dim3(512), 0, s, a);
       return true;
