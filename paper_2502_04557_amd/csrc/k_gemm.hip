@@ -616,10 +616,15 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
   // four column tiles (two if that leaves too few workgroups) and K is split until about 256 workgroups exist,
   // with at least two k tiles per wave and share
   if (max_rows >= 128) {           // 128+ rows: column-split workgroups, K shares until about 256 of them exist
-    const int row_groups = (max_rows + 127) / 128, col_groups = (a.n_tiles + 15) / 16;
-    int sk = std::max(1, std::min(std::min(max_shares, a.Kt / 16), (256 + col_groups * row_groups - 1) / (col_groups * row_groups)));
-    a.SK = sk;
-    if (try_gemm_wide<EPI_PART>(a, max_rows, sk, s)) return sk;
+    const int row_groups = (max_rows + 127) / 128, s_lim = std::max(1, std::min(max_shares, a.Kt / 16));
+    // first with four column tiles per wave (the shares make up for the fewer column groups), then with two
+    for (int per_group : {32, 16}) {
+      const int groups = (a.n_tiles + per_group - 1) / per_group * row_groups;
+      const int sk = std::max(1, std::min(s_lim, (256 + groups - 1) / groups));
+      if (per_group == 32 && groups * sk < 160) continue;
+      a.SK = sk;
+      if (try_gemm_wide<EPI_PART>(a, max_rows, sk, s)) return sk;
+    }
   }
   const int row_tiles = (max_rows + 15) / 16, passes = (row_tiles + 3) / 4;
   const int mt = std::max(2, (row_tiles + passes - 1) / passes);
