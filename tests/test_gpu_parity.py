@@ -325,6 +325,41 @@ def test_random_shapes(seed):
     p.close()
 
 
+@pytest.mark.parametrize("chunk_rows", [0, 256])
+def test_prefill_matrix_core_kernels_mid_size(chunk_rows):
+    """A prompt set large enough (9 ragged prompts, about 600 tokens) and models wide enough that prefill takes the
+    column-split GEMM for 128+ rows (FFN-up with 225 column tiles and a half-filled last k tile, the partial-output
+    GEMMs with K shares; the narrow QKV falls back to the K-split kernel) and the causal matrix-core attention at
+    head dimension 64 (draft, 2 query heads per KV head) and 128 (target, 4 per KV head), with row counts that are not
+    multiples of the 128-row groups or the 16-entry attention blocks; once in a single pass and once in passes of 256
+    entries (runs split over pass borders).  The caches feed every later step: 6 steps replayed by the oracle."""
+    from parity_util import compare_replay, close_enough, eps_of
+    draft = W.ModelCfg(W.ARCH_LLAMA, 2, 512, 8, 4, 1408, 2003, 128, 1e-5, 10000.0)
+    target = W.ModelCfg(W.ARCH_LLAMA, 3, 1024, 8, 2, 3600, 2003, 128, 1e-5, 10000.0)
+    cfg = W.SprinterCfg(draft, target, 40, W.DT_BF16, 9, 128, seed=77, name="mid", batch=9, prompt_len=90, prompt_len_min=40,
+                        n_gen=6, prompt_dist="zipf", weight_seed=501, prompt_seed=502, chunk_rows=chunk_rows)
+    p = _pair(cfg, ver_scale=8.0)
+    assert int(p.plen.sum()) - cfg.batch > 2 * 256
+    outs, st = p.gpu_steps(cfg.n_gen, debug=True)
+    g = {k: np.stack([o[k2] for o in outs], axis=1) for k, k2 in
+         (("tok", "committed_tok"), ("accept", "accept"), ("score", "score"), ("draft_tok", "draft_tok"))}
+    rec = p.oracle(cfg.n_gen, forced=dict(tok=g["tok"], accept=g["accept"]), keep_logits=True, whole_prompt_prefill=True)
+    rep = compare_replay(cfg, g, rec)
+    eps = eps_of(cfg)
+    worst = 0.0
+    for t, o in enumerate(outs):                       # the first step's logits depend on nothing but the prefilled caches
+        ok = close_enough(o["draft_logits"], rec["draft_logits"][t], eps)
+        assert ok.all(), (t, np.abs(o["draft_logits"] - rec["draft_logits"][t]).max())
+        worst = max(worst, float(np.abs(o["draft_logits"] - rec["draft_logits"][t]).max()))
+        rej = rec["rejected"][t]
+        if rej:
+            assert close_enough(o["target_logits"][:len(rej)], rec["target_logits"][t], eps).all(), t
+            worst = max(worst, float(np.abs(o["target_logits"][:len(rej)] - rec["target_logits"][t]).max()))
+    print("mid-size prefill", chunk_rows, rep, "max logit difference", worst, flush=True)
+    assert 0 < rep["reject_rate"] < 1
+    p.close()
+
+
 @pytest.mark.parametrize("ctx", [0, 1])
 def test_long_context_few_rows(ctx):
     """Contexts of 770-900 keys with 3 rows: the attention launch takes its 8-wave variant (few workgroups, long
