@@ -60,3 +60,21 @@ def test_algorithmic_bytes_match_a_brute_force_count():
         per_step, R = bench.algorithmic_bytes(cfg, plen, accept, first, seen.copy())
         assert np.array_equal(R, (accept == 0).sum(0))
         assert np.allclose(per_step, _brute(cfg, plen, accept, first, seen.copy()), rtol=1e-12)
+
+
+def test_prefill_operation_count_matches_a_brute_force_count():
+    """bench.py's useful-operation figure for prefill: every cached position (0 .. P_b-2) through all matrices of both
+    models except what follows the last layer's attention, plus 4 d_h operations per (query head, query, key) pair."""
+    cfg = W.mini_config("llama", W.DT_BF16)
+    _, plen = W.make_prompts(cfg)
+    total = 0
+    for m in (cfg.draft, cfg.target):
+        for b in range(cfg.batch):
+            for pos in range(int(plen[b]) - 1):
+                for layer in range(m.n_layer):
+                    total += 2 * m.d_qkv * m.d_model                              # QKV projection
+                    total += m.n_head * (pos + 1) * 4 * m.d_head                  # scores + weighted values over pos + 1 keys
+                    if layer + 1 < m.n_layer:
+                        total += 2 * m.d_model * m.n_head * m.d_head              # output projection
+                        total += 2 * 3 * m.d_model * m.d_ff                       # gate, up, down
+    assert abs(bench.prefill_flops(cfg, plen) - total) <= 1e-9 * total
