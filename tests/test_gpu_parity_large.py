@@ -189,6 +189,38 @@ def test_c3_full_size_sampled_rows(llama7b, ctx, rej):
     s.close()
 
 
+def test_c3_speculative_decoding_sampled_rows(llama7b):
+    """Standard speculative decoding (Sec. 2, Eq. (1)) at config 3's size, gamma = 4: the target pass of a round carries
+    32 x 5 = 160 entries (the column-split GEMMs, the LM head over 160 rows, the p/q check at vocabulary 32000), the first
+    draft pass of a round up to 64.  The oracle replays three rows on the GPU's history; the bookkeeping is checked for all."""
+    from oracle import sprinter as osp, sd_baseline as osd
+    from parity_util import compare_sd_rounds, sd_rounds_to_lists
+    weights, models = llama7b
+    gamma, rounds = 4, 4
+    cfg = replace(W.config("c3"), max_seq=320, sd_gamma=gamma)
+    s = Side(cfg, weights, models)
+    t = time.time()
+    s.gpu.prefill(s.prompts, s.plen)
+    g = {k: v.cpu().numpy() for k, v in s.gpu.sd_generate(gamma, rounds).items()}
+    st = s.gpu.stats()
+    progress(f"c3 SD: GPU prefill + {rounds} rounds in {time.time() - t:.0f} s, kept per round {g['n_acc'].mean():.2f}")
+    lists, n_acc, draft = sd_rounds_to_lists(g)
+    assert st["steps"] == rounds and st["coin_kept"] == int(n_acc.sum())
+    assert all(0 <= x < cfg.draft.vocab for row in lists for x in row)
+    rows = [0, 13, cfg.batch - 1]
+    pr, pl = s.prompts[rows], s.plen[rows]
+    t = time.time()
+    dc = osp.prefill_whole_prompt(s.draft, pr, pl)
+    tc = osp.prefill_whole_prompt(s.target, pr, pl)
+    progress(f"c3 SD: oracle prefill of rows {rows} in {time.time() - t:.0f} s")
+    rec = osd.sd_generate(s.draft, s.target, pr, pl, rounds, gamma, cfg.temperature, cfg.seed, rows=rows,
+                          forced=dict(draft=draft[rows], n_acc=n_acc[rows], tok=[lists[b] for b in rows]),
+                          draft_caches=dc, target_caches=tc)
+    rep = compare_sd_rounds(cfg, g, rec, rows=rows)
+    progress(f"c3 SD: rows {rows} {rep} at {time.time() - t:.0f} s")
+    s.close()
+
+
 def test_c4_compaction_and_ragged_target(llama7b):
     """Config 4: batch 128, per-row prompt lengths in [64, 1024]; the verifier's output bias is
     shifted so that the reject rate runs near 5 %, 25 % and 60 % at thresholds 0.3, 0.5, 0.7.
