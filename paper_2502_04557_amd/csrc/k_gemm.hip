@@ -552,12 +552,23 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
     // column tiles per wave that share the activation fragments: as many as leave about 192 workgroups
     // as few passes over the weights as 4 row tiles per pass allow, the row tiles spread evenly over them
     // (80 rows: 2 passes of 3 tiles, not 4 + 1)
-    const int row_tiles = (max_rows + 15) / 16, passes = (row_tiles + 3) / 4;
-    const int mt = std::max(2, (row_tiles + passes - 1) / passes);
+    const int row_tiles = (max_rows + 15) / 16;
     constexpr bool DUAL = EPI == EPI_SWIGLU;
+#define SPRINTER_ROWS(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI>), grid, dim3(512), 0, s, a)
+    if (row_tiles >= 5 && row_tiles <= 7 && (long long)a.n_tiles * a.Kt <= 24576) {
+      // 65 .. 112 rows of a matrix under 24 MiB in ONE pass over the weights (5-7 row tiles per workgroup; the
+      // registers allow two column tiles per wave, one for SwiGLU's two matrices) instead of two passes of 3-4 tiles:
+      // the fixed cost per pass weighs more than the activation traffic there (an SD round of 80 entries at c2
+      // 7.4 -> 6.5 ms; at c4's 4096-wide matrices the single pass is slower, 13.3 -> 14.4 ms per step)
+      constexpr int ntw = DUAL ? 1 : 2;
+      const dim3 grid((a.n_tiles + ntw - 1) / ntw, 1, 1);
+      if (row_tiles == 5) SPRINTER_ROWS(5, ntw); else if (row_tiles == 6) SPRINTER_ROWS(6, ntw); else SPRINTER_ROWS(7, ntw);
+      return;
+    }
+    const int passes = (row_tiles + 3) / 4;
+    const int mt = std::max(2, (row_tiles + passes - 1) / passes);
     const int ntw = (!DUAL && mt > 2 && a.n_tiles / 4 >= 192) ? 4 : (a.n_tiles / 2 >= (DUAL ? 256 : 128)) ? 2 : 1;
     const dim3 grid((a.n_tiles + ntw - 1) / ntw, passes, 1);
-#define SPRINTER_ROWS(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI>), grid, dim3(512), 0, s, a)
     if (ntw == 4) { if (mt == 3) SPRINTER_ROWS(3, 4); else SPRINTER_ROWS(4, 4); }
     else if (ntw == 2) { if (mt == 2) SPRINTER_ROWS(2, 2); else if (mt == 3) SPRINTER_ROWS(3, 2); else SPRINTER_ROWS(4, 2); }
     else { if (mt == 2) SPRINTER_ROWS(2, 1); else if (mt == 3) SPRINTER_ROWS(3, 1); else SPRINTER_ROWS(4, 1); }
@@ -626,14 +637,22 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
       if (try_gemm_wide<EPI_PART>(a, max_rows, sk, s)) return sk;
     }
   }
-  const int row_tiles = (max_rows + 15) / 16, passes = (row_tiles + 3) / 4;
-  const int mt = std::max(2, (row_tiles + passes - 1) / passes);
+  const int row_tiles = (max_rows + 15) / 16;
   const int s_max = std::max(1, std::min(max_shares, a.Kt / 16));
+#define SPRINTER_PART(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI_PART>), grid, dim3(512), 0, s, a)
+  if (row_tiles >= 5 && row_tiles <= 7 && (long long)a.n_tiles * a.Kt <= 24576) {   // small matrix: one pass of 5-7 row tiles
+    const int groups = (a.n_tiles + 1) / 2, sk = std::min(s_max, std::max(1, 256 / groups));
+    a.SK = sk;
+    const dim3 grid(groups, 1, sk);
+    if (row_tiles == 5) SPRINTER_PART(5, 2); else if (row_tiles == 6) SPRINTER_PART(6, 2); else SPRINTER_PART(7, 2);
+    return sk;
+  }
+  const int passes = (row_tiles + 3) / 4;
+  const int mt = std::max(2, (row_tiles + passes - 1) / passes);
   int ntw = 4, groups = (a.n_tiles + 3) / 4, sk = std::min(s_max, std::max(1, 256 / groups));
   if (groups * sk < 192) { ntw = 2; groups = (a.n_tiles + 1) / 2; sk = std::min(s_max, std::max(1, 256 / groups)); }
   a.SK = sk;
   const dim3 grid(groups, passes, sk);
-#define SPRINTER_PART(MT_, NTW_) hipLaunchKernelGGL((k_gemm_rows<MT_, NTW_, EPI_PART>), grid, dim3(512), 0, s, a)
   if (ntw == 4) { if (mt == 2) SPRINTER_PART(2, 4); else if (mt == 3) SPRINTER_PART(3, 4); else SPRINTER_PART(4, 4); }
   else { if (mt == 2) SPRINTER_PART(2, 2); else if (mt == 3) SPRINTER_PART(3, 2); else SPRINTER_PART(4, 2); }
 #undef SPRINTER_PART
