@@ -6,7 +6,10 @@
 A "step" is one pass of the whole hot path over the batch: draft forward, sample,
 verifier, compaction, target forward on the rejected rows, scatter-back.  The
 workload is configuration 2 of the five (GPT-2-small/XL-shaped pair, bf16, batch 16, 128-token
-Zipf prompts, threshold 0.5) with synthetic random-init weights.  Prints one JSON line.
+Zipf prompts, threshold 0.5) with synthetic random-init weights.  Prints one JSON line; besides the contract's
+fields it carries `roofline` (the decode step against the HBM peak), `prefill` (time of the prompt pass that
+precedes the timed steps and its matrix-core roofline; not part of `value`) and `cpu_baseline` (the oracle).
+`--method sd --gamma G` times standard speculative decoding on the same models instead (one round per step).
 """
 from __future__ import annotations
 import argparse
