@@ -100,7 +100,7 @@ typedef struct {
  *   0 <= sd_gamma <= 16.
  *   chunk_rows: rows of the activation buffers = entries one pass over the
  *   weights takes in a multi-entry forward (prefill, full-prefix work lists,
- *   speculative-decoding windows).  0 = default (bf16: 2048; float32: 16); else a
+ *   speculative-decoding windows).  0 = default (bf16: 4096; float32: 16); else a
  *   multiple of 64 in [64, 4096].  Never below max_batch rounded up. */
 typedef struct {
   sprinter_model_cfg draft, target;

@@ -135,7 +135,7 @@ size_t act_elems(int dtype, int rows, int K) { return act_plane(dtype, rows, K) 
 size_t packed_elems(int N, int K) { return (size_t)round_up(N, 16) * round_up(K, 32); }
 
 constexpr int MEGA_MAX_WG = 512;
-constexpr int DEFAULT_CHUNK_ROWS = 2048;
+constexpr int DEFAULT_CHUNK_ROWS = 4096;
 
 const char* check_model(const sprinter_model_cfg& m, const char* who, char* buf, size_t n) {
 #define BAD(...) do { snprintf(buf, n, __VA_ARGS__); return buf; } while (0)
