@@ -88,12 +88,7 @@ def sd_generate(draft, target, prompts, prompt_len, n_rounds, gamma, temperature
                 if ends_here:
                     n_acc, last = j, sd["resid_tok"]
                     rec["last_margin"][b, r] = sd["margin"]
-                    band = 0.0
-                    for v in (sd["resid_tok"], sd["runner_up"]):
-                        if v >= 0:
-                            pv, qv = np.exp(sd["logp"][v]), np.exp(sd["logq"][v])
-                            band += (pv + qv) / max(pv - qv, 1e-300)
-                    rec["last_band"][b, r] = band
+                    rec["last_band"][b, r] = sd["band"]
                     break
             if last is None:
                 last, y32 = philox.sample(lps[G], temperature, seed, philox.STREAM_TARGET, rows[b], L + G)

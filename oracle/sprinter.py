@@ -57,7 +57,7 @@ def sd_correction(lq, lp, x, temperature, seed, b, t, always_draw=False):
     else resample from Eq. (1): norm(max(0, p - q)); Alg. 2 draws the coin c ~ U(0, 1)).
     The coin comparison and the arg-max of the residual draw are taken on float32 values.
     Returns a dict: tok (the committed token), kept, coin, log_ratio = ln p(x) - ln q(x) (unclipped),
-    and for a residual draw its top-2 margin plus the two candidates (for tolerance bands).
+    and for a residual draw its top-2 margin, the runner-up and band = residual_band of the two (for tolerance bands).
     always_draw: also report the residual draw (as resid_tok) when the coin keeps x (replay of a history
     whose coin went the other way)."""
     if not temperature > 0.0:
@@ -66,7 +66,7 @@ def sd_correction(lq, lp, x, temperature, seed, b, t, always_draw=False):
     log_ratio = float(logp[x] - logq[x])
     c = philox.coin(seed, b, t)
     out = dict(coin=c, log_ratio=log_ratio, kept=bool(np.float32(c) <= np.float32(min(1.0, np.exp(log_ratio)))),
-               tok=int(x), margin=np.inf, runner_up=-1, logq=logq, logp=logp)
+               tok=int(x), margin=np.inf, runner_up=-1, band=0.0, logq=logq, logp=logp)
     if not out["kept"] or always_draw:
         r = np.maximum(0.0, np.exp(logp) - np.exp(logq))
         with np.errstate(divide="ignore"):
@@ -79,10 +79,25 @@ def sd_correction(lq, lp, x, temperature, seed, b, t, always_draw=False):
             order = np.argsort(z32.astype(np.float64), kind="stable")
             out["runner_up"] = int(order[-2]) if order[-1] == out["resid_tok"] else int(order[-1])
             out["margin"] = float(z32[out["resid_tok"]]) - float(z32[out["runner_up"]])
+        out["band"] = residual_band(logp, logq, (out["resid_tok"], out["runner_up"]))
     return out
 
 
+def residual_band(logp, logq, candidates) -> float:
+    """Tolerance scale of a residual draw (test tolerance, not part of the method): the draw compares
+    z_v = ln(p_v - q_v) + noise, and d z_v / d ln p_v = p_v / (p_v - q_v), d z_v / d ln q_v = -q_v / (p_v - q_v),
+    so an error of delta in each log-probability moves z_v by at most delta * (p_v + q_v) / (p_v - q_v).
+    Returns the sum of that factor over the given candidates (winner and runner-up; negative indices are skipped)."""
+    band = 0.0
+    for v in candidates:
+        if v >= 0:
+            pv, qv = np.exp(logp[v]), np.exp(logq[v])
+            band += (pv + qv) / max(pv - qv, 1e-300)
+    return float(band)
+
+
 def top2_margin(y32: np.ndarray) -> float:
+    """Largest minus second largest entry (0 for a tie at the top, inf for a single entry)."""
     if y32.shape[0] < 2:
         return float("inf")
     part = np.partition(y32.astype(np.float64), -2)
@@ -189,11 +204,7 @@ def generate(draft, target, verifier, prompts, prompt_len, n_gen, tau, temperatu
                     rec["kept"][b, g], rec["coin"][b, g], rec["log_ratio"][b, g] = sd["kept"], sd["coin"], sd["log_ratio"]
                     if not sd["kept"]:
                         rec["residual_margin"][b, g] = sd["margin"]
-                        # sensitivity of ln(p_v - q_v) to an error of the two log-probabilities, winner + runner-up
-                        for v in (sd["tok"], sd["runner_up"]):
-                            if v >= 0:
-                                pv, qv = np.exp(sd["logp"][v]), np.exp(sd["logq"][v])
-                                rec["residual_band"][b, g] += (pv + qv) / max(pv - qv, 1e-300)
+                        rec["residual_band"][b, g] = sd["band"]
                 else:
                     yb, y32 = philox.sample(lp[i], temperature, seed, philox.STREAM_TARGET, rows[b], t[b])
                     rec["target_margin"][b, g] = top2_margin(y32)
