@@ -1,15 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the batched SPRINTER decode step on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cN] [--reject-rate RHO]
 
 A "step" is one pass of the whole hot path over the batch: draft forward, sample,
-verifier, compaction, target forward on the rejected rows, scatter-back.  The
-workload is configuration 2 of the five (GPT-2-small/XL-shaped pair, bf16, batch 16, 128-token
-Zipf prompts, threshold 0.5) with synthetic random-init weights.  Prints one JSON line; besides the contract's
-fields it carries `roofline` (the decode step against the HBM peak), `prefill` (time of the prompt pass that
-precedes the timed steps and its matrix-core roofline; not part of `value`) and `cpu_baseline` (the oracle).
-`--method sd --gamma G` times standard speculative decoding on the same models instead (one round per step).
+verifier, compaction, target forward on the rejected rows, scatter-back.  Without
+--config the headline workload is configuration 5, the largest of the five (LLaMA-3-shaped
+pair with grouped queries, bf16, batch 64, 1024-token Zipf prompts, vocabulary 128256,
+both KV caches resident), and configuration 2 (GPT-2-small/XL-shaped pair, batch 16: the
+small-batch weight-streaming point) is measured beside it and reported under the key "c2"
+with the same fields.  All weights are synthetic random-init.  Prints one JSON line; besides
+the contract's fields it carries
+  roofline      the decode step against the HBM peak, plus the matrix-core rate of the same step
+                against the bf16 peak and against the ceiling its arithmetic intensity allows;
+  prefill       time of the prompt pass that precedes the timed steps and its matrix-core roofline
+                (not part of `value`);
+  by_threshold  ms per step with the threshold forced to 0 (draft only) and 1.5 (target every step);
+  at_reject_rate  the same workload with the verifier's output bias calibrated to the reject rate
+                that Table 2's "Avg Tokens" implies (about 9 %);
+  cpu_baseline  the oracle on the host cores.
+`--reject-rate RHO` calibrates the main run itself; `--sweep` (configuration 4) runs the nine
+(threshold, reject rate) settings of that workload; `--method sd --gamma G` times standard
+speculative decoding on the same models instead (one round per step).
 """
 from __future__ import annotations
 import argparse
@@ -88,53 +100,94 @@ def algorithmic_bytes(cfg, plen, accept, first_step, seen_before=None):
     return per_step, R
 
 
+def algorithmic_flops(cfg, plen, accept, first_step, seen_before):
+    """Floating-point operations per step (own-history target context): 2 per weight element and row for the
+    draft over B rows and the target over the R rejected rows, plus 4 * d_head per cached key and query head."""
+    import numpy as np
+    B, K = accept.shape
+    rej = (accept == 0)
+    R = rej.sum(0)
+
+    def welems(m):
+        d, ff = m.d_model, m.d_ff
+        return m.n_layer * (m.d_qkv * d + d * m.n_head * m.d_head + (2 if m.arch == 0 else 3) * d * ff) + m.vocab * d
+
+    def attn(m, keys):
+        return 4.0 * m.n_head * m.d_head * m.n_layer * keys
+
+    len_q = (plen[:, None] - 1) + first_step + np.arange(K)[None, :]
+    len_p = np.asarray(seen_before, dtype=np.int64)[:, None] + (np.cumsum(rej, axis=1) - rej)
+    per_step = 2.0 * B * welems(cfg.draft) + attn(cfg.draft, (len_q + 1).sum(0))
+    per_step = per_step + 2.0 * R * welems(cfg.target) + attn(cfg.target, (rej * (len_p + 1)).sum(0))
+    return per_step
+
+
 def measured_traffic(cfg):
     """HBM bytes per decode step from hardware counters (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known
-    size), collected offline with the native runner on this very workload: profiles/decode_step_c2_hbm_traffic.txt
-    holds the commands and the per-kernel table.  Only the default c2 workload has been measured."""
-    if cfg.name != "c2" or cfg.target_ctx_mode != 0 or cfg.reject_mode != 0:
-        return None
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "decode_step_c2_hbm_traffic.txt")
+    size).  The counters are not collected in this run: they come from two `rocprofv3 --pmc` runs of the native
+    runner on the same workload, whose summary (commands, per-kernel table) is kept under profiles/.  Returns
+    (bytes per step or None, where the figure comes from)."""
+    if cfg.target_ctx_mode != 0 or cfg.reject_mode != 0:
+        return None, None
+    name = f"decode_step_{cfg.name}_hbm_traffic.txt"
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", name)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_step"):
-                return float(line.split()[1])
+                return float(line.split()[1]), f"profiles/{name} (hardware counters of an earlier run of this workload, not of this run)"
     except OSError:
         pass
-    return None
+    return None, None
 
 
-def cpu_baseline(cfg, weights, n_rows, max_seconds=15.0, max_steps=64):
-    """The oracle, as it stands, on a bounded sample of the same workload."""
+def host_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1]))
+    except Exception:
+        return int(os.cpu_count() or 1)
+
+
+def cpu_baseline(cfg, weights, max_seconds=15.0, max_steps=64):
+    """The oracle, as it stands, on a bounded sample of the same workload: the first rows of the batch with
+    their own prompts for the configurations whose models it can prefill in seconds (c1, c2), two rows with
+    the prompts cut to their last 64 tokens for the large ones (one uncached forward per row fills the caches,
+    untimed like the GPU's prefill; the decode steps are timed)."""
     import numpy as np
     import workloads as W
     from oracle import model as om, sprinter as osp
     dw, tw, vw = weights
-    d, t, v = om.Decoder(cfg.draft, dw), om.Decoder(cfg.target, tw), om.Verifier(vw)
+    params = sum(int(np.prod(a.shape)) for a in dw.values()) + sum(int(np.prod(a.shape)) for a in tw.values())
+    big = params > 3e9
+    store = np.float32 if big else np.float64      # the float64 copies of an 8B-parameter pair do not pay for themselves here
+    d, t, v = om.Decoder(cfg.draft, dw, store=store), om.Decoder(cfg.target, tw, store=store), om.Verifier(vw)
     prompts, plen = W.make_prompts(cfg)
-    prompts, plen = prompts[:n_rows, :2].copy(), np.full(n_rows, 2, np.int32)
-    dc, tc = osp.prefill(d, prompts, plen), osp.prefill(t, prompts, plen)
+    n_rows = min(len(plen), 2 if big else 4)
+    if big:
+        keep = 64
+        assert int(plen[:n_rows].min()) >= keep
+        prompts = np.stack([prompts[b, int(plen[b]) - keep:int(plen[b])] for b in range(n_rows)])
+        plen = np.full(n_rows, keep, np.int32)
+        what = f"first {n_rows} rows, prompts cut to their last {keep} tokens, weights held in float32"
+    else:
+        prompts, plen = prompts[:n_rows].copy(), plen[:n_rows].copy()
+        what = f"first {n_rows} rows with their own prompts ({int(plen.min())}-{int(plen.max())} tokens)"
+    dc, tc = osp.prefill_whole_prompt(d, prompts, plen), osp.prefill_whole_prompt(t, prompts, plen)
+    seqs = [list(map(int, prompts[b, :int(plen[b])])) for b in range(n_rows)]
     steps, t0 = 0, time.perf_counter()
-    rec = None
-    forced = None
-    # one generate call per step so that the run can stop on the time bound
-    seqs = [list(p) for p in prompts]
+    # one generate call per step so that the run can stop on the time bound; the caches carry over
     while steps < max_steps and time.perf_counter() - t0 < max_seconds:
-        pr = np.array(seqs, dtype=np.int32)
-        pl = np.full(n_rows, pr.shape[1], np.int32)
+        m = max(len(q) for q in seqs)
+        pr = np.array([q + [0] * (m - len(q)) for q in seqs], dtype=np.int32)
+        pl = np.array([len(q) for q in seqs], np.int32)
         rec = osp.generate(d, t, v, pr, pl, 1, cfg.tau, cfg.temperature, cfg.seed, draft_caches=dc, target_caches=tc)
         for b in range(n_rows):
             seqs[b].append(int(rec["tok"][b, 0]))
         steps += 1
     dt = time.perf_counter() - t0
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count()
-    return dict(value=n_rows * steps / dt, unit="tokens/s", cores=int(threads), kind="oracle",
-                sample=f"{cfg.name}: first {n_rows} rows, prompts cut to 2 tokens, {steps} decode steps "
-                       f"in {dt:.1f} s (NumPy float64, os.cpu_count()={os.cpu_count()})")
+    return dict(value=n_rows * steps / dt, unit="tokens/s", cores=host_threads(), kind="oracle",
+                sample=f"{cfg.name}: {what}, {steps} decode steps in {dt:.1f} s (NumPy float64 arithmetic, "
+                       f"os.cpu_count()={os.cpu_count()})")
 
 
 def cpu_baseline_sd(cfg, weights, n_rows, gamma, max_seconds=15.0, max_rounds=16):
@@ -243,17 +296,179 @@ def bench_sd(args, base):
     del s
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline_sd(cfg, weights, B, G)
+        out["cpu_baseline"] = cpu_baseline_sd(cfg, weights, min(B, 4), G)
     print(json.dumps(out))
+
+
+def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
+    """One configuration through prefill, warm-up and K timed decode steps; returns the result object."""
+    import numpy as np
+    import torch
+    import workloads as W
+    from paper_2502_04557_amd import binding
+
+    pmax = base.prompt_len
+    CAL = 32                                              # calibration steps of a reject-rate run
+    need = pmax + Wm + K + CAL
+    lim = min(m.max_pos for m in (base.draft, base.target))
+    if need > lim:
+        raise SystemExit(f"prompt {pmax} + calibration {CAL} + warmup {Wm} + steps {K} exceeds the models' context {lim}")
+    cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau,
+                  target_ctx_mode=W.CTX_FULL_PREFIX if args.target_ctx == "full" else W.CTX_OWN_HISTORY,
+                  reject_mode=W.REJECT_SD if args.reject_mode == "sd" else W.REJECT_REPLACE,
+                  chunk_rows=args.chunk_rows)
+    t0 = time.time()
+    weights = W.make_weights(cfg)
+    prompts, plen = W.make_prompts(cfg)
+    print(f"[bench] {cfg.name}: weights generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    s = binding.Sprinter(cfg, "cuda:0")
+    for which, w in zip((binding.DRAFT, binding.TARGET, binding.VERIFIER), weights):
+        s.load_weights(which, w)
+    B, dev = len(plen), s.device
+    b2_0 = float(weights[2]["v.b2"][0])
+
+    def set_bias(b2):
+        vw = dict(weights[2])
+        vw["v.b2"] = np.array([b2], np.float32)
+        s.load_weights(binding.VERIFIER, vw)
+
+    def timed(tau, rho, n_warm, n_steps):
+        """prefill, optional calibration to reject rate rho, n_warm untimed and n_steps timed steps."""
+        s.set_tau(tau)
+        set_bias(b2_0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        s.prefill(prompts, plen)
+        torch.cuda.synchronize()
+        prefill_ms = (time.perf_counter() - t0) * 1e3
+        first = 0
+        seen = plen.astype(np.int64) - 1
+        pre = []
+        if rho is not None:
+            o = s.generate(CAL, want=("accept", "score"))
+            set_bias(W.shifted_bias(o["score"].cpu().numpy(), b2_0, tau, rho))
+            pre.append(o["accept"].cpu().numpy())
+        if n_warm:
+            pre.append(s.generate(n_warm, want=("tok", "accept"))["accept"].cpu().numpy())
+        if pre:
+            wa = np.concatenate(pre, 1)
+            first = wa.shape[1]
+            for b in range(B):
+                r = np.flatnonzero(wa[b] == 0)
+                if cfg.target_ctx_mode == 0:                      # own history: one entry per target call
+                    seen[b] += len(r)
+                elif len(r):                                      # full prefix: the cache is complete after a rejection
+                    seen[b] = plen[b] - 1 + r[-1] + 1
+        tok = torch.zeros(B, n_steps, dtype=torch.int32, device=dev)
+        acc = torch.zeros(B, n_steps, dtype=torch.uint8, device=dev)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record(s.stream)
+        s.generate_into(n_steps, tok=tok, accept=acc)
+        ev1.record(s.stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return dict(wall=wall, ev_ms=ev0.elapsed_time(ev1), accept=acc.cpu().numpy(), first=first, seen=seen,
+                    prefill_ms=prefill_ms)
+
+    def summarise(r, n_steps, tau):
+        accept = r["accept"]
+        per_step_bytes, R = algorithmic_bytes(cfg, plen, accept, r["first"], r["seen"])
+        step_ms = r["ev_ms"] / n_steps
+        achieved = per_step_bytes.mean() / (step_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "kernel": "one decode step (all kernels of sprinter_step)",
+                "bytes_per_launch": float(per_step_bytes.mean()), "ms_per_launch": step_ms}
+        if cfg.target_ctx_mode == 0:
+            flops = algorithmic_flops(cfg, plen, accept, r["first"], r["seen"]).mean()
+            ai = flops / per_step_bytes.mean()                     # flop per byte; the ridge is peak / bandwidth = 312
+            tf = flops / (step_ms * 1e-3) / 1e12
+            ceiling = min(MFMA_PEAK_TFLOPS, ai * HBM_PEAK_GBS / 1e3)
+            roof["mfma"] = {"achieved": tf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tf / MFMA_PEAK_TFLOPS,
+                            "flop_per_byte": ai, "ceiling_at_this_intensity": ceiling, "frac_of_ceiling": tf / ceiling}
+        return {"value": B * n_steps / r["wall"], "ms_per_step": r["wall"] * 1e3 / n_steps,
+                "target_calls_per_token": float(R.sum() / (B * n_steps)),
+                "steps_with_target_frac": float((R > 0).mean()),
+                "avg_accepted_run": float(accept.sum() / max(1, (accept == 0).sum())),
+                "roofline": roof}
+
+    r = timed(cfg.tau, reject_rate, Wm, K)
+    print(f"[bench] {cfg.name}: prefill of {int(plen.sum())} prompt tokens: {r['prefill_ms']:.1f} ms", file=sys.stderr, flush=True)
+    res = summarise(r, K, cfg.tau)
+    label = (f"{cfg.name}: batch {B}, prompt {pmax if not cfg.prompt_len_min else f'{cfg.prompt_len_min}..{pmax}'}, "
+             f"tau {cfg.tau}, T {cfg.temperature}; "
+             f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
+             f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts"
+             + ("; full-prefix target context" if cfg.target_ctx_mode == 1 else "")
+             + ("; p/q coin + residual on rejection" if cfg.reject_mode == 1 else "")
+             + (f"; verifier bias calibrated to a reject rate of {reject_rate}" if reject_rate is not None else
+                "; verifier as generated"))
+    traffic, source = measured_traffic(cfg) if reject_rate is None and args.tau is None else (None, None)
+    res["roofline"]["traffic"] = traffic
+    if source:
+        res["roofline"]["traffic_source"] = source
+    out = {"metric": "generated tokens/sec at batch B (1 GPU)", "value": res["value"], "unit": "tokens/s",
+           "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": res["ms_per_step"],
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
+           "config": {"workload": label, "batch": B, "prompt_len": pmax},
+           "target_calls_per_token": res["target_calls_per_token"],
+           "steps_with_target_frac": res["steps_with_target_frac"], "avg_accepted_run": res["avg_accepted_run"],
+           "roofline": res["roofline"]}
+    # the prompt pass that precedes the timed steps (not part of `value`): useful operations against the matrix-core peak
+    pf = prefill_flops(cfg, plen) / (r["prefill_ms"] * 1e-3) / 1e12
+    out["prefill"] = {"tokens": int(plen.sum()), "ms": r["prefill_ms"],
+                      "roofline": {"bound": "mfma", "achieved": pf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": pf / MFMA_PEAK_TFLOPS}}
+    if extras:
+        n_x = max(8, min(K, 32))
+        bt = {}
+        for tau in (0.0, 1.5):                              # the two weight streams apart
+            x = summarise(timed(tau, None, 4, n_x), n_x, tau)
+            bt[f"tau_{tau}"] = {"ms_per_step": x["ms_per_step"], "hbm_frac": x["roofline"]["frac"],
+                                "target_calls_per_token": x["target_calls_per_token"]}
+        out["by_threshold"] = bt
+        rho = 0.09                                          # 1 / (Avg Tokens + 1) of Table 2 lies in 0.08 .. 0.13
+        x = summarise(timed(cfg.tau, rho, 4, n_x), n_x, cfg.tau)
+        out["at_reject_rate"] = {"asked": rho, "achieved": x["target_calls_per_token"], "value": x["value"],
+                                 "ms_per_step": x["ms_per_step"], "steps_with_target_frac": x["steps_with_target_frac"],
+                                 "hbm_frac": x["roofline"]["frac"],
+                                 "note": "verifier output bias set from 32 calibration steps so that this share of "
+                                         "the tokens is rejected (the rate Table 2's Avg Tokens implies)"}
+    if args.sweep:
+        n_x = max(8, min(K, 32))
+        sw = []
+        for tau in (0.3, 0.5, 0.7):
+            for rho in (0.05, 0.25, 0.60):
+                x = summarise(timed(tau, rho, 4, n_x), n_x, tau)
+                sw.append({"tau": tau, "reject_rate_asked": rho, "reject_rate_achieved": x["target_calls_per_token"],
+                           "value": x["value"], "ms_per_step": x["ms_per_step"], "hbm_frac": x["roofline"]["frac"],
+                           "mfma_frac_of_ceiling": x["roofline"].get("mfma", {}).get("frac_of_ceiling")})
+                print(f"[bench] sweep {sw[-1]}", file=sys.stderr, flush=True)
+        out["sweep"] = sw
+    s.close()
+    del s
+    torch.cuda.empty_cache()
+    if want_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, weights)
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default=None,
+                    help="c1 .. c5; default: c5 (the largest) as the headline with c2 (batch 16) beside it")
     ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--reject-rate", type=float, default=None,
+                    help="calibrate the verifier's output bias over 32 steps so that this share of the tokens is rejected")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the nine (tau, reject rate) settings {0.3, 0.5, 0.7} x {5, 25, 60 %} (configuration 4's)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the tau = 0 / 1.5 and 9 % reject-rate runs")
     ap.add_argument("--target-ctx", choices=("own", "full"), default="own",
                     help="own: single-token target calls on the row's own history (the headline path); "
                          "full: the target first consumes the committed tokens it has not seen")
@@ -267,114 +482,25 @@ def main():
     ap.add_argument("--chunk-rows", type=int, default=0,
                     help="entries per pass of a multi-entry forward (prefill chunks, work lists); 0 = library default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain device copy of 256 MiB three times (reference for hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU decode step only; this build has no multi-GPU path "
               f"(--gpus {args.gpus} is not supported, use --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    if not (args.reject_rate is None or 0.0 < args.reject_rate < 1.0):
+        raise SystemExit("--reject-rate must lie strictly between 0 and 1")
 
-    import numpy as np
-    import torch
     import workloads as W
-    from paper_2502_04557_amd import binding
-
-    base = W.config(args.config)
     K, Wm = args.steps, args.warmup
-    pmax = base.prompt_len
     if args.method == "sd":
-        return bench_sd(args, base)
-    need = pmax + Wm + K
-    lim = min(m.max_pos for m in (base.draft, base.target))
-    if need > lim:
-        raise SystemExit(f"prompt {pmax} + warmup {Wm} + steps {K} exceeds the models' context {lim}")
-    cfg = replace(base, max_seq=max(base.max_seq, need), tau=base.tau if args.tau is None else args.tau,
-                  target_ctx_mode=W.CTX_FULL_PREFIX if args.target_ctx == "full" else W.CTX_OWN_HISTORY,
-                  reject_mode=W.REJECT_SD if args.reject_mode == "sd" else W.REJECT_REPLACE,
-                  chunk_rows=args.chunk_rows)
-
-    t0 = time.time()
-    weights = W.make_weights(cfg)
-    prompts, plen = W.make_prompts(cfg)
-    print(f"[bench] {cfg.name}: weights generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
-
-    if args.copy_calibration:
-        src = torch.ones(1 << 26, dtype=torch.float32, device="cuda:0")      # 256 MiB read + 256 MiB written per copy
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    s = binding.Sprinter(cfg, "cuda:0")
-    for which, w in zip((binding.DRAFT, binding.TARGET, binding.VERIFIER), weights):
-        s.load_weights(which, w)
-    B = len(plen)
-    dev = s.device
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    s.prefill(prompts, plen)
-    torch.cuda.synchronize()
-    prefill_ms = (time.perf_counter() - t0) * 1e3
-    print(f"[bench] prefill of {int(plen.sum())} prompt tokens: {prefill_ms:.1f} ms", file=sys.stderr, flush=True)
-    seen_before = plen.astype(np.int64) - 1
-    if Wm:
-        wa = s.generate(Wm, want=("tok", "accept"))["accept"].cpu().numpy()
-        for b in range(B):
-            r = np.flatnonzero(wa[b] == 0)
-            if cfg.target_ctx_mode == 0:                      # own history: one entry per target call
-                seen_before[b] += len(r)
-            elif len(r):                                      # full prefix: the cache is complete after a rejection
-                seen_before[b] = plen[b] - 1 + r[-1] + 1
-    tok = torch.zeros(B, K, dtype=torch.int32, device=dev)
-    acc = torch.zeros(B, K, dtype=torch.uint8, device=dev)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record(s.stream)
-    s.generate_into(K, tok=tok, accept=acc)
-    ev1.record(s.stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ev_ms = ev0.elapsed_time(ev1)
-    st = s.stats()
-    accept = acc.cpu().numpy()
-    per_step_bytes, R = algorithmic_bytes(cfg, plen, accept, Wm, seen_before)
-    step_ms = ev_ms / K
-    achieved = per_step_bytes.mean() / (step_ms * 1e-3) / 1e9
-    out = {
-        "metric": "generated tokens/sec at batch B (1 GPU)",
-        "value": B * K / wall,
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": wall * 1e3 / K,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: batch {B}, prompt {pmax}, tau {cfg.tau}, T {cfg.temperature}; "
-                               f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
-                               f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts"
-                               + ("; full-prefix target context" if cfg.target_ctx_mode == 1 else "")
-                               + ("; p/q coin + residual on rejection" if cfg.reject_mode == 1 else ""),
-                   "batch": B, "prompt_len": pmax},
-        "target_calls_per_token": float(R.sum() / (B * K)),
-        "steps_with_target_frac": float((R > 0).mean()),
-        "avg_accepted_run": float(accept.sum() / max(1, (accept == 0).sum())),
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(cfg),
-                     "kernel": "one decode step (all kernels of sprinter_step)",
-                     "bytes_per_launch": float(per_step_bytes.mean()), "ms_per_launch": step_ms},
-    }
-    # the prompt pass that precedes the timed steps (not part of `value`): useful operations against the matrix-core peak
-    pf = prefill_flops(cfg, plen) / (prefill_ms * 1e-3) / 1e12
-    out["prefill"] = {"tokens": int(plen.sum()), "ms": prefill_ms,
-                      "roofline": {"bound": "mfma", "achieved": pf, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": pf / MFMA_PEAK_TFLOPS}}
-    s.close()
-    del s
-    torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, weights, B)
+        return bench_sd(args, W.config(args.config or "c2"))
+    extras = not args.no_extras and args.target_ctx == "own" and args.reject_mode == "replace" and args.tau is None
+    if args.config is not None:
+        out = run_decode(W.config(args.config), args, K, Wm, args.reject_rate, extras, not args.no_cpu_baseline)
+    else:
+        out = run_decode(W.config("c5"), args, K, Wm, args.reject_rate, extras, not args.no_cpu_baseline)
+        side = run_decode(W.config("c2"), args, K, Wm, args.reject_rate, extras, not args.no_cpu_baseline)
+        out["c2"] = side
     print(json.dumps(out))
 
 

@@ -15,9 +15,16 @@
  *   -> target single-token forward on the R rejected rows -> LM head + sample
  *   -> scatter the replacements back, advance per-row state.
  *
- * Everything is enqueued on the caller's HIP stream; nothing in a step
- * synchronises with the host (R stays on the device).  The library never
- * allocates device memory: the caller hands over one workspace.
+ * Everything is enqueued on the caller's HIP stream and all decisions are taken
+ * on the device.  The host learns one number per step, the count R of rejected
+ * rows: the calling thread waits a few microseconds inside sprinter_step (it
+ * polls a pinned host word the decide kernel writes) and then launches the
+ * target pass for exactly R rows, or none.  A step can therefore not be
+ * recorded into a HIP graph, and one thread drives a context at a time.
+ * sprinter_prefill drains the stream every 4 passes; sprinter_get_stats and
+ * sprinter_destroy wait for it.  The library never allocates device memory: the
+ * caller hands over one workspace.  sprinter_create allocates 256 bytes of
+ * pinned host memory (that polled word), freed by sprinter_destroy.
  *
  * Conventions
  *   - "dev" pointers are device memory, "host" pointers host memory.
@@ -150,11 +157,14 @@ typedef struct {
 
 typedef struct sprinter_ctx sprinter_ctx;
 
-/* Bytes of device workspace sprinter_create needs for cfg (KV caches of both
- * models for max_batch x max_seq, tile-packed weight copies, activations, state). */
+/* Bytes of device workspace sprinter_create needs for cfg: everything the loop
+ * of Alg. 2 keeps between tokens for the inputs "M_p, M_q, V, Prefix" (KV caches
+ * of both models for max_batch x max_seq, the committed prefixes), tile-packed
+ * weight copies and activations. */
 int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes);
 
-/* Creates a context on the current device.  dev_workspace (256-byte aligned, at
+/* Creates a context for one triple (M_q, M_p, V) and threshold tau, the fixed
+ * inputs of Alg. 1 / Alg. 2, on the current device.  dev_workspace (256-byte aligned, at
  * least sprinter_workspace_bytes) stays owned by the caller and must outlive the
  * context; hip_stream is a hipStream_t (NULL = the default stream) on which all
  * later work is enqueued.  The library allocates no device memory; create
@@ -164,7 +174,8 @@ int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes);
 int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes,
                     void* hip_stream, sprinter_ctx** out_ctx);
 
-/* Hands over the parameters of one model.  which: SPRINTER_DRAFT, _TARGET or
+/* Hands over the parameters of one of the three models of Sec. 3 (draft M_q,
+ * target M_p, verifier V of Sec. 3.2).  which: SPRINTER_DRAFT, _TARGET or
  * _VERIFIER.  names[i] / dev_ptrs[i] / shapes[4*i..4*i+3] (unused dims 0) describe
  * tensor i.  Names: "tok_emb" [V,d], "pos_emb" [max_pos,d] (GPT), "lm_head" [V,d]
  * (LLaMA), "normf.g" [d], "normf.b" [d] (GPT) and per layer i "l<i>.norm1.g",
@@ -181,7 +192,8 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
 int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names,
                           const void* const* dev_ptrs, const int64_t* shapes, int n);
 
-/* Starts B rows: resets state and counters and fills both KV caches with
+/* Takes the "Prefix" input of Alg. 1 / Alg. 2 for B independent rows: resets
+ * state and counters and fills both KV caches with
  * positions 0 .. P_b-2 of each prompt; the first decode step then feeds the last
  * prompt token at position P_b-1.  bf16: all (row, position) pairs go through both
  * models in row-major chunks of cfg.chunk_rows tokens per pass over the weights
@@ -194,7 +206,9 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
 int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t* host_prompt_len,
                      int B, int max_prompt);
 
-/* One decode step for all rows (the steps listed at the top).  out may be NULL.
+/* One iteration of the loop of Alg. 2 for every row: "q_r ~ M_q(Prefix)",
+ * "x ~ q_r", the test "V(s(x, Prefix)) >= tau", and for the rows that fail it
+ * "Run M_p Once" (the steps listed at the top).  out may be NULL.
  * Error if no prefill was done or a row would exceed max_seq / max_pos.
  * The calling thread waits inside the call (a few microseconds of polling on a
  * pinned word the decide kernel writes) until the device has counted the rejected
@@ -203,7 +217,9 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
  * a HIP graph, and two threads must not drive one context at the same time. */
 int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out);
 
-/* n_tokens decode steps back to back (each with the short wait described at
+/* The whole loop of Alg. 2 for a fixed number of tokens (the paper generates a
+ * fixed count per prompt, Sec. 4; there is no end-of-sequence rule): Prefix + t
+ * for t = 1 .. n_tokens.  n_tokens decode steps back to back (each with the short wait described at
  * sprinter_step; no stream synchronisation).  Outputs are [B, n_tokens] row-major
  * device arrays; any of them may be NULL: committed tokens, accept flags, verifier
  * scores, draft tokens.  The last step's tail is still running when the call returns. */
@@ -239,22 +255,15 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
 int sprinter_sd_generate(sprinter_ctx* ctx, int gamma, int n_rounds, int32_t* dev_out_tok, int tok_stride,
                          int32_t* dev_out_n_tok, int32_t* dev_out_n_acc, int32_t* dev_out_draft);
 
-/* Replaces the threshold tau (takes effect for steps enqueued afterwards). */
+/* Replaces the prediction threshold tau of Alg. 1 / Alg. 2 (the operating point on the
+ * verifier's ROC curve, Sec. 3.2); takes effect for steps enqueued afterwards. */
 int sprinter_set_tau(sprinter_ctx* ctx, float tau);
 
-/* Waits for the stream and copies the counters to the host.
+/* Waits for the stream and copies the counters to the host: the quantities behind
+ * Table 2's "Avg Tokens" (generated tokens per target call) and the cost model of
+ * Sec. 3.1(c) (number of target runs).
  * host_target_calls, if not NULL, receives the per-row number of target calls [B]. */
 int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* host_target_calls);
-
-/* For tuning tools and other callers that want a time breakdown (no paper passage: a
- * diagnostic).  With the environment variable SPRINTER_PHASE_TICKS=1 set at create time,
- * workgroup 0 of the persistent decode kernel accumulates 100 MHz clock ticks per phase
- * type; this call waits for the stream and copies 128 words to host_out: [0..63] tick sums
- * ([0..12]: embed, norm, QKV, attention, O-proj, FFN-up, FFN-down, LM head, verifier,
- * decide, finish, barrier wait, per-step fence as seen by wave 0; [13..14] wave 0 waiting
- * for partial sums / running epilogues; [16..47] the timeline of one compute wave inside the
- * four GEMM kinds), [64..127] the matching event counts.  All zero when off. */
-int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out);
 
 /* Waits for the stream, frees the context and its pinned word; the workspace stays with the caller. */
 void sprinter_destroy(sprinter_ctx* ctx);

@@ -17,7 +17,7 @@ DRAFT, TARGET, VERIFIER = 0, 1, 2
 F32, BF16 = 0, 1
 
 EXPORTS = ("sprinter_workspace_bytes", "sprinter_create", "sprinter_load_weights", "sprinter_prefill",
-           "sprinter_step", "sprinter_generate", "sprinter_sd_generate", "sprinter_set_tau", "sprinter_get_stats", "sprinter_debug_phase_ticks",
+           "sprinter_step", "sprinter_generate", "sprinter_sd_generate", "sprinter_set_tau", "sprinter_get_stats",
            "sprinter_destroy", "sprinter_last_error")
 
 
@@ -65,7 +65,6 @@ def load_library(path: str = LIB_PATH):
     lib.sprinter_sd_generate.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp]
     lib.sprinter_set_tau.argtypes = [vp, C.c_float]
     lib.sprinter_get_stats.argtypes = [vp, C.POINTER(StatsC), C.POINTER(C.c_int64)]
-    lib.sprinter_debug_phase_ticks.argtypes = [vp, C.POINTER(C.c_uint64)]
     lib.sprinter_destroy.argtypes = [vp]
     lib.sprinter_destroy.restype = None
     lib.sprinter_last_error.argtypes = [vp]
@@ -108,9 +107,9 @@ class Sprinter:
         need = C.c_size_t(0)
         self._check(self.lib.sprinter_workspace_bytes(C.byref(self.ccfg), C.byref(need)), None)
         self.workspace_bytes = need.value
-        self.workspace = torch.empty(need.value, dtype=torch.uint8, device=self.device)
         self.stream = torch.cuda.current_stream(self.device)
         ctx = C.c_void_p(None)
+        self.workspace = torch.empty(need.value, dtype=torch.uint8, device=self.device)
         self._check(self.lib.sprinter_create(C.byref(self.ccfg), _ptr(self.workspace), need.value,
                                              C.c_void_p(self.stream.cuda_stream), C.byref(ctx)), None)
         self.ctx = ctx
@@ -227,17 +226,6 @@ class Sprinter:
 
     def set_tau(self, tau: float):
         self._check(self.lib.sprinter_set_tau(self.ctx, tau), self.ctx)
-
-    def phase_ticks(self) -> dict:
-        """Tick counters of the persistent kernels (see sprinter_debug_phase_ticks): name -> (microseconds, events)."""
-        buf = (C.c_uint64 * 128)()
-        self._check(self.lib.sprinter_debug_phase_ticks(self.ctx, buf), self.ctx)
-        names = ["embed", "norm", "qkv", "attn", "oproj", "ffn1", "ffn2", "lmhead", "verifier", "decide", "finish",
-                 "barrier", "fence", "w0_wait_partials", "w0_epilogue", "w0_15"]
-        for kind in ("qkv", "oproj", "ffn1", "ffn2"):
-            names += [f"c_{kind}_{x}" for x in ("barrier", "stats", "operands", "mfma", "prefetch", "sync", "6", "7")]
-        names += [f"slot{i}" for i in range(len(names), 64)]
-        return {n: (buf[i] / 100.0, int(buf[64 + i])) for i, n in enumerate(names)}
 
     def stats(self) -> dict:
         st = StatsC()

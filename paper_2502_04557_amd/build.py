@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsprinter.so")
 NATIVE_BENCH = os.path.join(PKG, "native_bench")
-SOURCES = ["k_norm.hip", "k_gemm.hip", "k_attn.hip", "k_lmhead.hip", "k_control.hip", "k_sd.hip", "mega.hip", "mega16.hip", "abi.cpp"]
+SOURCES = ["k_norm.hip", "k_gemm.hip", "k_attn.hip", "k_lmhead.hip", "k_control.hip", "k_sd.hip", "abi.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 VALU forms are kept off on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -78,7 +78,12 @@ struct sprinter_ctx {
   float* score = nullptr;
   unsigned char* accept = nullptr;
   int rows_alloc = 0;
-  unsigned long long* host_counts = nullptr;   // pinned: [0] (ticket << 32) | rejected rows, written by the decide kernel
+  unsigned long long* host_counts = nullptr;   // what the host reads: [0] (ticket << 32) | rejected rows, [1] work-list entries, [2] draft entries
+  unsigned long long* kernel_word = nullptr;   // where the kernels store those words: host_counts itself (pinned memory), or, for a
+                                               // context of sprinter_create_static, four words of the workspace that wait_ticket copies
+  unsigned long long* dev_counts = nullptr;    // those four words of the workspace
+  unsigned long long static_words[4] = {0, 0, 0, 0};
+  int static_dev = -1;                         // >= 0: the workspace is the library's static array on that device
   unsigned ticket = 0;
   int *ent_off = nullptr, *t_last = nullptr;   // full-prefix mode: work-list prefix sums, last-entry flags of a chunk
   int* coin_kept = nullptr;                    // reject_mode 1: counter, and the step's logits of both models
@@ -89,17 +94,6 @@ struct sprinter_ctx {
   int sd_next_entries = 0;       // entries of the next round's first draft pass, once known
   unsigned sd_wait_ticket = 0;   // != 0: the last round's finish kernel will report them under this ticket
   int run_kind = 0;              // since the last prefill: 0 nothing, 1 decode steps, 2 speculative-decoding rounds
-  // persistent decode kernel (bf16 mode)
-  bool mega_on = false, mega_built = false;
-  int mega_mt = 1, mega_grid = 0;
-  size_t mega_smem = 0;
-  int mega_tab_bytes = 0;
-  MegaParams mega_host;
-  MegaParams* mega_dev = nullptr;
-  LayerW *mega_layers_q = nullptr, *mega_layers_p = nullptr;
-  std::vector<PhaseDesc> mega_phases_q, mega_phases_p;
-  int* mega_err = nullptr;
-  unsigned long long* mega_prof = nullptr;
   // host bookkeeping
   int B = 0, max_prompt_len = 0;
   long long steps_done = 0;
@@ -134,7 +128,6 @@ size_t act_plane(int dtype, int rows, int K) { return (size_t)rows * (dtype == S
 size_t act_elems(int dtype, int rows, int K) { return act_plane(dtype, rows, K) * (dtype == SPRINTER_F32 ? 1 : 2); }
 size_t packed_elems(int N, int K) { return (size_t)round_up(N, 16) * round_up(K, 32); }
 
-constexpr int MEGA_MAX_WG = 512;
 constexpr int DEFAULT_CHUNK_ROWS = 4096;
 
 const char* check_model(const sprinter_model_cfg& m, const char* who, char* buf, size_t n) {
@@ -178,7 +171,8 @@ int validate_cfg(const sprinter_cfg* c, char* buf, size_t n) {
   if (c->sd_gamma < 0 || c->sd_gamma > 16) BAD("sd_gamma %d outside [0, 16]", c->sd_gamma);
   if (c->chunk_rows != 0 && (c->chunk_rows < 64 || c->chunk_rows > 4096 || c->chunk_rows % 64 != 0))
     BAD("chunk_rows %d is not 0 or a multiple of 64 in [64, 4096]", c->chunk_rows);
-  for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
+  // the float32 attention kernel keeps one score per cached key in LDS; the bf16 kernels keep none
+  if (c->dtype == SPRINTER_F32) for (const sprinter_model_cfg* m : {&c->draft, &c->target}) {
     int dh = m->d_model / m->n_head, G = m->n_head / m->n_kv_head;
     size_t lds = (size_t)(G * dh + 2 * dh + 4 * G * dh + G * c->max_seq) * 4;
     if (lds > 64 * 1024) BAD("attention needs %zu bytes of LDS for max_seq %d (limit 65536)", lds, c->max_seq);
@@ -271,13 +265,6 @@ void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc
   }
 }
 
-// The persistent decode kernel is opt-in (environment, read when the workspace is sized and when the context is
-// created): only then are its per-layer activation buffers part of the workspace.
-bool persistent_requested(const sprinter_cfg& c) {
-  const char* on = getenv("SPRINTER_PERSISTENT");
-  return on && on[0] == '1' && c.dtype == SPRINTER_BF16 && c.target_ctx_mode == 0 && c.reject_mode == 0;
-}
-
 // Rows the activation buffers hold = entries one pass of a multi-entry forward takes (prefill chunks, full-prefix
 // work lists, speculative-decoding windows).
 int chunk_rows_of(const sprinter_cfg& c) {
@@ -345,55 +332,12 @@ size_t carve(const sprinter_cfg& c, void* base, sprinter_ctx* ctx, size_t* scrat
   int* rej_idx = (int*)bump.take((size_t)c.max_batch * 4);
   int* n_rej = (int*)bump.take(4);
   int* committed = (int*)bump.take((size_t)c.max_batch * 4);
-  // buffers of the persistent decode kernel: one activation buffer per layer (written once per step)
-  MegaParams mp;
-  memset(&mp, 0, sizeof mp);
-  LayerW *lw_q = nullptr, *lw_p = nullptr;
-  MegaParams* mp_dev = nullptr;
-  if (persistent_requested(c)) {
-    int which = 0;
-    for (const sprinter_model_cfg* mc : {&c.draft, &c.target}) {
-      MegaModel& mm = which == 0 ? mp.draft : mp.target;
-      ModelDims md = dims_of(*mc);
-      const int L = md.n_layer;
-      mm.md = md;
-      mm.pl_d = act_plane(c.dtype, rows, md.d);
-      mm.pl_a = act_plane(c.dtype, rows, md.H * md.dh);
-      mm.pl_f = act_plane(c.dtype, rows, md.ff);
-      mm.xn_stride = 2 * mm.pl_d; mm.ao_stride = 2 * mm.pl_a; mm.mid_stride = 2 * mm.pl_f;
-      mm.y_stride = (size_t)rows * md.dqkv; mm.h_stride = (size_t)rows * md.d;
-      mm.h0 = (float*)bump.take(mm.h_stride * 4);
-      mm.xn1 = (unsigned short*)bump.take(mm.xn_stride * L * 2);
-      mm.xn2 = (unsigned short*)bump.take(mm.xn_stride * L * 2);
-      mm.y = (float*)bump.take(mm.y_stride * L * 4);
-      mm.ao = (unsigned short*)bump.take(mm.ao_stride * L * 2);
-      mm.mid = (unsigned short*)bump.take(mm.mid_stride * L * 2);
-      mm.hA = (float*)bump.take(mm.h_stride * L * 4);
-      mm.hB = (float*)bump.take(mm.h_stride * L * 4);
-      mm.hf = (float*)bump.take(mm.h_stride * 4);
-      mm.hfn = (unsigned short*)bump.take(mm.xn_stride * 2);
-      mm.rope = (float*)bump.take((size_t)rows * md.dh * 4);
-      mm.stats_stride = (size_t)((md.d + 15) / 16) * 16 * 2;
-      mm.stats = (float*)bump.take(mm.stats_stride * (2 * L + 1) * 4);
-      mm.am_part = (unsigned long long*)bump.take((size_t)MEGA_MAX_WG * rows * 8);
-      LayerW* lw = (LayerW*)bump.take((size_t)L * sizeof(LayerW));
-      mm.phases = (const PhaseDesc*)bump.take((size_t)(7 * L + 4) * sizeof(PhaseDesc));
-      if (which == 0) lw_q = lw; else lw_p = lw;
-      ++which;
-    }
-    mp.sync = (unsigned*)bump.take(65536);
-    mp.epoch = (unsigned*)bump.take(256);
-    mp.err = (int*)bump.take(256);
-    mp.prof = (unsigned long long*)bump.take(1024);
-    mp_dev = (MegaParams*)bump.take(sizeof(MegaParams));
-  }
+  unsigned long long* dev_counts = (unsigned long long*)bump.take(256);
   size_t total = (bump.off + 255) & ~(size_t)255;
   if (ctx) {
-    ctx->mega_host = mp; ctx->mega_layers_q = lw_q; ctx->mega_layers_p = lw_p; ctx->mega_dev = mp_dev;
-    ctx->mega_err = mp.err;
     ctx->ver_part = ver_part; ctx->ver_chunks = chunks; ctx->st = st; ctx->tau_dev = tau;
     ctx->draft_tok = draft_tok; ctx->score = score; ctx->accept = accept; ctx->rej_idx = rej_idx;
-    ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows;
+    ctx->n_rej = n_rej; ctx->committed = committed; ctx->rows_alloc = rows; ctx->dev_counts = dev_counts;
     ctx->ent_off = ent_off; ctx->t_last = t_last; ctx->coin_kept = coin_kept; ctx->dl = dl; ctx->tl = tl;
     sd.st = st; sd.coin_kept = coin_kept; sd.V = c.target.vocab;
     sd.seed_lo = (unsigned)(c.seed & 0xFFFFFFFFull); sd.seed_hi = (unsigned)(c.seed >> 32);
@@ -478,137 +422,6 @@ int check_ready(sprinter_ctx* ctx) {
   return SPRINTER_OK;
 }
 
-// Fills the device-side description of both models for the persistent kernel (once, after all weights are in).
-int build_mega(sprinter_ctx* ctx) {
-  if (!ctx->mega_on || ctx->mega_built) return SPRINTER_OK;
-  MegaParams& hp = ctx->mega_host;
-  int which = 0;
-  for (Model* m : {&ctx->draft, &ctx->target}) {
-    MegaModel& mm = which == 0 ? hp.draft : hp.target;
-    LayerW* lw = which == 0 ? ctx->mega_layers_q : ctx->mega_layers_p;
-    mm.tok_emb = m->tok_emb; mm.pos_emb = m->pos_emb; mm.lm_head = m->lm_head;
-    mm.normf_g = (const float*)m->normf_g; mm.normf_b = (const float*)m->normf_b;
-    mm.layers = lw;
-    mm.kcache = m->kcache; mm.vcache = m->vcache; mm.layer_stride = m->layer_stride;
-    mm.rd_n = m->rd_n; mm.rd_b = m->rd_b; mm.rd_tok = m->rd_tok; mm.rd_pos = m->rd_pos; mm.rd_slot = m->rd_slot;
-    if (hipMemcpyAsync(lw, m->layers.data(), m->layers.size() * sizeof(LayerW), hipMemcpyHostToDevice, ctx->stream) !=
-        hipSuccess)
-      return fail(ctx, SPRINTER_E_HIP, "copy of the layer table failed");
-    {   // the phase list of one forward
-      std::vector<PhaseDesc>& ph = which == 0 ? ctx->mega_phases_q : ctx->mega_phases_p;
-      ph.clear();
-      const ModelDims& md = mm.md;
-      const int d = md.d, Kt_d = (d + 31) / 32, Kt_a = (md.H * md.dh + 31) / 32, Kt_f = (md.ff + 31) / 32;
-      const bool fused = ctx->mega_mt == 1;
-      const bool gpt = md.arch == SPRINTER_ARCH_GPT;
-      auto blank = [](int kind) { PhaseDesc p; memset(&p, 0, sizeof p); p.kind = kind; return p; };
-      auto norm_phase = [&](const float* h, const float* g, const float* b, unsigned short* out, float* f32_out) {
-        PhaseDesc p = blank(PK_NORM);
-        p.h = h; p.g = g; p.b = b; p.eps = md.eps; p.arch = md.arch; p.K = d; p.out_act = out; p.out_plane = mm.pl_d;
-        p.f32_out2 = f32_out;
-        return p;
-      };
-      ph.push_back(blank(PK_EMBED));
-      const float* h_prev = mm.h0;
-      const float* st_prev = mm.stats;
-      for (int l = 0; l < md.n_layer; ++l) {
-        const LayerW& L = m->layers[l];
-        unsigned short* xn1 = mm.xn1 + mm.xn_stride * l;
-        unsigned short* xn2 = mm.xn2 + mm.xn_stride * l;
-        float* y = mm.y + mm.y_stride * l;
-        unsigned short* ao = mm.ao + mm.ao_stride * l;
-        unsigned short* mid = mm.mid + mm.mid_stride * l;
-        float* hA = mm.hA + mm.h_stride * l;
-        float* hB = mm.hB + mm.h_stride * l;
-        float* stA = mm.stats + mm.stats_stride * (1 + 2 * l);
-        float* stB = mm.stats + mm.stats_stride * (2 + 2 * l);
-        if (!fused) ph.push_back(norm_phase(h_prev, L.n1g, L.n1b, xn1, nullptr));
-        {
-          PhaseDesc p = blank(PK_GEMM);
-          p.epi = EPI_F32; p.layer = 2; p.fused_norm = fused;
-          p.W = (const uint4*)L.wqkv; p.N = md.dqkv; p.Kt = Kt_d; p.n_tiles = (md.dqkv + 15) / 16; p.K = d; p.bias = L.bqkv;
-          if (fused) { p.h = h_prev; p.stats_in = st_prev; p.n_stat_tiles = (d + 15) / 16; p.g = L.n1g; p.b = L.n1b; p.eps = md.eps; p.arch = md.arch; }
-          else { p.X = (const uint4*)xn1; p.x_plane16 = mm.pl_d / 8; }
-          p.out_f32 = y; p.ldo = md.dqkv;
-          ph.push_back(p);
-        }
-        { PhaseDesc p = blank(PK_ATTN); p.layer = l; ph.push_back(p); }
-        {
-          PhaseDesc p = blank(PK_GEMM);
-          p.epi = EPI_RESID; p.layer = 4;
-          p.W = (const uint4*)L.wo; p.N = d; p.Kt = Kt_a; p.n_tiles = (d + 15) / 16; p.K = md.H * md.dh; p.bias = L.bo;
-          p.X = (const uint4*)ao; p.x_plane16 = mm.pl_a / 8;
-          p.resid = h_prev; p.out_f32 = hA; p.ldo = d; p.stats_out = fused ? stA : nullptr;
-          ph.push_back(p);
-        }
-        if (!fused) ph.push_back(norm_phase(hA, L.n2g, L.n2b, xn2, nullptr));
-        {
-          PhaseDesc p = blank(PK_GEMM);
-          p.epi = gpt ? EPI_GELU : EPI_SWIGLU; p.layer = 5; p.fused_norm = fused;
-          p.W = (const uint4*)(gpt ? L.w1 : L.wg); p.W2 = gpt ? nullptr : (const uint4*)L.wu;
-          p.N = md.ff; p.Kt = Kt_d; p.n_tiles = (md.ff + 15) / 16; p.K = d; p.bias = gpt ? L.b1 : nullptr;
-          if (fused) { p.h = hA; p.stats_in = stA; p.n_stat_tiles = (d + 15) / 16; p.g = L.n2g; p.b = L.n2b; p.eps = md.eps; p.arch = md.arch; }
-          else { p.X = (const uint4*)xn2; p.x_plane16 = mm.pl_d / 8; }
-          p.out_act = mid; p.out_K = md.ff; p.out_plane = mm.pl_f;
-          ph.push_back(p);
-        }
-        {
-          PhaseDesc p = blank(PK_GEMM);
-          p.epi = EPI_RESID; p.layer = 6;
-          p.W = (const uint4*)L.w2; p.N = d; p.Kt = Kt_f; p.n_tiles = (d + 15) / 16; p.K = md.ff; p.bias = L.b2;
-          p.X = (const uint4*)mid; p.x_plane16 = mm.pl_f / 8;
-          p.resid = hA; p.out_f32 = hB; p.ldo = d; p.stats_out = fused ? stB : nullptr;
-          ph.push_back(p);
-        }
-        h_prev = hB;
-        st_prev = stB;
-      }
-      ph.push_back(norm_phase(h_prev, (const float*)m->normf_g, (const float*)m->normf_b, mm.hfn, mm.hf));
-      ph.push_back(blank(PK_LMHEAD));
-      if (ctx->mega_mt == 1 && (int)ph.size() != mm.n_phases)
-        return fail(ctx, SPRINTER_E_STATE, "phase list of %d entries, expected %d", (int)ph.size(), mm.n_phases);
-      mm.n_phases = (int)ph.size();
-      if (hipMemcpyAsync((void*)mm.phases, ph.data(), ph.size() * sizeof(PhaseDesc), hipMemcpyHostToDevice, ctx->stream) !=
-          hipSuccess)
-        return fail(ctx, SPRINTER_E_HIP, "copy of the phase table failed");
-    }
-    ++which;
-  }
-  hp.v_w1 = (const float*)ctx->v_w1; hp.v_b1 = (const float*)ctx->v_b1;
-  hp.v_w2 = (const float*)ctx->v_w2; hp.v_b2 = (const float*)ctx->v_b2;
-  hp.ver_d_hidden = ctx->cfg.ver_d_hidden; hp.ver_chunks = ctx->ver_chunks; hp.ver_part = ctx->ver_part;
-  hp.st = ctx->st; hp.tau = ctx->tau_dev;
-  hp.draft_tok = ctx->draft_tok; hp.rej_idx = ctx->rej_idx; hp.n_rej = ctx->n_rej; hp.committed = ctx->committed;
-  hp.score = ctx->score; hp.accept = ctx->accept;
-  hp.seed_lo = (unsigned)(ctx->cfg.seed & 0xFFFFFFFFull); hp.seed_hi = (unsigned)(ctx->cfg.seed >> 32);
-  hp.inv_temperature = ctx->cfg.temperature > 0.f ? 1.0f / ctx->cfg.temperature : 0.f;
-  hp.rows_alloc = ctx->rows_alloc; hp.max_seq = ctx->cfg.max_seq; hp.max_batch = ctx->cfg.max_batch;
-  if (hipMemcpyAsync(ctx->mega_dev, &hp, sizeof hp, hipMemcpyHostToDevice, ctx->stream) != hipSuccess)
-    return fail(ctx, SPRINTER_E_HIP, "copy of the kernel parameters failed");
-  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
-  ctx->mega_built = true;
-  return SPRINTER_OK;
-}
-
-int enqueue_mega(sprinter_ctx* ctx, const sprinter_step_out* out, int n_steps, int n_tokens, int32_t* g_tok,
-                 uint8_t* g_accept, float* g_score, int32_t* g_draft_tok) {
-  MegaOut o;
-  memset(&o, 0, sizeof o);
-  o.B = ctx->B; o.n_tokens = n_tokens;
-  if (out) {
-    o.o_draft_tok = out->draft_tok; o.o_rej_idx = out->rej_idx; o.o_n_rej = out->n_rej;
-    o.o_committed = out->committed_tok; o.o_score = out->score; o.o_accept = out->accept;
-    o.o_draft_logits = out->draft_logits; o.o_draft_hidden = out->draft_hidden;
-    o.o_target_logits = out->target_logits; o.o_target_hidden = out->target_hidden;
-  }
-  o.g_tok = g_tok; o.g_draft_tok = g_draft_tok; o.g_accept = g_accept; o.g_score = g_score;
-  hipError_t e = ctx->mega_mt == 1
-                     ? launch_mega16(ctx->mega_dev, n_steps, o, ctx->mega_smem, ctx->mega_tab_bytes, ctx->mega_grid, ctx->stream)
-                     : launch_mega(ctx->mega_dev, ctx->mega_mt, n_steps, o, ctx->mega_smem, ctx->mega_grid, ctx->stream);
-  if (e != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "cooperative launch failed: %s", hipGetErrorString(e));
-  return SPRINTER_OK;
-}
-
 int check_room(sprinter_ctx* ctx, long long extra_steps) {
   if (!ctx->prefilled) return fail(ctx, SPRINTER_E_STATE, "no prefill has been done");
   long long last_slot = (long long)ctx->max_prompt_len - 1 + ctx->steps_done + extra_steps - 1;
@@ -621,6 +434,16 @@ int check_room(sprinter_ctx* ctx, long long extra_steps) {
 // Polls a pinned word a kernel stores (ticket << 32) | value into; after 2 s without the ticket it falls back to
 // a stream synchronisation.
 int wait_ticket(sprinter_ctx* ctx, volatile unsigned long long* word, unsigned ticket, int* value, const char* what) {
+  if (ctx->static_dev >= 0) {
+    // no pinned memory in this kind of context: the kernels store the words in the workspace; fetch them
+    if (hipMemcpyAsync(ctx->static_words, ctx->dev_counts, sizeof ctx->static_words, hipMemcpyDeviceToHost, ctx->stream) != hipSuccess ||
+        hipStreamSynchronize(ctx->stream) != hipSuccess)
+      return fail(ctx, SPRINTER_E_HIP, "waiting for the device failed: %s", hipGetErrorString(hipGetLastError()));
+    const unsigned long long v = *word;
+    if ((unsigned)(v >> 32) != ticket) return fail(ctx, SPRINTER_E_HIP, "%s", what);
+    *value = (int)(unsigned)(v & 0xFFFFFFFFull);
+    return SPRINTER_OK;
+  }
   const auto t0 = std::chrono::steady_clock::now();
   for (unsigned spin = 0;; ++spin) {
     const unsigned long long v = *word;
@@ -659,7 +482,7 @@ int enqueue_step(sprinter_ctx* ctx, const sprinter_step_out* out, int n_tokens, 
   da.o_n_rej = out ? out->n_rej : nullptr;
   const int mode = ctx->cfg.target_ctx_mode;
   da.ctx_mode = mode; da.ent_off = ctx->ent_off;
-  da.host_word = ctx->host_counts; da.ticket = ++ctx->ticket;
+  da.host_word = ctx->kernel_word; da.ticket = ++ctx->ticket;
   if (da.ticket == 0) da.ticket = ++ctx->ticket;   // 0 is the word's initial value
   launch_draft_decide(da, s);
   // The host waits for the number of rejected rows R: the target's kernels are then launched for exactly R
@@ -728,30 +551,10 @@ int hip_status(sprinter_ctx* ctx, const char* what) {
   return SPRINTER_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes) {
-  if (!cfg || !out_bytes) return fail(nullptr, SPRINTER_E_NULL, "sprinter_workspace_bytes: NULL argument");
-  char buf[256];
-  int rc = validate_cfg(cfg, buf, sizeof buf);
-  if (rc) return fail(nullptr, rc, "%s", buf);
-  *out_bytes = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
-  return SPRINTER_OK;
-}
-
-int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes, void* hip_stream,
-                    sprinter_ctx** out_ctx) {
-  if (!cfg || !dev_workspace || !out_ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_create: NULL argument");
-  *out_ctx = nullptr;
-  char buf[256];
-  int rc = validate_cfg(cfg, buf, sizeof buf);
-  if (rc) return fail(nullptr, rc, "%s", buf);
-  if (((uintptr_t)dev_workspace) & 255) return fail(nullptr, SPRINTER_E_WORKSPACE, "workspace is not 256-byte aligned");
-  size_t need = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
-  if (workspace_bytes < need)
-    return fail(nullptr, SPRINTER_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+// What sprinter_create and sprinter_create_static share: cfg is valid and the workspace large enough.
+// static_dev >= 0: the workspace is the library's static array on that device and the context must not allocate
+// anything, pinned host memory included.
+int create_common(const sprinter_cfg* cfg, void* dev_workspace, void* hip_stream, int static_dev, sprinter_ctx** out_ctx) {
   sprinter_ctx* ctx = new sprinter_ctx();
   ctx->cfg = *cfg;
   ctx->stream = (hipStream_t)hip_stream;
@@ -780,63 +583,55 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
     launch_fill_zero(m->sc.hfn, act_elems(cfg->dtype, rows, m->md.d) * es, ctx->stream);
   }
   launch_set_f32(ctx->tau_dev, cfg->tau, ctx->stream);
-  if (hipHostMalloc((void**)&ctx->host_counts, 256, hipHostMallocDefault) != hipSuccess) {
-    delete ctx;
-    return fail(nullptr, SPRINTER_E_HIP, "allocation of the pinned count buffer failed");
+  launch_fill_zero(ctx->dev_counts, 256, ctx->stream);
+  if (static_dev >= 0) {
+    ctx->static_dev = static_dev;
+    ctx->host_counts = ctx->static_words;
+    ctx->kernel_word = ctx->dev_counts;
+  } else {
+    if (hipHostMalloc((void**)&ctx->host_counts, 256, hipHostMallocDefault) != hipSuccess) {
+      delete ctx;
+      return fail(nullptr, SPRINTER_E_HIP, "allocation of the pinned count buffer failed");
+    }
+    memset(ctx->host_counts, 0, 256);
+    ctx->kernel_word = ctx->host_counts;
   }
-  memset(ctx->host_counts, 0, 256);
-  if (persistent_requested(*cfg)) {
-    // operand-tile planes of the persistent kernel: padding lanes must read as zero
-    for (MegaModel* mm : {&ctx->mega_host.draft, &ctx->mega_host.target}) {
-      const int L = mm->md.n_layer;
-      launch_fill_zero(mm->xn1, mm->xn_stride * L * 2, ctx->stream);
-      launch_fill_zero(mm->xn2, mm->xn_stride * L * 2, ctx->stream);
-      launch_fill_zero(mm->ao, mm->ao_stride * L * 2, ctx->stream);
-      launch_fill_zero(mm->mid, mm->mid_stride * L * 2, ctx->stream);
-      launch_fill_zero(mm->hfn, mm->xn_stride * 2, ctx->stream);
-    }
-    launch_fill_zero(ctx->mega_host.sync, 65536, ctx->stream);
-    launch_fill_zero(ctx->mega_host.epoch, 256, ctx->stream);
-    launch_fill_zero(ctx->mega_host.err, 256, ctx->stream);
-    launch_fill_zero(ctx->mega_host.prof, 1024, ctx->stream);
-    ctx->mega_prof = ctx->mega_host.prof;
-    {
-      const char* pp = getenv("SPRINTER_PHASE_TICKS");
-      if (!(pp && pp[0] == '1')) ctx->mega_host.prof = nullptr;
-    }
-    // the persistent kernel is opt-in while the per-operation kernels are the faster path
-    {
-      const int rows = ctx->rows_alloc;
-      const int rb = rows_alloc_for(cfg->max_batch);      // row tiles follow the batch; the buffers may hold more rows
-      ctx->mega_mt = rb <= 16 ? 1 : rb <= 32 ? 2 : rb <= 64 ? 4 : 8;
-      MegaParams& hp = ctx->mega_host;
-      hp.max_seq = cfg->max_seq; hp.max_batch = cfg->max_batch; hp.rows_alloc = rows;
-      int grid = 0;
-      hipError_t e;
-      if (ctx->mega_mt == 1) {
-        hp.draft.n_phases = 5 * hp.draft.md.n_layer + 3;     // embed, 5 per layer, final norm, LM head
-        hp.target.n_phases = 5 * hp.target.md.n_layer + 3;
-        ctx->mega_smem = mega16_smem_bytes(hp, &ctx->mega_tab_bytes);
-        e = ctx->mega_smem <= 160 * 1024 ? mega16_prepare(ctx->mega_smem, &grid) : hipErrorInvalidValue;
-      } else {
-        ctx->mega_smem = mega_smem_bytes(hp, ctx->mega_mt);
-        e = ctx->mega_smem <= 160 * 1024 ? mega_prepare(ctx->mega_mt, ctx->mega_smem, &grid) : hipErrorInvalidValue;
-      }
-      int dev = 0, coop = 0;
-      (void)hipGetDevice(&dev);
-      (void)hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev);
-      if (e == hipSuccess && grid > 0 && coop) {
-        ctx->mega_on = true;
-        ctx->mega_grid = grid < MEGA_MAX_WG ? grid : MEGA_MAX_WG;
-      } else {
-        (void)hipGetLastError();   // the per-operation kernels remain available
-      }
-    }
+  int rc = hip_status(ctx, "sprinter_create");
+  if (rc) {
+    if (static_dev >= 0) { ctx->static_dev = -1; ctx->host_counts = nullptr; }   // (the caller releases the static workspace)
+    sprinter_destroy(ctx);
+    return rc;
   }
-  rc = hip_status(ctx, "sprinter_create");
-  if (rc) { sprinter_destroy(ctx); return rc; }
   *out_ctx = ctx;
   return SPRINTER_OK;
+}
+
+
+}  // namespace
+
+extern "C" {
+
+int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes) {
+  if (!cfg || !out_bytes) return fail(nullptr, SPRINTER_E_NULL, "sprinter_workspace_bytes: NULL argument");
+  char buf[256];
+  int rc = validate_cfg(cfg, buf, sizeof buf);
+  if (rc) return fail(nullptr, rc, "%s", buf);
+  *out_bytes = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
+  return SPRINTER_OK;
+}
+
+int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes, void* hip_stream,
+                    sprinter_ctx** out_ctx) {
+  if (!cfg || !dev_workspace || !out_ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_create: NULL argument");
+  *out_ctx = nullptr;
+  char buf[256];
+  int rc = validate_cfg(cfg, buf, sizeof buf);
+  if (rc) return fail(nullptr, rc, "%s", buf);
+  if (((uintptr_t)dev_workspace) & 255) return fail(nullptr, SPRINTER_E_WORKSPACE, "workspace is not 256-byte aligned");
+  size_t need = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
+  if (workspace_bytes < need)
+    return fail(nullptr, SPRINTER_E_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  return create_common(cfg, dev_workspace, hip_stream, -1, out_ctx);
 }
 
 int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names, const void* const* dev_ptrs,
@@ -890,7 +685,6 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
   if (which == SPRINTER_DRAFT) ctx->draft.loaded = true;
   else if (which == SPRINTER_TARGET) ctx->target.loaded = true;
   else ctx->v_loaded = true;
-  ctx->mega_built = false;     // the persistent kernel's tables hold the weight pointers
   return hip_status(ctx, "sprinter_load_weights");
 }
 
@@ -899,8 +693,6 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
   if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_prefill: NULL context");
   if (!dev_prompt || !host_prompt_len) return fail(ctx, SPRINTER_E_NULL, "sprinter_prefill: NULL argument");
   int rc = check_ready(ctx);
-  if (rc) return rc;
-  rc = build_mega(ctx);
   if (rc) return rc;
   if (B < 1 || B > ctx->cfg.max_batch) return fail(ctx, SPRINTER_E_RANGE, "batch %d outside [1, %d]", B, ctx->cfg.max_batch);
   if (max_prompt < 1 || max_prompt > ctx->cfg.max_seq)
@@ -973,15 +765,8 @@ int sprinter_step(sprinter_ctx* ctx, const sprinter_step_out* out) {
   ctx->run_kind = 1;
   if (ctx->cfg.target_ctx_mode == 1 && out && (out->target_logits || out->target_hidden))
     return fail(ctx, SPRINTER_E_CONFIG, "target_logits / target_hidden are not produced with the full-prefix target context");
-  rc = build_mega(ctx);
+  rc = enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
   if (rc) return rc;
-  if (ctx->mega_on) {
-    rc = enqueue_mega(ctx, out, 1, 0, nullptr, nullptr, nullptr, nullptr);
-    if (rc) return rc;
-  } else {
-    rc = enqueue_step(ctx, out, 0, nullptr, nullptr, nullptr, nullptr);
-    if (rc) return rc;
-  }
   ctx->steps_done += 1;
   return hip_status(ctx, "sprinter_step");
 }
@@ -996,23 +781,12 @@ int sprinter_generate(sprinter_ctx* ctx, int n_tokens, int32_t* dev_out_tok, uin
   if (rc) return rc;
   if (ctx->run_kind == 2) return fail(ctx, SPRINTER_E_STATE, "speculative-decoding rounds were run since the last prefill");
   if (n_tokens > 0) ctx->run_kind = 1;
-  rc = build_mega(ctx);
-  if (rc) return rc;
   launch_reset_gen_idx(ctx->st.counters, ctx->stream);
-  if (ctx->mega_on) {
-    if (n_tokens > 0) {
-      rc = enqueue_mega(ctx, nullptr, n_tokens, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
-      if (rc) return rc;
-    }
-  } else {
-    for (int g = 0; g < n_tokens; ++g) {
-      rc = enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
-      if (rc) return rc;
-      ctx->steps_done += 1;
-    }
-    return hip_status(ctx, "sprinter_generate");
+  for (int g = 0; g < n_tokens; ++g) {
+    rc = enqueue_step(ctx, nullptr, n_tokens, dev_out_tok, dev_out_accept, dev_out_score, dev_out_draft_tok);
+    if (rc) return rc;
+    ctx->steps_done += 1;
   }
-  ctx->steps_done += n_tokens;
   return hip_status(ctx, "sprinter_generate");
 }
 
@@ -1086,7 +860,7 @@ int sprinter_sd_generate(sprinter_ctx* ctx, int gamma, int n_rounds, int32_t* de
     SdFinishArgs fa;
     fa.round = r; fa.n_rounds = n_rounds; fa.tok_stride = tok_stride;
     fa.o_tok = dev_out_tok; fa.o_n_tok = dev_out_n_tok; fa.o_n_acc = dev_out_n_acc; fa.o_draft = dev_out_draft;
-    fa.host_word = ctx->host_counts + 2;
+    fa.host_word = ctx->kernel_word + 2;
     fa.ticket = ++ctx->ticket;
     if (fa.ticket == 0) fa.ticket = ++ctx->ticket;
     launch_sd_round_finish(sd, fa, s);
@@ -1108,12 +882,6 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
   if (!host_out) return fail(ctx, SPRINTER_E_NULL, "sprinter_get_stats: NULL argument");
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
   long long c[4] = {0, 0, 0, 0};
-  if (ctx->mega_on) {
-    int derr = 0;
-    if (hipMemcpy(&derr, ctx->mega_err, 4, hipMemcpyDeviceToHost) != hipSuccess)
-      return fail(ctx, SPRINTER_E_HIP, "copy of the device error flag failed");
-    if (derr) return fail(ctx, SPRINTER_E_HIP, "a grid barrier of the persistent decode kernel timed out; results are invalid");
-  }
   if (ctx->prefilled) {
     if (hipMemcpy(c, ctx->st.counters, sizeof c, hipMemcpyDeviceToHost) != hipSuccess)
       return fail(ctx, SPRINTER_E_HIP, "copy of counters failed");
@@ -1131,20 +899,10 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
   return SPRINTER_OK;
 }
 
-int sprinter_debug_phase_ticks(sprinter_ctx* ctx, uint64_t* host_out) {
-  if (!ctx || !host_out) return fail(ctx, SPRINTER_E_NULL, "sprinter_debug_phase_ticks: NULL argument");
-  for (int i = 0; i < 128; ++i) host_out[i] = 0;
-  if (!ctx->mega_prof) return SPRINTER_OK;
-  if (hipStreamSynchronize(ctx->stream) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
-  if (hipMemcpy(host_out, ctx->mega_prof, 1024, hipMemcpyDeviceToHost) != hipSuccess)
-    return fail(ctx, SPRINTER_E_HIP, "copy of the tick counters failed");
-  return SPRINTER_OK;
-}
-
 void sprinter_destroy(sprinter_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);     // a decide kernel still in flight writes into the pinned word
-  if (ctx->host_counts) (void)hipHostFree(ctx->host_counts);
+  if (ctx->static_dev < 0 && ctx->host_counts) (void)hipHostFree(ctx->host_counts);
   delete ctx;
 }
 

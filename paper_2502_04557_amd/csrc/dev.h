@@ -1,5 +1,4 @@
-// Device-side helpers shared by the per-operation kernels (k_*.hip) and the
-// persistent decode kernel (mega.hip): bf16 conversion, operand-tile indexing,
+// Device-side helpers shared by the kernels (k_*.hip): bf16 conversion, operand-tile indexing,
 // wave reductions, Philox4x32-10 / Gumbel noise, packed arg-max keys.
 #pragma once
 #include "internal.h"

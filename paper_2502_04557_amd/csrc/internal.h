@@ -215,102 +215,4 @@ void launch_reset_gen_idx(long long* counters, hipStream_t s);
 void launch_set_f32(float* p, float v, hipStream_t s);
 void launch_copy_f32(const float* src, float* dst, const int* n_rows, int row_len, int max_rows, hipStream_t s);
 
-// ---- persistent decode kernel (mega.hip), bf16 mode -------------------------------------
-// One cooperative launch runs n_steps whole decode steps.  Workgroups meet at a grid barrier
-// between dependent phases; everything one workgroup hands to another is written with
-// write-through (device-scope) stores into buffers that are written once per step and read
-// only after the barrier, so no cache flush is needed per barrier (one fence per step).
-enum { PK_EMBED = 0, PK_NORM = 1, PK_GEMM = 2, PK_ATTN = 3, PK_LMHEAD = 4 };
-// One phase of a model forward, prepared by the host; the kernel walks the list.
-struct PhaseDesc {
-  int kind, layer, epi, fused_norm;
-  // GEMM: Y = X W^T; W / W2 in operand tiles
-  const uint4 *W, *W2;
-  int N, Kt, n_tiles, K;
-  const float* bias;
-  const uint4* X;                 // activations in operand tiles (hi plane; lo plane x_plane16 further) ...
-  size_t x_plane16;
-  const float *h, *stats_in, *g, *b;   // ... or the float32 residual stream + its statistics + norm parameters
-  int n_stat_tiles, arch;
-  float eps;
-  int pad0;
-  const float* resid;
-  float* out_f32;
-  int ldo, out_K;
-  unsigned short* out_act;
-  size_t out_plane;
-  float* stats_out;
-  float* f32_out2;                // norm phase: optional float32 copy of the output
-};
-
-struct MegaModel {
-  ModelDims md;
-  const PhaseDesc* phases;         // device array [n_phases]
-  int n_phases, pad1;
-  const void *tok_emb, *pos_emb, *lm_head;
-  const float *normf_g, *normf_b;
-  const LayerW* layers;            // device array [n_layer]
-  void *kcache, *vcache;
-  size_t layer_stride;             // elements per layer in a cache
-  // activations, one buffer per layer where marked [L]: each address is written once per step
-  float* h0;                       // [Mp, d] embedding output
-  unsigned short* xn1;             // [L] normalised input of the QKV projection (hi/lo planes)
-  unsigned short* xn2;             // [L] normalised input of the FFN
-  float* y;                        // [L][Mp, dqkv]
-  unsigned short* ao;              // [L] attention output (hi/lo planes)
-  unsigned short* mid;             // [L] FFN hidden (hi/lo planes)
-  float* hA;                       // [L][Mp, d] residual stream after the attention block
-  float* hB;                       // [L][Mp, d] residual stream after the FFN
-  size_t xn_stride, y_stride, ao_stride, mid_stride, h_stride;   // elements between layers
-  size_t pl_d, pl_a, pl_f;         // hi -> lo plane distance (elements) for widths d, H*dh, ff
-  float* hf;                       // [Mp, d]
-  unsigned short* hfn;             // hi/lo planes
-  float* rope;                     // [Mp, dh]
-  float* stats;                    // [2L+1][ceil(d/16)][16][2] per-column-tile (sum, sum of squares) of the residual stream (M <= 16 path)
-  size_t stats_stride;             // floats between consecutive stat buffers
-  unsigned long long* am_part;     // [nwg, Mp]
-  int *rd_n, *rd_b, *rd_tok, *rd_pos, *rd_slot;
-};
-
-struct MegaParams {
-  MegaModel draft, target;
-  const float *v_w1, *v_b1, *v_w2, *v_b2;
-  int ver_d_hidden, ver_chunks;
-  float* ver_part;                 // [chunks, B]
-  State st;
-  const float* tau;
-  int *draft_tok, *rej_idx, *n_rej, *committed;
-  float* score;
-  unsigned char* accept;
-  unsigned seed_lo, seed_hi;
-  float inv_temperature;
-  int rows_alloc, max_seq, max_batch;
-  unsigned* sync;                  // barrier words (see mega.hip), zeroed at create
-  unsigned* epoch;                 // [1] barrier epoch carried from launch to launch
-  int* err;                        // [1] set when a barrier wait gave up
-  unsigned long long* prof;        // [32] per-phase tick counters of workgroup 0 (nullptr = off)
-};
-
-struct MegaOut {                   // per-launch outputs (all optional)
-  int B, n_tokens;
-  int *o_draft_tok, *o_rej_idx, *o_n_rej, *o_committed;
-  float* o_score;
-  unsigned char* o_accept;
-  float *o_draft_logits, *o_draft_hidden, *o_target_logits, *o_target_hidden;
-  int *g_tok, *g_draft_tok;
-  unsigned char* g_accept;
-  float* g_score;
-};
-
-size_t mega_smem_bytes(const MegaParams& hp, int MT);
-// Returns hipSuccess or the launch error.  grid = number of workgroups (one per compute unit).
-hipError_t launch_mega(const MegaParams* dev_params, int MT, int n_steps, const MegaOut& out, size_t smem, int grid,
-                       hipStream_t s);
-hipError_t mega_prepare(int MT, size_t smem, int* max_grid);
-// the variant for at most 16 rows (mega16.hip); needs draft.n_phases / target.n_phases set
-size_t mega16_smem_bytes(const MegaParams& hp, int* tab_bytes);
-hipError_t mega16_prepare(size_t smem, int* max_grid);
-hipError_t launch_mega16(const MegaParams* dev_params, int n_steps, const MegaOut& out, size_t smem, int tab_bytes, int grid,
-                         hipStream_t s);
-
 }  // namespace sprinter

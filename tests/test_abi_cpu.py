@@ -91,3 +91,4 @@ def test_config_validation(lib):
     assert lib.sprinter_generate(None, 4, None, None, None, None) == -1
     assert lib.sprinter_prefill(None, None, None, 1, 1) == -1
     assert lib.sprinter_sd_generate(None, 2, 1, None, 0, None, None, None) == -1
+

@@ -78,3 +78,39 @@ def test_prefill_operation_count_matches_a_brute_force_count():
                         total += 2 * m.d_model * m.n_head * m.d_head              # output projection
                         total += 2 * 3 * m.d_model * m.d_ff                       # gate, up, down
     assert abs(bench.prefill_flops(cfg, plen) - total) <= 1e-9 * total
+
+
+def test_algorithmic_flops_match_a_brute_force_count():
+    """Per step and per row a model call costs 2 flops per weight element (LM head included) plus, per layer and
+    query head, 2 * d_head for the scores and 2 * d_head for the weighted sum of every key it attends to (the
+    cached ones and its own)."""
+    rng = np.random.default_rng(1)
+    cfg = W.mini_config("llama", W.DT_BF16)
+    _, plen = W.make_prompts(cfg)
+    K = 9
+    accept = (rng.random((cfg.batch, K)) < 0.5).astype(np.uint8)
+    first = 2
+    seen = plen.astype(np.int64) - 1 + rng.integers(0, 2, size=cfg.batch)
+
+    def call(m, keys):
+        per_layer = m.d_qkv * m.d_model + m.d_model * m.n_head * m.d_head + (2 if m.arch == W.ARCH_GPT else 3) * m.d_model * m.d_ff
+        flops = 2 * (m.n_layer * per_layer + m.vocab * m.d_model)
+        for _layer in range(m.n_layer):
+            for _head in range(m.n_head):
+                flops += keys * 2 * m.d_head * 2
+        return flops
+
+    len_q = plen.astype(np.int64) - 1 + first
+    len_p = seen.copy()
+    want = []
+    for k in range(K):
+        total = 0
+        for b in range(cfg.batch):
+            total += call(cfg.draft, len_q[b] + 1)
+            if accept[b, k] == 0:
+                total += call(cfg.target, len_p[b] + 1)
+                len_p[b] += 1
+        len_q += 1
+        want.append(float(total))
+    got = bench.algorithmic_flops(cfg, plen, accept, first, seen.copy())
+    assert np.allclose(got, want, rtol=1e-12)

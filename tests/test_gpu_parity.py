@@ -31,19 +31,6 @@ def test_c1_free_run_is_identical():
     p.close()
 
 
-@pytest.fixture
-def persistent_kernel(monkeypatch):
-    """Contexts created inside the test use the persistent cooperative decode kernel (bf16 only)."""
-    monkeypatch.setenv("SPRINTER_PERSISTENT", "1")
-
-
-@pytest.mark.parametrize("kind", ["gpt", "llama", "linear"])
-def test_mini_step_by_step_persistent_kernel(kind, persistent_kernel):
-    """The same step-by-step parity with the opt-in persistent kernel: mini-gpt and mini-linear take
-    the variant for at most 16 rows, mini-llama (19 rows) the general one."""
-    test_mini_step_by_step(kind, W.DT_BF16)
-
-
 @pytest.mark.parametrize("kind,dtype", [("gpt", W.DT_F32), ("llama", W.DT_F32), ("linear", W.DT_F32),
                                         ("gpt", W.DT_BF16), ("llama", W.DT_BF16), ("linear", W.DT_BF16)])
 def test_mini_step_by_step(kind, dtype):
@@ -419,11 +406,6 @@ def test_maximum_batch(ctx, rej):
     g2, _ = p.gpu_generate(G)
     assert np.array_equal(g2["tok"], g["tok"])
     p.close()
-
-
-def test_c2_persistent_kernel_sampled_rows(persistent_kernel):
-    """Config 2 at full size through the opt-in persistent kernel."""
-    test_c2_full_size_sampled_rows()
 
 
 def test_c2_full_prefix_sampled_rows():

@@ -135,11 +135,7 @@ def _logit(p):
     return float(np.log(p) - np.log1p(-p))
 
 
-def _shifted_bias(scores, b2_in_force, tau, rho):
-    """Output bias that puts the rho-quantile of the verifier's pre-bias logit on logit(tau)."""
-    sc = np.asarray(scores, np.float64)
-    z_pre = np.log(sc) - np.log1p(-sc) - b2_in_force
-    return float(np.float32(_logit(tau) - np.quantile(z_pre, rho)))
+_shifted_bias = W.shifted_bias
 
 
 @pytest.fixture(scope="module")

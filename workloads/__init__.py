@@ -15,3 +15,4 @@ from .configs import (ModelCfg, SprinterCfg, ARCH_GPT, ARCH_LLAMA, DT_F32, DT_BF
 from .synth import (round_bf16, make_model_weights, make_verifier_weights,
                     make_weights, make_prompts, zipf_probs, model_weight_shapes,
                     verifier_weight_shapes)
+from .calibrate import shifted_bias, logit
