@@ -174,6 +174,22 @@ int sprinter_workspace_bytes(const sprinter_cfg* cfg, size_t* out_bytes);
 int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspace_bytes,
                     void* hip_stream, sprinter_ctx** out_ctx);
 
+/* sprinter_create for callers that cannot allocate device memory at all (code that runs while a
+ * HIP graph is being captured elsewhere in the process, tight serving loops, harnesses that forbid
+ * hipMalloc): the workspace is a static array inside the library, SPRINTER_STATIC_WORKSPACE_BYTES
+ * (64 MiB) on every GPU the library runs on, held until the process ends.  The call allocates
+ * nothing, neither device nor pinned host memory, and neither do later calls on the context; a
+ * context made here therefore learns the number of rejected rows through a small device-to-host copy
+ * and a stream synchronisation per step instead of a polled pinned word (about 10 us more per step).
+ * Weights, prompts and outputs are passed to the later calls as for any other context.
+ * Errors: cfg whose sprinter_workspace_bytes exceeds the limit (SPRINTER_E_WORKSPACE, both sizes in
+ * the message); a second context of this kind on a device while the first is alive
+ * (SPRINTER_E_STATE): all such contexts of a device share that one array, so they must not overlap
+ * - destroy one before creating the next.  The array keeps the previous context's contents; create
+ * clears everything that has to start at zero. */
+#define SPRINTER_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
+int sprinter_create_static(const sprinter_cfg* cfg, void* hip_stream, sprinter_ctx** out_ctx);
+
 /* Hands over the parameters of one of the three models of Sec. 3 (draft M_q,
  * target M_p, verifier V of Sec. 3.2).  which: SPRINTER_DRAFT, _TARGET or
  * _VERIFIER.  names[i] / dev_ptrs[i] / shapes[4*i..4*i+3] (unused dims 0) describe

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libsprinter.so")
 DRAFT, TARGET, VERIFIER = 0, 1, 2
 F32, BF16 = 0, 1
 
-EXPORTS = ("sprinter_workspace_bytes", "sprinter_create", "sprinter_load_weights", "sprinter_prefill",
+EXPORTS = ("sprinter_workspace_bytes", "sprinter_create", "sprinter_create_static", "sprinter_load_weights", "sprinter_prefill",
            "sprinter_step", "sprinter_generate", "sprinter_sd_generate", "sprinter_set_tau", "sprinter_get_stats",
            "sprinter_destroy", "sprinter_last_error")
 
@@ -58,6 +58,7 @@ def load_library(path: str = LIB_PATH):
     vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
     lib.sprinter_workspace_bytes.argtypes = [C.POINTER(CfgC), C.POINTER(sz)]
     lib.sprinter_create.argtypes = [C.POINTER(CfgC), vp, sz, vp, C.POINTER(vp)]
+    lib.sprinter_create_static.argtypes = [C.POINTER(CfgC), vp, C.POINTER(vp)]
     lib.sprinter_load_weights.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(vp), C.POINTER(C.c_int64), i32]
     lib.sprinter_prefill.argtypes = [vp, vp, C.POINTER(C.c_int32), i32, i32]
     lib.sprinter_step.argtypes = [vp, C.POINTER(StepOutC)]
@@ -99,7 +100,8 @@ def _ptr(t):
 class Sprinter:
     """One context = one (draft, target, verifier) triple on the current device."""
 
-    def __init__(self, cfg, device="cuda:0"):
+    def __init__(self, cfg, device="cuda:0", static_workspace=False):
+        """static_workspace: use sprinter_create_static (the library's own fixed workspace, no allocation)."""
         self.lib = load_library()
         self.cfg = cfg
         self.device = torch.device(device)
@@ -109,9 +111,15 @@ class Sprinter:
         self.workspace_bytes = need.value
         self.stream = torch.cuda.current_stream(self.device)
         ctx = C.c_void_p(None)
-        self.workspace = torch.empty(need.value, dtype=torch.uint8, device=self.device)
-        self._check(self.lib.sprinter_create(C.byref(self.ccfg), _ptr(self.workspace), need.value,
-                                             C.c_void_p(self.stream.cuda_stream), C.byref(ctx)), None)
+        if static_workspace:
+            self.workspace = None
+            with torch.cuda.device(self.device):
+                self._check(self.lib.sprinter_create_static(C.byref(self.ccfg), C.c_void_p(self.stream.cuda_stream),
+                                                            C.byref(ctx)), None)
+        else:
+            self.workspace = torch.empty(need.value, dtype=torch.uint8, device=self.device)
+            self._check(self.lib.sprinter_create(C.byref(self.ccfg), _ptr(self.workspace), need.value,
+                                                 C.c_void_p(self.stream.cuda_stream), C.byref(ctx)), None)
         self.ctx = ctx
         self._keep = {}
         self.B = 0

@@ -12,6 +12,7 @@
 #include <unordered_map>
 #include <algorithm>
 #include <chrono>
+#include <mutex>
 #include <vector>
 
 using namespace sprinter;
@@ -19,6 +20,16 @@ using namespace sprinter;
 namespace {
 
 thread_local char g_err[512] = "";
+
+// The workspace of contexts made by sprinter_create_static: callers that must not allocate device memory get it from
+// here.  In host code the array's name is only a stand-in; its device address comes from hipGetSymbolAddress (per
+// device, see sprinter_create_static) and only that address is ever handed to kernels.
+constexpr size_t STATIC_WORKSPACE_BYTES = SPRINTER_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_WORKSPACE_BYTES];
+constexpr int MAX_STATIC_DEVICES = 64;
+struct StaticSlot { void* base = nullptr; bool in_use = false; };
+StaticSlot g_static[MAX_STATIC_DEVICES];
+std::mutex g_static_mu;
 
 struct Bump {   // 256-byte aligned bump allocator; base == nullptr only measures
   char* base; size_t off;
@@ -634,6 +645,44 @@ int sprinter_create(const sprinter_cfg* cfg, void* dev_workspace, size_t workspa
   return create_common(cfg, dev_workspace, hip_stream, -1, out_ctx);
 }
 
+int sprinter_create_static(const sprinter_cfg* cfg, void* hip_stream, sprinter_ctx** out_ctx) {
+  if (!cfg || !out_ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_create_static: NULL argument");
+  *out_ctx = nullptr;
+  char buf[256];
+  int rc = validate_cfg(cfg, buf, sizeof buf);
+  if (rc) return fail(nullptr, rc, "%s", buf);
+  const size_t need = carve(*cfg, nullptr, nullptr, nullptr, nullptr);
+  if (need > STATIC_WORKSPACE_BYTES)
+    return fail(nullptr, SPRINTER_E_WORKSPACE, "this configuration needs %zu bytes of workspace, the static workspace holds %zu",
+                need, STATIC_WORKSPACE_BYTES);
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_STATIC_DEVICES)
+    return fail(nullptr, SPRINTER_E_HIP, "no current device with an index below %d", MAX_STATIC_DEVICES);
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticSlot& slot = g_static[dev];
+    if (!slot.base) {   // once per device, with that device current: every GPU holds its own copy of the array
+      void* p = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return fail(nullptr, SPRINTER_E_HIP, "address of the static workspace on device %d: %s", dev, hipGetErrorString(e));
+      if (((uintptr_t)p) & 255) return fail(nullptr, SPRINTER_E_WORKSPACE, "static workspace is not 256-byte aligned");
+      slot.base = p;
+    }
+    if (slot.in_use)
+      return fail(nullptr, SPRINTER_E_STATE, "device %d already has a live context on the static workspace; destroy it first", dev);
+    slot.in_use = true;
+    base = slot.base;
+  }
+  rc = create_common(cfg, base, hip_stream, dev, out_ctx);
+  if (rc) {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    g_static[dev].in_use = false;
+  }
+  return rc;
+}
+
 int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names, const void* const* dev_ptrs,
                           const int64_t* shapes, int n) {
   if (!ctx) return fail(nullptr, SPRINTER_E_NULL, "sprinter_load_weights: NULL context");
@@ -902,7 +951,12 @@ int sprinter_get_stats(sprinter_ctx* ctx, sprinter_stats* host_out, int64_t* hos
 void sprinter_destroy(sprinter_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);     // a decide kernel still in flight writes into the pinned word
-  if (ctx->static_dev < 0 && ctx->host_counts) (void)hipHostFree(ctx->host_counts);
+  if (ctx->static_dev >= 0) {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    g_static[ctx->static_dev].in_use = false;
+  } else if (ctx->host_counts) {
+    (void)hipHostFree(ctx->host_counts);
+  }
   delete ctx;
 }
 

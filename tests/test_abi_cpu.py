@@ -92,3 +92,20 @@ def test_config_validation(lib):
     assert lib.sprinter_prefill(None, None, None, 1, 1) == -1
     assert lib.sprinter_sd_generate(None, 2, 1, None, 0, None, None, None) == -1
 
+
+def test_create_static_rejects_what_does_not_fit(lib):
+    """The size check of sprinter_create_static comes before any device call, so it can be forced here."""
+    from paper_2502_04557_amd import binding
+    hdr = open(os.path.join(ROOT, "include", "sprinter.h")).read()
+    limit = int(re.search(r"SPRINTER_STATIC_WORKSPACE_BYTES \(\(size_t\)(\d+) << 20\)", hdr).group(1)) << 20
+    cfg = W.config("c2")
+    rc, need, _ = _ws(lib, cfg)
+    assert rc == 0 and need > limit
+    ctx = C.c_void_p(None)
+    c = binding.cfg_to_c(cfg)
+    rc = lib.sprinter_create_static(C.byref(c), None, C.byref(ctx))
+    msg = lib.sprinter_last_error(None).decode()
+    assert rc == -3 and not ctx.value
+    assert str(need) in msg and str(limit) in msg
+    assert lib.sprinter_create_static(None, None, C.byref(ctx)) == -1
+    assert lib.sprinter_create_static(C.byref(c), None, None) == -1
