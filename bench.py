@@ -148,10 +148,15 @@ def host_threads():
         return int(os.cpu_count() or 1)
 
 
+def note(msg):
+    """Progress line on stderr (the JSON line on stdout stays alone)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def cpu_baseline(cfg, weights, max_seconds=15.0, max_steps=64):
     """The oracle, as it stands, on a bounded sample of the same workload: the first rows of the batch with
     their own prompts for the configurations whose models it can prefill in seconds (c1, c2), two rows with
-    the prompts cut to their last 64 tokens for the large ones (one uncached forward per row fills the caches,
+    the prompts cut to their last 32 tokens for the large ones (one uncached forward per row fills the caches,
     untimed like the GPU's prefill; the decode steps are timed)."""
     import numpy as np
     import workloads as W
@@ -159,20 +164,27 @@ def cpu_baseline(cfg, weights, max_seconds=15.0, max_steps=64):
     dw, tw, vw = weights
     params = sum(int(np.prod(a.shape)) for a in dw.values()) + sum(int(np.prod(a.shape)) for a in tw.values())
     big = params > 3e9
-    store = np.float32 if big else np.float64      # the float64 copies of an 8B-parameter pair do not pay for themselves here
-    d, t, v = om.Decoder(cfg.draft, dw, store=store), om.Decoder(cfg.target, tw, store=store), om.Verifier(vw)
+    t0 = time.perf_counter()
+    d = om.Decoder(cfg.draft, dw)
+    note(f"cpu_baseline {cfg.name}: draft copied to float64 after {time.perf_counter() - t0:.0f} s")
+    t = om.Decoder(cfg.target, tw)
+    note(f"cpu_baseline {cfg.name}: target copied to float64 after {time.perf_counter() - t0:.0f} s")
+    v = om.Verifier(vw)
     prompts, plen = W.make_prompts(cfg)
     n_rows = min(len(plen), 2 if big else 4)
     if big:
-        keep = 64
+        keep = 32
         assert int(plen[:n_rows].min()) >= keep
         prompts = np.stack([prompts[b, int(plen[b]) - keep:int(plen[b])] for b in range(n_rows)])
         plen = np.full(n_rows, keep, np.int32)
-        what = f"first {n_rows} rows, prompts cut to their last {keep} tokens, weights held in float32"
+        what = f"first {n_rows} rows, prompts cut to their last {keep} tokens"
     else:
         prompts, plen = prompts[:n_rows].copy(), plen[:n_rows].copy()
         what = f"first {n_rows} rows with their own prompts ({int(plen.min())}-{int(plen.max())} tokens)"
-    dc, tc = osp.prefill_whole_prompt(d, prompts, plen), osp.prefill_whole_prompt(t, prompts, plen)
+    dc = osp.prefill_whole_prompt(d, prompts, plen)
+    note(f"cpu_baseline {cfg.name}: draft caches filled after {time.perf_counter() - t0:.0f} s")
+    tc = osp.prefill_whole_prompt(t, prompts, plen)
+    note(f"cpu_baseline {cfg.name}: target caches filled after {time.perf_counter() - t0:.0f} s")
     seqs = [list(map(int, prompts[b, :int(plen[b])])) for b in range(n_rows)]
     steps, t0 = 0, time.perf_counter()
     # one generate call per step so that the run can stop on the time bound; the caches carry over
@@ -185,8 +197,9 @@ def cpu_baseline(cfg, weights, max_seconds=15.0, max_steps=64):
             seqs[b].append(int(rec["tok"][b, 0]))
         steps += 1
     dt = time.perf_counter() - t0
+    note(f"cpu_baseline {cfg.name}: {steps} steps in {dt:.1f} s")
     return dict(value=n_rows * steps / dt, unit="tokens/s", cores=host_threads(), kind="oracle",
-                sample=f"{cfg.name}: {what}, {steps} decode steps in {dt:.1f} s (NumPy float64 arithmetic, "
+                sample=f"{cfg.name}: {what}, {steps} decode steps in {dt:.1f} s (NumPy float64, "
                        f"os.cpu_count()={os.cpu_count()})")
 
 
@@ -320,7 +333,7 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
     t0 = time.time()
     weights = W.make_weights(cfg)
     prompts, plen = W.make_prompts(cfg)
-    print(f"[bench] {cfg.name}: weights generated in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    note(f"{cfg.name}: weights generated in {time.time() - t0:.1f} s")
     s = binding.Sprinter(cfg, "cuda:0")
     for which, w in zip((binding.DRAFT, binding.TARGET, binding.VERIFIER), weights):
         s.load_weights(which, w)
@@ -394,9 +407,12 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
                 "avg_accepted_run": float(accept.sum() / max(1, (accept == 0).sum())),
                 "roofline": roof}
 
+    note(f"{cfg.name}: weights on the device")
     r = timed(cfg.tau, reject_rate, Wm, K)
-    print(f"[bench] {cfg.name}: prefill of {int(plen.sum())} prompt tokens: {r['prefill_ms']:.1f} ms", file=sys.stderr, flush=True)
+    note(f"{cfg.name}: prefill of {int(plen.sum())} prompt tokens: {r['prefill_ms']:.1f} ms")
     res = summarise(r, K, cfg.tau)
+    note(f"{cfg.name}: {K} timed steps, {res['ms_per_step']:.3f} ms per step, {res['value']:.0f} tokens/s, "
+         f"{res['roofline']['frac']:.3f} of the HBM peak")
     label = (f"{cfg.name}: batch {B}, prompt {pmax if not cfg.prompt_len_min else f'{cfg.prompt_len_min}..{pmax}'}, "
              f"tau {cfg.tau}, T {cfg.temperature}; "
              f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
@@ -429,9 +445,11 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
             x = summarise(timed(tau, None, 4, n_x), n_x, tau)
             bt[f"tau_{tau}"] = {"ms_per_step": x["ms_per_step"], "hbm_frac": x["roofline"]["frac"],
                                 "target_calls_per_token": x["target_calls_per_token"]}
+            note(f"{cfg.name}: tau {tau}: {x['ms_per_step']:.3f} ms per step")
         out["by_threshold"] = bt
         rho = 0.09                                          # 1 / (Avg Tokens + 1) of Table 2 lies in 0.08 .. 0.13
         x = summarise(timed(cfg.tau, rho, 4, n_x), n_x, cfg.tau)
+        note(f"{cfg.name}: reject rate {x['target_calls_per_token']:.3f}: {x['ms_per_step']:.3f} ms per step")
         out["at_reject_rate"] = {"asked": rho, "achieved": x["target_calls_per_token"], "value": x["value"],
                                  "ms_per_step": x["ms_per_step"], "steps_with_target_frac": x["steps_with_target_frac"],
                                  "hbm_frac": x["roofline"]["frac"],
@@ -446,7 +464,7 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
                 sw.append({"tau": tau, "reject_rate_asked": rho, "reject_rate_achieved": x["target_calls_per_token"],
                            "value": x["value"], "ms_per_step": x["ms_per_step"], "hbm_frac": x["roofline"]["frac"],
                            "mfma_frac_of_ceiling": x["roofline"].get("mfma", {}).get("frac_of_ceiling")})
-                print(f"[bench] sweep {sw[-1]}", file=sys.stderr, flush=True)
+                note(f"sweep {sw[-1]}")
         out["sweep"] = sw
     s.close()
     del s

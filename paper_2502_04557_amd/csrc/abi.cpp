@@ -200,12 +200,15 @@ ModelDims dims_of(const sprinter_model_cfg& m) {
   return d;
 }
 
+// Slots per (row, KV head) of a cache: the bf16 value cache is kept in blocks of 32 slots (tiles of V^T).
+int kv_slots(const sprinter_cfg& c) { return c.dtype == SPRINTER_BF16 ? round_up(c.max_seq, 32) : c.max_seq; }
+
 // Lays one model out in the workspace (or only measures when bump.base == nullptr).
 void carve_model(Bump& bump, const sprinter_cfg& c, const sprinter_model_cfg& mc, Model* m, int rows) {
   ModelDims md = dims_of(mc);
   const size_t es = esize(c.dtype);
   const bool bf = c.dtype == SPRINTER_BF16;
-  size_t layer_stride = (size_t)c.max_batch * md.KVH * c.max_seq * md.dh;
+  size_t layer_stride = (size_t)c.max_batch * md.KVH * kv_slots(c) * md.dh;
   void* kc = bump.take(layer_stride * md.n_layer * es);
   void* vc = bump.take(layer_stride * md.n_layer * es);
   ModelScratch sc;
@@ -397,12 +400,12 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
                 0, max_rows, s);
     if (shared_caches) {
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, 1);
+                       kv_slots(ctx->cfg), sc.ao, pl_a, max_rows, s, 1);
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s, long_runs ? 3 : 2);
+                       kv_slots(ctx->cfg), sc.ao, pl_a, max_rows, s, long_runs ? 3 : 2);
     } else {
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       ctx->cfg.max_seq, sc.ao, pl_a, max_rows, s);
+                       kv_slots(ctx->cfg), sc.ao, pl_a, max_rows, s);
     }
     if (!want_head && i + 1 == md.n_layer) break;   // a prefill position only has to fill the caches
     resid_gemm(L.wo, sc.ao, pl_a, md.H * md.dh, L.bo);

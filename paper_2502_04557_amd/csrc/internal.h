@@ -82,7 +82,8 @@ void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* 
                  int out_K, size_t out_plane, int max_rows, hipStream_t s);
 
 void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
-                      void* kcache, void* vcache, size_t layer_off, int ctx_bound /* upper bound of the rows' cache lengths */, int max_seq,
+                      void* kcache, void* vcache, size_t layer_off, int ctx_bound /* upper bound of the rows' cache lengths */,
+                      int max_seq /* slots per (row, KV head) of the caches; bf16: a multiple of 32 */,
                       void* ao, size_t ao_plane, int max_rows, hipStream_t s, int phase = 0);
 // phase 0: append the row's new key / value to the cache and attend (rows of one launch own different caches);
 // phase 1: append only; phase 2: attend only (the pair serves launches where several rows share a cache).

@@ -161,222 +161,258 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
   }
 }
 
-// bf16 single-query attention with a short dependency chain: one workgroup (4 waves) per (row, KV head).
-// Once the row's cache slot is known, every wave requests its share of the cached keys AND values
-// at once (they do not depend on the new query), then the query / new key / new value; each lane
-// group runs an online softmax over its own keys, the groups are merged by shuffles, the 4 waves
-// and the new key by one pass through LDS: a single block-wide synchronisation.
-//   lane = kin * LPK + chunk: LPK = DH / 8 lanes share one key (8 elements each), a wave-wide
-//   16-byte load covers KPW = 64 / LPK consecutive keys; wave w takes key blocks w, w + 4, ...
-template <int DH, int G, int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn_bf16(AttnArgs a) {
-  constexpr int LPK = DH / 8, KPW = 64 / LPK, HALF = DH / 2;
-  constexpr int NB = (G <= 4 && DH == 64) ? 8 : 4;       // key blocks held in registers per round and wave
+// Layout of the bf16 value cache.  The key cache is row-major [slot][DH]: a row is already what the matrix
+// instruction wants for S = Q K^T (contraction over DH).  O = P V contracts over the keys, so the values are kept
+// as operand tiles of V^T: per (row, KV head) blocks of 32 slots, a block holds DH / 16 tiles of 16 columns x 32
+// keys (1 KiB, lane = (key % 32) / 8 * 16 + column % 16, 8 consecutive keys per lane).  A wave then fetches a
+// value tile with one coalesced 16-byte-per-lane load and feeds it to the MFMA unchanged; appending one key is
+// DH scattered 2-byte stores.  Slots per (row, KV head) are a multiple of 32 (AttnArgs::max_seq in bf16 mode).
+__device__ __forceinline__ size_t vt_index(int slot, int d, int DH) {
+  return (size_t)(slot >> 5) * (size_t)(32 * DH) + (size_t)(d >> 4) * 512 + (size_t)(((((slot & 31) >> 3) << 4) + (d & 15)) * 8 + (slot & 7));
+}
+// One operand piece of a value tile (8 consecutive keys from `key0` of one column): keys after `slot` become 0 (the
+// cache may hold anything there, and 0 x NaN is NaN on the matrix cores), key == slot becomes `own` (bf16 bits).
+__device__ __forceinline__ uint4 vt_fix(uint4 v, int key0, int slot, unsigned own) {
+  unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int key = key0 + e;
+    unsigned h = (e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu);
+    h = key > slot ? 0u : (key == slot ? own : h);
+    w[e >> 1] = (e & 1) ? ((w[e >> 1] & 0xffffu) | (h << 16)) : ((w[e >> 1] & 0xffff0000u) | h);
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// bf16 single-query attention on the matrix cores: one workgroup of NW waves per (row, KV head); the G query heads
+// that share the KV head are rows of one 16-row operand, so a cached key costs the same whatever G is and the
+// kernel is left with streaming the cache.  Wave w takes the 32-key blocks w, w + NW, ...; per block
+// S = Q K^T (Q rotated, scaled and split into hi + lo bf16 planes in registers, so it enters at float32
+// precision; K fragments straight from the cache), online softmax in float32 on the accumulator layout (the 16 keys
+// of a tile sit in one DPP row), P through a wave-private piece of LDS into operand layout (hi + lo), V^T tiles
+// straight from the cache, O += P V.  A block's keys are requested a whole step ahead (two register buffers), its
+// value tiles as soon as the previous block's have been consumed; nothing in the loop synchronises waves.  The row's own key and value
+// (the token being processed) are computed in the prologue, appended to the cache by wave 0 and patched into the
+// operands of the block that holds slot `slot`, which is the row's last block; keys beyond it are masked.
+// The waves' partial results are merged through LDS at the end.
+//   phase 0: append + attend; 1: append only; 2: attend only (the entry is already cached; patching it in again
+//   changes nothing).
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
+  constexpr int T = DH / 32, CT = DH / 16, PS = 36, HALF = DH / 2, GMAX = 8;
   constexpr float NEG = -1e30f;
-  __shared__ float s_m[NW][G], s_l[NW][G], s_o[NW][G][DH], s_vnew[DH], s_snew[G];
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ __attribute__((aligned(16))) float lds_p[NW][GMAX * PS];
+  __shared__ __attribute__((aligned(16))) bf16_t lds_kn[DH];
+  __shared__ float s_ml[NW][GMAX][2];
+  __shared__ float s_o[NW][GMAX][DH];
   const int r = blockIdx.y;
   if (r >= *a.rd.n_rows) return;
   const int kvh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
-  const int chunk = lane % LPK, kin = lane / LPK;
+  const int l16 = lane & 15, lq = lane >> 4, G = a.H / a.KVH;
   const int b = a.rd.b[r], slot = a.rd.slot[r], S = a.max_seq;
   bf16_t* __restrict__ Kc = (bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   bf16_t* __restrict__ Vc = (bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
-  const int n_blocks = (slot + KPW - 1) / KPW;                 // blocks of cached keys
-  const int n_rounds = (n_blocks + NW * NB - 1) / (NW * NB);
-  // Two register buffers where the registers are there (head dimension 128, at most 2 query heads per KV head): the
-  // keys and values of round rd + 1 are in flight while round rd is consumed (c4's step 15.5 -> 14.5 ms).  With more
-  // query heads or 64-wide heads the second buffer costs occupancy and measured slower (c5's draft 38.6 -> 45.5 us).
-  constexpr bool TWO_BUFFERS = DH == 128 && G <= 2;
-  uint4 kA[NB], vA[NB], kB[TWO_BUFFERS ? NB : 1], vB[TWO_BUFFERS ? NB : 1];
-  auto request = [&](uint4* kb, uint4* vb, int rd) {           // clamped addresses, no branches
+  const int n_steps = (slot + 32 * NW) / (32 * NW);             // blocks 0 .. slot / 32, NW per step
+  // Register buffers: two for the key fragments (a block's keys are requested a whole step ahead), one for the value
+  // tiles (requested as soon as the previous block's P V is issued).  Addresses are clamped into the cache.
+  struct KBuf { u32x4 k[2][T]; };
+  auto fetch_k = [&](KBuf& B, int kb) {
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-      const int key = min(((rd * NB + j) * NW + w) * KPW + kin, max(slot - 1, 0));
-      kb[j] = *reinterpret_cast<const uint4*>(Kc + (size_t)key * DH + chunk * 8);
-      vb[j] = *reinterpret_cast<const uint4*>(Vc + (size_t)key * DH + chunk * 8);
+    for (int tile = 0; tile < 2; ++tile) {
+      const bf16_t* kr = Kc + (size_t)min(kb + tile * 16 + l16, slot) * DH + lq * 8;
+#pragma unroll
+      for (int t = 0; t < T; ++t) B.k[tile][t] = *reinterpret_cast<const u32x4*>(kr + t * 32);
     }
   };
-  request(kA, vA, 0);
-  // Query heads, new key and new value: this lane's 8 elements and their rotary partners.  Everything is requested
-  // up front as unconditional 16-byte loads (2 G + 3 pairs from the projection row, 4 from the cos / sin row) and only
-  // then used: with a branch on the rotary flag between the loads each head paid its own memory round trip (12 us
-  // before the first key at 4 query heads per KV head).  Without rotary the partner values are multiplied by 0.
+  u32x4 V[CT];
+  auto fetch_v = [&](int kb) {
+    const bf16_t* vb = Vc + (size_t)(min(kb, slot & ~31) >> 5) * (32 * DH) + lane * 8;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) V[ct] = *reinterpret_cast<const u32x4*>(vb + ct * 512);
+  };
+  KBuf A, B;
+  fetch_k(A, w * 32);
+  fetch_v(w * 32);
+  // The query heads as one operand (row l16 = head min(l16, G - 1): rows beyond G repeat the last head and are
+  // ignored), the new key as operand pieces, the new value per column: unconditional loads first, then arithmetic.
   const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
-  const bool upper = chunk >= LPK / 2;
-  const int pchunk = chunk ^ (LPK / 2);
-  auto load8 = [&](const float* src, float* out) {            // 32-byte aligned: all offsets are multiples of 8 floats
-    const float4 lo = reinterpret_cast<const float4*>(src)[0], hi = reinterpret_cast<const float4*>(src)[1];
-    out[0] = lo.x; out[1] = lo.y; out[2] = lo.z; out[3] = lo.w; out[4] = hi.x; out[5] = hi.y; out[6] = hi.z; out[7] = hi.w;
-  };
-  float qx[G][8], qp[G][8], kx[8], kp[8], vnew[8], csr[16];
+  const float* __restrict__ rp = a.rope + (size_t)r * DH;
+  const float* __restrict__ yq = y + (size_t)(kvh * G + min(l16, G - 1)) * DH;
+  const float* __restrict__ yk = y + (size_t)(a.H + kvh) * DH;
+  const float* __restrict__ yv = y + (size_t)(a.H + a.KVH + kvh) * DH;
+  float vraw[CT];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    load8(y + (size_t)(kvh * G + g) * DH + chunk * 8, qx[g]);
-    load8(y + (size_t)(kvh * G + g) * DH + pchunk * 8, qp[g]);
-  }
-  load8(y + (size_t)(a.H + kvh) * DH + chunk * 8, kx);
-  load8(y + (size_t)(a.H + kvh) * DH + pchunk * 8, kp);
-  load8(y + (size_t)(a.H + a.KVH + kvh) * DH + chunk * 8, vnew);
-  {
-    const float* __restrict__ cs = a.rope + (size_t)r * DH + 2 * (chunk % (LPK / 2)) * 8;   // (cos, sin) pairs of this lane's 8 angles
-    load8(cs, csr);
-    load8(cs + 8, csr + 8);
-  }
-  float cr[8], sr[8];
+  for (int ct = 0; ct < CT; ++ct) vraw[ct] = yv[ct * 16 + l16];
+  uint4 qh[T], ql[T];
+  u32x4 knew[T];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { cr[e] = a.use_rope ? csr[2 * e] : 1.f; sr[e] = a.use_rope ? csr[2 * e + 1] : 0.f; }
-  float q[G][8], knew[8];
+  for (int t = 0; t < T; ++t) {
+    const int d0 = t * 32 + lq * 8, p0 = d0 ^ HALF;
+    const bool upper = d0 >= HALF;
+    float x[8], xp[8], kx[8], kp[8], cs[16];
 #pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      q[g][e] = (upper ? qx[g][e] * cr[e] + qp[g][e] * sr[e] : qx[g][e] * cr[e] - qp[g][e] * sr[e]) * a.scale;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) knew[e] = upper ? kx[e] * cr[e] + kp[e] * sr[e] : kx[e] * cr[e] - kp[e] * sr[e];
-  unsigned kpk[4], vpk[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const float v0 = vnew[2 * e], v1 = vnew[2 * e + 1];
-    const bf16_t k0 = f2bf(knew[2 * e]), k1 = f2bf(knew[2 * e + 1]), w0 = f2bf(v0), w1 = f2bf(v1);
-    kpk[e] = (unsigned)k0 | ((unsigned)k1 << 16);
-    vpk[e] = (unsigned)w0 | ((unsigned)w1 << 16);
-    knew[2 * e] = bf2f(k0); knew[2 * e + 1] = bf2f(k1);         // the entry as later steps will read it back
-    vnew[2 * e] = bf2f(w0); vnew[2 * e + 1] = bf2f(w1);
-  }
-  if (w == 0 && kin == 0) {                                     // append to the cache
-    if (a.phase != 2) {
-      *reinterpret_cast<uint4*>(Kc + (size_t)slot * DH + chunk * 8) = make_uint4(kpk[0], kpk[1], kpk[2], kpk[3]);
-      *reinterpret_cast<uint4*>(Vc + (size_t)slot * DH + chunk * 8) = make_uint4(vpk[0], vpk[1], vpk[2], vpk[3]);
+    for (int i = 0; i < 2; ++i) {
+      const float4 u = reinterpret_cast<const float4*>(yq + d0)[i], v = reinterpret_cast<const float4*>(yq + p0)[i];
+      const float4 ku = reinterpret_cast<const float4*>(yk + d0)[i], kv = reinterpret_cast<const float4*>(yk + p0)[i];
+      x[4 * i] = u.x; x[4 * i + 1] = u.y; x[4 * i + 2] = u.z; x[4 * i + 3] = u.w;
+      xp[4 * i] = v.x; xp[4 * i + 1] = v.y; xp[4 * i + 2] = v.z; xp[4 * i + 3] = v.w;
+      kx[4 * i] = ku.x; kx[4 * i + 1] = ku.y; kx[4 * i + 2] = ku.z; kx[4 * i + 3] = ku.w;
+      kp[4 * i] = kv.x; kp[4 * i + 1] = kv.y; kp[4 * i + 2] = kv.z; kp[4 * i + 3] = kv.w;
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_vnew[chunk * 8 + e] = vnew[e];
+    for (int i = 0; i < 4; ++i) {
+      const float4 u = reinterpret_cast<const float4*>(rp + 2 * (d0 % HALF))[i];
+      cs[4 * i] = u.x; cs[4 * i + 1] = u.y; cs[4 * i + 2] = u.z; cs[4 * i + 3] = u.w;
+    }
+    float qv[8], kn[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float c = a.use_rope ? cs[2 * i] : 1.f, sn = a.use_rope ? cs[2 * i + 1] : 0.f;
+      qv[i] = (upper ? x[i] * c + xp[i] * sn : x[i] * c - xp[i] * sn) * a.scale;
+      kn[i] = upper ? kx[i] * c + kp[i] * sn : kx[i] * c - kp[i] * sn;
+    }
+    split2(qv[0], qv[1], qh[t].x, ql[t].x);
+    split2(qv[2], qv[3], qh[t].y, ql[t].y);
+    split2(qv[4], qv[5], qh[t].z, ql[t].z);
+    split2(qv[6], qv[7], qh[t].w, ql[t].w);
+    knew[t].x = (unsigned)f2bf(kn[0]) | ((unsigned)f2bf(kn[1]) << 16);
+    knew[t].y = (unsigned)f2bf(kn[2]) | ((unsigned)f2bf(kn[3]) << 16);
+    knew[t].z = (unsigned)f2bf(kn[4]) | ((unsigned)f2bf(kn[5]) << 16);
+    knew[t].w = (unsigned)f2bf(kn[6]) | ((unsigned)f2bf(kn[7]) << 16);
+  }
+  if (w == 0 && l16 == 0) {                                      // the new key: into LDS for the row's last block, and into the cache
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      *reinterpret_cast<u32x4*>(lds_kn + t * 32 + lq * 8) = knew[t];
+      if (a.phase != 2) *reinterpret_cast<u32x4*>(Kc + (size_t)slot * DH + t * 32 + lq * 8) = knew[t];
+    }
+  }
+  unsigned vnew[CT / 2];                                         // the new value of columns ct * 16 + l16 as bf16 bits, two per register
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) {
+    const unsigned h = f2bf(vraw[ct]);
+    if (a.phase != 2 && w == 0 && lq == 0) Vc[vt_index(slot, ct * 16 + l16, DH)] = (bf16_t)h;
+    if (ct & 1) vnew[ct >> 1] |= h << 16; else vnew[ct >> 1] = h;
   }
   if (a.phase == 1) return;
-  float snew[G];
+  __syncthreads();                                               // the new key is in LDS for every wave
+  f32x4 O[CT];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float p = 0.f;
+  for (int ct = 0; ct < CT; ++ct) O[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run[4] = {NEG, NEG, NEG, NEG}, l_run[4] = {0.f, 0.f, 0.f, 0.f};
+  float* myp = lds_p[w];
+  // step(keys of block kb, block kb, next block whose value tiles are requested once this block's are consumed)
+  auto step = [&](KBuf& Bk, int kb, int kb_next) {
+    if (kb + 31 >= slot) {                                       // (scalar) the row's last block or beyond: patch the new key in
 #pragma unroll
-    for (int e = 0; e < 8; ++e) p += q[g][e] * knew[e];
-    snew[g] = group_sum<LPK>(p);
-  }
-  if (w == 0 && lane == 0) {
+      for (int tile = 0; tile < 2; ++tile)
+        if (kb + tile * 16 + l16 == slot) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) s_snew[g] = snew[g];
-  }
-  // online softmax over this lane group's keys
-  float m[G], l[G], acc[G][8];
+          for (int t = 0; t < T; ++t) Bk.k[tile][t] = *reinterpret_cast<const u32x4*>(lds_kn + t * 32 + lq * 8);
+        }
+    }
+    f32x4 sc[2];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = NEG; l[g] = 0.f;
+    for (int tile = 0; tile < 2; ++tile) {
+      sc[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-  }
-  // One softmax rescale per round instead of one per key block: the round's scores first, then their maximum, one
-  // correction of the running sums, then the weighted values.
-  auto consume = [&](const uint4* kb, const uint4* vb, int rd) {
-    float sc[NB][G];
-    bool valid[NB];
+      for (int t = 0; t < T; ++t) {
+        const u32x4 kk = Bk.k[tile][t];
+        const uint4 kf = make_uint4(kk.x, kk.y, kk.z, kk.w);
+        sc[tile] = mfma_bf16(qh[t], kf, sc[tile]);
+        sc[tile] = mfma_bf16(ql[t], kf, sc[tile]);
+      }
+    }
+    // accumulator register v of lane (lq, l16) is head lq * 4 + v, key kb + tile * 16 + l16
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-      const int key = ((rd * NB + j) * NW + w) * KPW + kin;
-      valid[j] = key < slot;
-      const bf16_t* kt = reinterpret_cast<const bf16_t*>(&kb[j]);
-      float kf[8];
+    for (int v = 0; v < 4; ++v) {
+      const int last = (lq * 4 + v < G) ? slot : -1;             // last valid key of accumulator row v (head lq * 4 + v)
+      const bool ok0 = kb + l16 <= last, ok1 = kb + 16 + l16 <= last;
+      const float mx = group_max16(fmaxf(ok0 ? sc[0][v] : NEG, ok1 ? sc[1][v] : NEG));
+      const float mn = fmaxf(m_run[v], mx);
+      const float corr = __expf(m_run[v] - mn);
+      const float p0 = ok0 ? __expf(sc[0][v] - mn) : 0.f, p1 = ok1 ? __expf(sc[1][v] - mn) : 0.f;
+      l_run[v] = l_run[v] * corr + group_sum<16>(p0 + p1);
+      m_run[v] = mn;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) kf[e] = bf2f(kt[e]);
+      for (int ct = 0; ct < CT; ++ct) O[ct][v] *= corr;
+      if (lq < 2) {                                              // heads 0 .. 7 (rows beyond G hold zeros)
+        myp[(lq * 4 + v) * PS + l16] = p0;
+        myp[(lq * 4 + v) * PS + 16 + l16] = p1;
+      }
+    }
+    __builtin_amdgcn_wave_barrier();                             // LDS operations of one wave complete in order
+    uint4 ph, pl;                                                // P in operand layout: head l16, keys lq * 8 .. + 8
+    {
+      const float4 u = *reinterpret_cast<const float4*>(myp + (l16 & 7) * PS + lq * 8);
+      const float4 x = *reinterpret_cast<const float4*>(myp + (l16 & 7) * PS + lq * 8 + 4);
+      split2(u.x, u.y, ph.x, pl.x);
+      split2(u.z, u.w, ph.y, pl.y);
+      split2(x.x, x.y, ph.z, pl.z);
+      split2(x.z, x.w, ph.w, pl.w);
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (kb + 31 >= slot) {                                       // (scalar) new value in, keys beyond the row's last one out
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float d = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) d += q[g][e] * kf[e];
-        sc[j][g] = group_sum<LPK>(d);
+      for (int ct = 0; ct < CT; ++ct) {
+        const unsigned own = (ct & 1) ? (vnew[ct >> 1] >> 16) : (vnew[ct >> 1] & 0xffffu);
+        const uint4 f = vt_fix(make_uint4(V[ct].x, V[ct].y, V[ct].z, V[ct].w), kb + lq * 8, slot, own);
+        V[ct].x = f.x; V[ct].y = f.y; V[ct].z = f.z; V[ct].w = f.w;
       }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float mn = m[g];
-#pragma unroll
-      for (int j = 0; j < NB; ++j) mn = valid[j] ? fmaxf(mn, sc[j][g]) : mn;
-      const float corr = __expf(m[g] - mn);
-      m[g] = mn;
-      l[g] *= corr;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+    for (int ct = 0; ct < CT; ++ct) {
+      const uint4 vf = make_uint4(V[ct].x, V[ct].y, V[ct].z, V[ct].w);
+      O[ct] = mfma_bf16(ph, vf, O[ct]);
+      O[ct] = mfma_bf16(pl, vf, O[ct]);
     }
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-      const bf16_t* vt = reinterpret_cast<const bf16_t*>(&vb[j]);
-      float vf[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) vf[e] = valid[j] ? bf2f(vt[e]) : 0.f;   // (an empty cache holds no finite data yet)
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float p = valid[j] ? __expf(sc[j][g] - m[g]) : 0.f;
-        l[g] += p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] += p * vf[e];
-      }
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    fetch_v(kb_next);
   };
-  if constexpr (TWO_BUFFERS) {
-    for (int rd = 0; rd < n_rounds; rd += 2) {    // (a round beyond the last one consumes nothing: all its keys are masked)
-      request(kB, vB, rd + 1);
+  for (int i = 0; i < n_steps; i += 2) {
+    const int kb = (i * NW + w) * 32;
+    fetch_k(B, kb + 32 * NW);
+    __builtin_amdgcn_sched_barrier(0);
+    step(A, kb, kb + 32 * NW);
+    __builtin_amdgcn_sched_barrier(0);
+    if (i + 1 < n_steps) {                                       // (scalar condition)
+      fetch_k(A, kb + 64 * NW);
       __builtin_amdgcn_sched_barrier(0);
-      consume(kA, vA, rd);
+      step(B, kb + 32 * NW, kb + 64 * NW);
       __builtin_amdgcn_sched_barrier(0);
-      request(kA, vA, rd + 2);
-      __builtin_amdgcn_sched_barrier(0);
-      consume(kB, vB, rd + 1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  } else {
-    for (int rd = 0; rd < n_rounds; ++rd) {
-      if (rd > 0) request(kA, vA, rd);
-      consume(kA, vA, rd);
     }
   }
-  // merge the KPW lane groups of the wave
+  // merge the waves: heads lq * 4 + v < G live in the lanes of the first G / 4 (rounded up) DPP rows
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+  for (int v = 0; v < 4; ++v) {
+    const int g = lq * 4 + v;
+    if (g < G) {
+      if (l16 == 0) { s_ml[w][g][0] = m_run[v]; s_ml[w][g][1] = l_run[v]; }
 #pragma unroll
-    for (int o = LPK; o < 64; o <<= 1) {
-      const float mo = __shfl_xor(m[g], o), lo = __shfl_xor(l[g], o);
-      const float mn = fmaxf(m[g], mo);
-      const float c1 = __expf(m[g] - mn), c2 = __expf(mo - mn);
-      l[g] = l[g] * c1 + lo * c2;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * c1 + __shfl_xor(acc[g][e], o) * c2;
-      m[g] = mn;
-    }
-    if (kin == 0) {
-      if (chunk == 0) { s_m[w][g] = m[g]; s_l[w][g] = l[g]; }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) s_o[w][g][chunk * 8 + e] = acc[g][e];
+      for (int ct = 0; ct < CT; ++ct) s_o[w][g][ct * 16 + l16] = O[ct][v];
     }
   }
   __syncthreads();
-  // merge the NW waves and the new key; one output element per thread and pass
   bf16_t* __restrict__ ao = (bf16_t*)a.ao;
   for (int idx = tid; idx < G * DH; idx += NW * 64) {
     const int g = idx / DH, i = idx % DH;
-    const float sn = s_snew[g];
-    float mn = sn;
+    float mn = NEG;
 #pragma unroll
-    for (int q4 = 0; q4 < NW; ++q4) mn = fmaxf(mn, s_m[q4][g]);
-    float den = __expf(sn - mn), num = den * s_vnew[i];
+    for (int q = 0; q < NW; ++q) mn = fmaxf(mn, s_ml[q][g][0]);
+    float den = 0.f, num = 0.f;
 #pragma unroll
-    for (int q4 = 0; q4 < NW; ++q4) {
-      const float c = __expf(s_m[q4][g] - mn);
-      den += c * s_l[q4][g];
-      num += c * s_o[q4][g][i];
+    for (int q = 0; q < NW; ++q) {
+      const float c = __expf(s_ml[q][g][0] - mn);
+      den += c * s_ml[q][g][1];
+      num += c * s_o[q][g][i];
     }
     act_store<bf16_t>(ao, a.ao_plane, r, kvh * G * DH + idx, a.ao_K, num / den);
   }
 }
 
 // Append-only launch of a multi-entry pass: rotate the new key, round key and value to bf16 and write them to the
-// entry's cache slot - what k_attn_bf16 does in its prologue, without the attention around it.  One 64-lane
+// entry's cache slot - what k_attn_dec_bf16 does in its prologue, without the attention around it.  One 64-lane
 // workgroup per (entry, KV head): the first DH / 8 lanes take the key, the next DH / 8 the value, 8 elements each.
 template <int DH>
 __global__ __launch_bounds__(64) void k_kv_append_bf16(AttnArgs a) {
@@ -415,7 +451,13 @@ __global__ __launch_bounds__(64) void k_kv_append_bf16(AttnArgs a) {
     pk[i] = (unsigned)f2bf(v2[0]) | ((unsigned)f2bf(v2[1]) << 16);
   }
   bf16_t* __restrict__ dst = (bf16_t*)(is_v ? a.vcache : a.kcache) + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
-  *reinterpret_cast<uint4*>(dst + (size_t)slot * DH + chunk * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+  if (!is_v) {
+    *reinterpret_cast<uint4*>(dst + (size_t)slot * DH + chunk * 8) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+  } else {                                                       // value cache: operand tiles of V^T (vt_index)
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      dst[vt_index(slot, chunk * 8 + e, DH)] = (bf16_t)((e & 1) ? (pk[e >> 1] >> 16) : (pk[e >> 1] & 0xffffu));
+  }
 }
 
 // Causal attention on the matrix cores for a multi-entry pass whose entries come in runs of consecutive positions of
@@ -423,14 +465,13 @@ __global__ __launch_bounds__(64) void k_kv_append_bf16(AttnArgs a) {
 // One wave per (block of 16 entries, query head).  Per block of 32 keys: S = Q K^T (16 x 32 scores, Q as hi + lo bf16
 // planes so that it enters at float32 precision, K straight from the cache in operand layout), causal mask per
 // query, online softmax in float32 on the accumulator layout (a query's 16 keys of a tile sit in one DPP row),
-// P through LDS into operand layout (hi + lo), V through LDS transposed (the MFMA wants 8 consecutive keys per
-// lane), O += P V.  A block that straddles two batch rows handles its runs one after the other.
+// P through LDS into operand layout (hi + lo), V^T tiles straight from the cache (keys beyond the run's last one
+// zeroed: 0 x NaN is NaN), O += P V.  A block that straddles two batch rows handles its runs one after the other.
 template <int DH>
 __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
-  constexpr int T = DH / 32, CT = DH / 16, VS = DH + 8, PS = 36;
+  constexpr int T = DH / 32, CT = DH / 16, PS = 36;
   constexpr float NEG = -1e30f;
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  __shared__ __attribute__((aligned(16))) bf16_t lds_v[32 * VS];
   __shared__ __attribute__((aligned(16))) float lds_p[16 * PS];
   const int n_rows = *a.rd.n_rows, r0 = blockIdx.y * 16;
   if (r0 >= n_rows) return;
@@ -490,7 +531,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
     // Two register buffers: the keys (operand fragments) and values (staging pieces) of block kb + 32 are requested
     // before block kb is worked on.  Addresses are clamped to the run's last key, so a block beyond it loads valid
     // memory, has every key masked and every value zeroed, and changes nothing.
-    struct Blk { u32x4 k[2][T]; u32x4 v[DH / 16]; };
+    struct Blk { u32x4 k[2][T]; u32x4 v[CT]; };
     auto fetch = [&](Blk& B, int kb) {
 #pragma unroll
       for (int tile = 0; tile < 2; ++tile) {
@@ -498,19 +539,17 @@ __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
 #pragma unroll
         for (int t = 0; t < T; ++t) B.k[tile][t] = *reinterpret_cast<const u32x4*>(kr + t * 32);
       }
+      const bf16_t* vb = Vc + (size_t)(min(kb, max_slot & ~31) >> 5) * (32 * DH) + lane * 8;
 #pragma unroll
-      for (int i = 0; i < DH / 16; ++i) {
-        const int u = lane + 64 * i, key = u / (DH / 8), piece = u % (DH / 8);
-        B.v[i] = *reinterpret_cast<const u32x4*>(Vc + (size_t)min(kb + key, max_slot) * DH + piece * 8);
-      }
+      for (int ct = 0; ct < CT; ++ct) B.v[ct] = *reinterpret_cast<const u32x4*>(vb + ct * 512);
     };
-    auto step = [&](const Blk& B, int kb) {
-      // stage V[kb .. kb+31][0 .. DH) in LDS (rows beyond the run's last key as zeros: they may hold anything)
+    auto step = [&](Blk& B, int kb) {
+      if (kb + 31 > max_slot) {                                   // (scalar) zero the values of keys beyond the run's last one
 #pragma unroll
-      for (int i = 0; i < DH / 16; ++i) {
-        const int u = lane + 64 * i, key = u / (DH / 8), piece = u % (DH / 8);
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<u32x4*>(lds_v + key * VS + piece * 8) = (kb + key > max_slot) ? z : B.v[i];
+        for (int ct = 0; ct < CT; ++ct) {
+          const uint4 f = vt_fix(make_uint4(B.v[ct].x, B.v[ct].y, B.v[ct].z, B.v[ct].w), kb + lq * 8, max_slot + 1, 0u);
+          B.v[ct].x = f.x; B.v[ct].y = f.y; B.v[ct].z = f.z; B.v[ct].w = f.w;
+        }
       }
       // scores of the two 16-key tiles
       f32x4 sc[2];
@@ -555,13 +594,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
       }
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
-        // V^T in operand layout: column ct * 16 + l16, keys lq * 8 .. + 8
-        const bf16_t* vr = lds_v + (lq * 8) * VS + ct * 16 + l16;
-        uint4 vf;
-        vf.x = (unsigned)vr[0] | ((unsigned)vr[VS] << 16);
-        vf.y = (unsigned)vr[2 * VS] | ((unsigned)vr[3 * VS] << 16);
-        vf.z = (unsigned)vr[4 * VS] | ((unsigned)vr[5 * VS] << 16);
-        vf.w = (unsigned)vr[6 * VS] | ((unsigned)vr[7 * VS] << 16);
+        const uint4 vf = make_uint4(B.v[ct].x, B.v[ct].y, B.v[ct].z, B.v[ct].w);
         O[ct] = mfma_bf16(ph, vf, O[ct]);
         O[ct] = mfma_bf16(pl, vf, O[ct]);
       }
@@ -596,9 +629,6 @@ static size_t attn_smem_bytes(int DH, int G, int max_seq) {
 
 template <int DH>
 static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, int ctx_bound, hipStream_t s) {
-  // NW = waves per workgroup that share one (row, KV head)'s keys: 8 when the launch has no more workgroups than
-  // the chip has compute units and the contexts are long (c5's target pass: 20 rows x 8 KV heads x 1000+ keys),
-  // else 4 (at c2's 130-400 keys the 8-wave variant takes 9.5 us against 7.8)
   if (a.phase == 1) {          // append only
     hipLaunchKernelGGL((k_kv_append_bf16<DH>), dim3(a.KVH, max_rows), dim3(64), 0, s, a);
     return;
@@ -607,17 +637,12 @@ static void launch_attn_bf16(const AttnArgs& a, int G, int max_rows, int ctx_bou
     hipLaunchKernelGGL((k_attn_mfma_bf16<DH>), dim3(a.H, (max_rows + 15) / 16), dim3(64), 0, s, a);
     return;
   }
+  // NW = waves per workgroup that share one (row, KV head)'s keys: 8 when the launch has no more workgroups than
+  // the chip has compute units and the contexts are long, else 4
   dim3 grid(a.KVH, max_rows);
   const bool wide = (long long)a.KVH * max_rows <= 256 && ctx_bound >= 512;
-#define SPRINTER_ATTN(G_) do { if (wide) hipLaunchKernelGGL((k_attn_bf16<DH, G_, 8>), grid, dim3(512), 0, s, a); \
-                               else hipLaunchKernelGGL((k_attn_bf16<DH, G_, 4>), grid, dim3(256), 0, s, a); } while (0)
-  switch (G) {
-    case 1: SPRINTER_ATTN(1); break;
-    case 2: SPRINTER_ATTN(2); break;
-    case 4: SPRINTER_ATTN(4); break;
-    default: hipLaunchKernelGGL((k_attn_bf16<DH, 8, 4>), grid, dim3(256), 0, s, a); break;   // (8 waves would spill)
-  }
-#undef SPRINTER_ATTN
+  if (wide) hipLaunchKernelGGL((k_attn_dec_bf16<DH, 8>), grid, dim3(512), 0, s, a);
+  else hipLaunchKernelGGL((k_attn_dec_bf16<DH, 4>), grid, dim3(256), 0, s, a);
 }
 
 template <typename T, int DH>
