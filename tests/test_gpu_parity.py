@@ -408,17 +408,65 @@ def test_maximum_batch(ctx, rej):
     p.close()
 
 
-def test_c2_full_prefix_sampled_rows():
-    """Config 2 at full size with the full-prefix target context (work lists of about 20 entries per step)."""
-    test_c2_full_size_sampled_rows(W.CTX_FULL_PREFIX)
+def test_c2_full_prefix_with_coin_and_residual_sampled_rows():
+    """Config 2 at full size with the full-prefix target context (work lists of about 20 entries per step) and the
+    p/q correction on rejection (vocabulary 50257) together; each mode alone is covered at the mini sizes."""
+    _c2_sampled_rows(W.CTX_FULL_PREFIX, W.REJECT_SD)
 
 
-def test_c2_coin_and_residual_sampled_rows():
-    """Config 2 at full size with the p/q correction on rejection (vocabulary 50257)."""
-    test_c2_full_size_sampled_rows(W.CTX_OWN_HISTORY, W.REJECT_SD)
+def test_c2_full_size_all_rows_all_steps():
+    """Config 2 at its full size, in the launch configuration the benchmark times (GPT-2-small/XL shapes, bf16,
+    batch 16, 128-token Zipf prompts, max_seq 384): every row over all 256 generated tokens.  The oracle replays
+    the GPU's committed history decision by decision, 32 steps per call with the caches carried over (and a
+    progress line per call), so contexts up to the workload's last position (383) are compared."""
+    import sys
+    import time
+    from parity_util import compare_replay
+    from oracle import sprinter as osp
+    cfg = W.config("c2")
+    assert cfg.max_seq == cfg.prompt_len + cfg.n_gen and cfg.n_gen == 256
+    t0 = time.time()
+    p = _pair(cfg)
+    G = cfg.n_gen
+    g, st = p.gpu_generate(G)
+    print(f"c2: GPU done after {time.time() - t0:.0f} s, reject rate {1 - g['accept'].mean():.3f}", flush=True)
+    acc = g["accept"].astype(bool)
+    assert np.array_equal(g["accept"], (g["score"] >= np.float32(cfg.tau)).astype(np.uint8))
+    assert np.array_equal(g["tok"][acc], g["draft_tok"][acc])
+    assert np.array_equal(st["target_calls"], (~acc).sum(1)) and st["steps"] == G
+    def say(line):
+        print(line, flush=True)
+        sys.__stderr__.write(line + "\n")
+        sys.__stderr__.flush()
+
+    dc = osp.prefill_whole_prompt(p.draft, p.prompts, p.plen)
+    say(f"c2: oracle draft caches filled at {time.time() - t0:.0f} s")
+    tc = []
+    for b in range(0, cfg.batch, 4):                     # four rows per call, a progress line each
+        tc += osp.prefill_whole_prompt(p.target, p.prompts[b:b + 4], p.plen[b:b + 4])
+        say(f"c2: oracle target caches of rows {b}..{b + 3} filled at {time.time() - t0:.0f} s")
+    seqs = [list(map(int, p.prompts[b][:p.plen[b]])) for b in range(cfg.batch)]
+    tot = dict(n=0, flag_flips_tolerated=0, draft_tok_flips_tolerated=0, target_tok_flips_tolerated=0, max_score_diff=0.0)
+    for g0 in range(0, G, 32):
+        g1 = min(G, g0 + 32)
+        gs = {k: v[:, g0:g1] for k, v in g.items()}
+        prm = np.array(seqs, np.int32)
+        pln = np.full(cfg.batch, prm.shape[1], np.int32)
+        rec = osp.generate(p.draft, p.target, p.verifier, prm, pln, g1 - g0, cfg.tau, cfg.temperature, cfg.seed,
+                           forced=dict(tok=gs["tok"], accept=gs["accept"], draft_tok=gs["draft_tok"]),
+                           draft_caches=dc, target_caches=tc)
+        rep = compare_replay(cfg, gs, rec)
+        for k in tot:
+            tot[k] = max(tot[k], rep[k]) if k == "max_score_diff" else tot[k] + rep[k]
+        for b in range(cfg.batch):
+            seqs[b] += [int(x) for x in gs["tok"][b]]
+        say(f"c2: oracle steps {g0}..{g1 - 1} at {time.time() - t0:.0f} s: {rep}")
+    print("c2 all rows, all steps:", tot, flush=True)
+    assert tot["n"] == cfg.batch * G
+    p.close()
 
 
-def test_c2_full_size_sampled_rows(ctx_mode=W.CTX_OWN_HISTORY, reject_mode=W.REJECT_REPLACE):
+def _c2_sampled_rows(ctx_mode, reject_mode):
     """Config 2 at its full size and in the launch configuration the benchmark times
     (GPT-2-small/XL shapes, bf16, batch 16, 128-token Zipf prompts): the oracle replays
     a sample of rows (first, last, two seeded) over the first steps on the GPU's history."""

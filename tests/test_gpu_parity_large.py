@@ -76,28 +76,53 @@ def _whole_batch_properties(g, st, tau, vocab):
     assert (g["tok"] >= 0).all() and (g["tok"] < vocab).all()
 
 
-def _replay_segments(side, g, rows, settings):
+def _caches_after(side, row, g, n_steps):
+    """The oracle's caches of one row as they stand after n_steps of the GPU's committed history, rebuilt with
+    one uncached forward per model (own-history target context): the draft has read every committed token but
+    the last, the target the prompt (all but its last token) plus the input token of every rejected step, each
+    at its true position."""
+    from oracle import model as om
+    P = int(side.plen[row])
+    seq = [int(x) for x in side.prompts[row][:P]] + [int(x) for x in g["tok"][row][:n_steps]]
+    dc, tc = side.draft.new_cache(), side.target.new_cache()
+    t = time.time()
+    side.draft.forward_full(seq[:-1], cache=dc, want_logits=False)
+    progress(f"{side.cfg.name}: oracle draft cache of row {row} rebuilt over {len(seq) - 1} tokens in {time.time() - t:.0f} s")
+    pos = list(range(P - 1)) + [P - 1 + k for k in range(n_steps) if g["accept"][row][k] == 0]
+    t = time.time()
+    side.target.forward_full([seq[j] for j in pos], positions=pos, cache=tc, want_logits=False)
+    progress(f"{side.cfg.name}: oracle target cache of row {row} rebuilt over {len(pos)} entries in {time.time() - t:.0f} s")
+    return dc, tc, seq
+
+
+def _replay_segments(side, g, rows, settings, start=0, caches=None):
     """Oracle replay of the sampled rows on the GPU's committed history.  settings[step] =
     (tau, b2): the threshold and the verifier's output bias in force at that step; consecutive
-    steps with the same setting are replayed in one oracle call, the caches carry over."""
+    steps with the same setting are replayed in one oracle call, the caches carry over.
+    start / caches: replay steps start .. start + len(settings) - 1 from caches rebuilt by _caches_after
+    (lists of draft caches, target caches and token lists, one per row) instead of from the prompts."""
     from oracle import model as om, sprinter as osp
     from parity_util import compare_replay, compare_sd
     cfg = side.cfg
     sd = cfg.reject_mode == W.REJECT_SD
-    G = len(settings)
-    pr, pl = side.prompts[rows], side.plen[rows]
-    t = time.time()
-    dc = osp.prefill_whole_prompt(side.draft, pr, pl)
-    progress(f"{cfg.name}: oracle draft prefill of rows {rows} in {time.time() - t:.0f} s")
-    t = time.time()
-    tc = []
-    for i in range(len(rows)):       # row by row, with a progress line each
-        tc += osp.prefill_whole_prompt(side.target, pr[i:i + 1], pl[i:i + 1])
-        progress(f"{cfg.name}: oracle target prefill row {rows[i]} (P={int(pl[i])}) at {time.time() - t:.0f} s")
-    seqs = [list(map(int, pr[i][:pl[i]])) for i in range(len(rows))]
+    G = start + len(settings)
+    settings = [None] * start + list(settings)
+    if caches is None:
+        pr, pl = side.prompts[rows], side.plen[rows]
+        t = time.time()
+        dc = osp.prefill_whole_prompt(side.draft, pr, pl)
+        progress(f"{cfg.name}: oracle draft prefill of rows {rows} in {time.time() - t:.0f} s")
+        t = time.time()
+        tc = []
+        for i in range(len(rows)):       # row by row, with a progress line each
+            tc += osp.prefill_whole_prompt(side.target, pr[i:i + 1], pl[i:i + 1])
+            progress(f"{cfg.name}: oracle target prefill row {rows[i]} (P={int(pl[i])}) at {time.time() - t:.0f} s")
+        seqs = [list(map(int, pr[i][:pl[i]])) for i in range(len(rows))]
+    else:
+        dc, tc, seqs = caches
     tot = dict(flag_flips_tolerated=0, draft_tok_flips_tolerated=0, target_tok_flips_tolerated=0, n=0,
                max_score_diff=0.0, rejected=0)
-    g0 = 0
+    g0 = start
     while g0 < G:
         tau, b2 = settings[g0]
         g1 = g0
@@ -158,7 +183,7 @@ def test_c3_full_size_sampled_rows(llama7b, ctx, rej):
     exercised on the sampled rows too.  Second case: the full-prefix target context together with the
     p/q correction (after eight almost rejection-free steps the first work lists are long)."""
     weights, models = llama7b
-    cfg = replace(W.config("c3"), max_seq=320, target_ctx_mode=ctx, reject_mode=rej)
+    cfg = replace(W.config("c3"), target_ctx_mode=ctx, reject_mode=rej)      # max_seq 768: the benchmark's cache strides
     s = Side(cfg, weights, models)
     n1, n2 = 8, 8
     t = time.time()
@@ -193,7 +218,7 @@ def test_c3_speculative_decoding_sampled_rows(llama7b):
     from parity_util import compare_sd_rounds, sd_rounds_to_lists
     weights, models = llama7b
     gamma, rounds = 4, 4
-    cfg = replace(W.config("c3"), max_seq=320, sd_gamma=gamma)
+    cfg = replace(W.config("c3"), sd_gamma=gamma)
     s = Side(cfg, weights, models)
     t = time.time()
     s.gpu.prefill(s.prompts, s.plen)
@@ -229,7 +254,7 @@ def test_c4_compaction_and_ragged_target(llama7b):
     n_cal, n_seg = 8, 4
     combos = [(tau, rho) for tau in (0.3, 0.5, 0.7) for rho in (0.05, 0.25, 0.60)]
     G = n_cal + n_seg * len(combos)
-    cfg = replace(base, max_seq=base.prompt_len + G + 2)
+    cfg = base                                                # max_seq 1280: the benchmark's cache strides
     s = Side(cfg, weights, models)
     B = cfg.batch
     assert s.plen.min() >= 64 and s.plen.max() <= 1024 and len(set(s.plen.tolist())) > 64
@@ -279,7 +304,9 @@ def test_c4_compaction_and_ragged_target(llama7b):
     assert st["steps"] == G and st["sum_rejected"] == int((g["accept"] == 0).sum())
     order = np.argsort(s.plen, kind="stable")
     rng = np.random.default_rng(4)
-    rows = sorted({int(order[0]), int(order[B // 2]), int(rng.choice(order[: B // 2]))})
+    # shortest prompt, one seeded from the shorter half, and the longest (its target cache starts near slot 1000)
+    rows = sorted({int(order[0]), int(rng.choice(order[: B // 2])), int(order[-1])})
+    assert int(s.plen[order[-1]]) > 960
     tot = _replay_segments(s, g, rows, settings)
     assert tot["rejected"] > 0
     progress(f"c4: achieved reject rates {np.round(achieved, 3).tolist()}")
@@ -288,10 +315,17 @@ def test_c4_compaction_and_ragged_target(llama7b):
 
 def test_c5_full_size_sampled_rows():
     """Config 5: batch 64, 1024-token prompts, grouped-query attention (32 query / 8 KV heads),
-    vocabulary 128256, both KV caches resident."""
-    base = W.config("c5")
-    G = 6
-    cfg = replace(base, max_seq=base.prompt_len + G + 2)
+    vocabulary 128256, both KV caches resident, at the benchmark's max_seq (2048) and cache strides.
+    Segments on the GPU: 8 steps with the workload's verifier, 16 with its output bias shifted to a 50 %
+    reject rate, 480 with the threshold above 1 (every row rejected: both caches grow to 1500+ entries),
+    then 8 more at the 50 % setting.  The oracle replays rows 0 and 63 over the first 24 steps from the
+    prompt, and a seeded row over the last 8 steps from caches rebuilt over its 1500+ committed tokens, so
+    late cache slots of both models are attended under comparison (an oracle prefill of one 1024-token row
+    of this pair takes 45 s, a rebuild 85 s: the sample is sized to the test-time budget)."""
+    cfg = W.config("c5")
+    assert cfg.max_seq == 2048
+    n1, n2, n_long, n_late = 8, 16, 480, 8
+    G = n1 + n2 + n_long + n_late
     t = time.time()
     weights = W.make_weights(cfg)
     progress(f"c5 weights generated in {time.time() - t:.0f} s")
@@ -299,11 +333,44 @@ def test_c5_full_size_sampled_rows():
     s = Side(cfg, weights, models)
     t = time.time()
     s.gpu.prefill(s.prompts, s.plen)
-    o = s.gpu.generate(G)
-    g = {k: v.cpu().numpy() for k, v in o.items()}
+    b2_0 = float(weights[2]["v.b2"][0])
+    outs = [{k: v.cpu().numpy() for k, v in s.gpu.generate(n1).items()}]
+    b2 = _shifted_bias(outs[0]["score"], b2_0, cfg.tau, 0.50)
+    vw = dict(weights[2])
+    vw["v.b2"] = np.array([b2], np.float32)
+    s.gpu.load_weights(s.b.VERIFIER, vw)
+    outs.append({k: v.cpu().numpy() for k, v in s.gpu.generate(n2).items()})
+    s.gpu.set_tau(1.5)
+    outs.append({k: v.cpu().numpy() for k, v in s.gpu.generate(n_long).items()})
+    s.gpu.set_tau(cfg.tau)
+    outs.append({k: v.cpu().numpy() for k, v in s.gpu.generate(n_late).items()})
+    g = {k: np.concatenate([o[k] for o in outs], 1) for k in outs[0]}
     st = s.gpu.stats()
-    progress(f"c5: GPU prefill + {G} steps in {time.time() - t:.0f} s, reject rate {1 - g['accept'].mean():.3f}")
-    _whole_batch_properties(g, st, cfg.tau, cfg.draft.vocab)
-    tot = _replay_segments(s, g, [0, cfg.batch - 1], [(cfg.tau, float(weights[2]["v.b2"][0]))] * G)
-    assert tot["rejected"] > 0
+    progress(f"c5: GPU prefill + {G} steps in {time.time() - t:.0f} s, reject rates "
+             f"{[round(float(1 - o['accept'].mean()), 3) for o in outs]}")
+    # whole-batch rules, per segment (the threshold differs)
+    at = 0
+    for o, tau in zip(outs, (cfg.tau, cfg.tau, 1.5, cfg.tau)):
+        n = o["accept"].shape[1]
+        assert np.array_equal(o["accept"], (o["score"] >= np.float32(tau)).astype(np.uint8))
+        at += n
+    acc = g["accept"].astype(bool)
+    assert np.array_equal(g["tok"][acc], g["draft_tok"][acc])
+    assert np.array_equal(st["target_calls"], (~acc).sum(1)) and st["steps"] == G
+    assert (g["tok"] >= 0).all() and (g["tok"] < cfg.draft.vocab).all()
+    assert not outs[2]["accept"].any()
+    assert 0.3 < 1 - outs[1]["accept"].mean() < 0.7
+    rng = np.random.default_rng(5)
+    extra = [int(x) for x in rng.choice(np.arange(1, cfg.batch - 1), 2, replace=False)]
+    rows = [0, cfg.batch - 1]
+    early = {k: v[:, :n1 + n2] for k, v in g.items()}
+    tot = _replay_segments(s, early, rows, [(cfg.tau, b2_0)] * n1 + [(cfg.tau, b2)] * n2)
+    assert tot["rejected"] >= 12
+    # late window of one more row: steps n1 + n2 + n_long .. G - 1, positions 1528 .. 1535
+    row, start = extra[1], n1 + n2 + n_long
+    dc, tc, seq = _caches_after(s, row, g, start)
+    assert len(dc) == 1024 + start - 1 and len(tc) >= 1023 + n_long
+    late = _replay_segments(s, g, [row], [(cfg.tau, b2)] * n_late, start=start, caches=([dc], [tc], [seq]))
+    progress(f"c5: late window of row {row}: {late}")
+    assert tot["rejected"] + late["rejected"] >= 16
     s.close()
