@@ -416,7 +416,8 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
     label = (f"{cfg.name}: batch {B}, prompt {pmax if not cfg.prompt_len_min else f'{cfg.prompt_len_min}..{pmax}'}, "
              f"tau {cfg.tau}, T {cfg.temperature}; "
              f"draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target L{cfg.target.n_layer} "
-             f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, Zipf(1.1) prompts"
+             f"d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init weights, "
+             f"{'Zipf(1.1)' if cfg.prompt_dist == 'zipf' else 'uniform'} prompts"
              + ("; full-prefix target context" if cfg.target_ctx_mode == 1 else "")
              + ("; p/q coin + residual on rejection" if cfg.reject_mode == 1 else "")
              + (f"; verifier bias calibrated to a reject rate of {reject_rate}" if reject_rate is not None else

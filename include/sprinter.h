@@ -211,10 +211,11 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
 /* Takes the "Prefix" input of Alg. 1 / Alg. 2 for B independent rows: resets
  * state and counters and fills both KV caches with
  * positions 0 .. P_b-2 of each prompt; the first decode step then feeds the last
- * prompt token at position P_b-1.  bf16: all (row, position) pairs go through both
+ * prompt token at position P_b-1.  All (row, position) pairs go through both
  * models in row-major chunks of cfg.chunk_rows tokens per pass over the weights
- * (matrix-core GEMMs over the whole chunk, causal attention over each row's run of
- * positions); float32: one pass per position.  The
+ * (bf16: matrix-core GEMMs over the whole chunk and causal matrix-core attention
+ * over each row's run of positions; float32: the vector kernels, 16 tokens per
+ * pass by default).  The
  * stream is drained every 4 passes.  dev_prompt is [B, max_prompt] int32 (padding
  * is never read), host_prompt_len[B] has 1 <= P_b <= max_prompt.  Errors:
  * B > max_batch, P_b out of range, max_prompt > max_seq (or > max_pos), weights

@@ -763,10 +763,11 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
   ctx->steps_done = 0;
   ctx->run_kind = 0; ctx->sd_wait_ticket = 0;
   Model &dq = ctx->draft, &tp = ctx->target;
-  if (ctx->cfg.dtype == SPRINTER_BF16) {
+  {
     // Chunked prefill: all (row, position) pairs, row-major, go through both models rows_alloc at a time with the
     // kernels of the multi-entry target pass (every layer appends the chunk's keys / values, then attends), so the
-    // weights are streamed once per rows_alloc prompt tokens instead of once per position of the batch.
+    // weights are streamed once per rows_alloc prompt tokens instead of once per position of the batch
+    // (bf16: 4096 tokens per pass through the matrix-core kernels; float32: 16 unless cfg.chunk_rows says otherwise).
     std::vector<int> off((size_t)B + 1, 0);
     for (int b = 0; b < B; ++b) off[b + 1] = off[b] + host_prompt_len[b] - 1;
     const long long E = off[B];
@@ -788,18 +789,6 @@ int sprinter_prefill(sprinter_ctx* ctx, const int32_t* dev_prompt, const int32_t
       // bound the number of launches in flight (tools that keep per-dispatch state have died on long backlogs)
       if ((chunk & 3) == 3 && hipStreamSynchronize(s) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
     }
-  } else
-  for (int j = 0; j + 1 < pmax; ++j) {
-    int n_j = 0;                                   // rows whose prompt still has a token to cache at index j
-    for (int b = 0; b < B; ++b) n_j += j < host_prompt_len[b] - 1;
-    launch_prefill_prep(dev_prompt, max_prompt, j, B, ctx->st.prompt_len, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos,
-                        dq.rd_slot, s);
-    forward(ctx, dq, dq.rd(), n_j, false, 0u, nullptr);
-    forward(ctx, tp, dq.rd(), n_j, false, 1u, nullptr);
-    // A long prompt would otherwise leave hundreds of thousands of launches queued (c2: 860 per position);
-    // profiling tools that keep per-dispatch state have died on such a backlog.  Draining every 4 positions
-    // costs nothing measurable.
-    if ((j & 3) == 3 && hipStreamSynchronize(s) != hipSuccess) return fail(ctx, SPRINTER_E_HIP, "stream synchronisation failed");
   }
   launch_prefill_finish(dev_prompt, max_prompt, B, ctx->st, dq.rd_n, dq.rd_b, dq.rd_tok, dq.rd_pos, dq.rd_slot, s);
   launch_set_i32(ctx->coin_kept, 0, s);

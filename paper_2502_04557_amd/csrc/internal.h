@@ -207,8 +207,6 @@ struct SdFinishArgs {
 };
 void launch_sd_round_finish(const SdBase& a, const SdFinishArgs& f, hipStream_t s);
 
-void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const int* prompt_len,
-                         int* n_rows, int* rb, int* rtok, int* rpos, int* rslot, hipStream_t s);
 void launch_prefill_begin(const int* prompt, int max_prompt, int B, State st, int* rej_idx, int* n_rej, hipStream_t s);
 void launch_prefill_finish(const int* prompt, int max_prompt, int B, State st,
                            int* d_n_rows, int* d_b, int* d_tok, int* d_pos, int* d_slot, hipStream_t s);

@@ -147,38 +147,6 @@ void launch_step_finish(const FinishArgs& a, hipStream_t s) {
 }
 
 // ================================================================ prefill
-// Rows whose prompt still has a token at index j (other than its last one).
-__global__ __launch_bounds__(1024) void k_prefill_prep(const int* __restrict__ prompt, int max_prompt, int j, int B,
-                                                       const int* __restrict__ prompt_len, int* n_rows, int* rb,
-                                                       int* rtok, int* rpos, int* rslot) {
-  __shared__ int s_wave_cnt[16];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const bool on = tid < B && j < prompt_len[tid] - 1;
-  const u64 mask = __ballot(on);
-  const int rank = __popcll(mask & ((1ull << lane) - 1ull));
-  if (lane == 0) s_wave_cnt[w] = __popcll(mask);
-  __syncthreads();
-  int off = 0, total = 0;
-  for (int q = 0; q < 16; ++q) {
-    int c = s_wave_cnt[q];
-    if (q < w) off += c;
-    total += c;
-  }
-  if (on) {
-    int i = off + rank;
-    rb[i] = tid;
-    rtok[i] = prompt[(size_t)tid * max_prompt + j];
-    rpos[i] = j;
-    rslot[i] = j;
-  }
-  if (tid == 0) *n_rows = total;
-}
-void launch_prefill_prep(const int* prompt, int max_prompt, int j, int B, const int* prompt_len, int* n_rows, int* rb,
-                         int* rtok, int* rpos, int* rslot, hipStream_t s) {
-  hipLaunchKernelGGL(k_prefill_prep, dim3(1), dim3(1024), 0, s, prompt, max_prompt, j, B, prompt_len, n_rows, rb,
-                     rtok, rpos, rslot);
-}
-
 // Chunked prefill: the prompts go into the token history, every row's caches count as empty and every row is
 // listed, so that the full-prefix work-list kernel (k_catchup_chunk) enumerates the prompt positions 0 .. P_b-2
 // in row-major order from the prefix sums the host uploaded.
