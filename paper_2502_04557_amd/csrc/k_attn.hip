@@ -184,26 +184,32 @@ __device__ __forceinline__ uint4 vt_fix(uint4 v, int key0, int slot, unsigned ow
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global access
+// of the wave (vmcnt(0)): here that would be the first block's keys and values, requested on purpose long before
+// they are needed, and the cache append.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // bf16 single-query attention on the matrix cores: one workgroup of NW waves per (row, KV head); the G query heads
 // that share the KV head are rows of one 16-row operand, so a cached key costs the same whatever G is and the
 // kernel is left with streaming the cache.  Wave w takes the 32-key blocks w, w + NW, ...; per block
 // S = Q K^T (Q rotated, scaled and split into hi + lo bf16 planes in registers, so it enters at float32
 // precision; K fragments straight from the cache), online softmax in float32 on the accumulator layout (the 16 keys
 // of a tile sit in one DPP row), P through a wave-private piece of LDS into operand layout (hi + lo), V^T tiles
-// straight from the cache, O += P V.  A block's keys are requested a whole step ahead (two register buffers), its
-// value tiles as soon as the previous block's have been consumed; nothing in the loop synchronises waves.  The row's own key and value
+// straight from the cache, O += P V.  A block's keys and value tiles are requested a whole step ahead (two register
+// buffers; the query operand is kept in LDS to make room); nothing in the loop synchronises waves.  The row's own key and value
 // (the token being processed) are computed in the prologue, appended to the cache by wave 0 and patched into the
 // operands of the block that holds slot `slot`, which is the row's last block; keys beyond it are masked.
 // The waves' partial results are merged through LDS at the end.
 //   phase 0: append + attend; 1: append only; 2: attend only (the entry is already cached; patching it in again
 //   changes nothing).
 template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
+__global__ __launch_bounds__(NW * 64, 2) void k_attn_dec_bf16(AttnArgs a) {
   constexpr int T = DH / 32, CT = DH / 16, PS = 36, HALF = DH / 2, GMAX = 8;
   constexpr float NEG = -1e30f;
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   __shared__ __attribute__((aligned(16))) float lds_p[NW][GMAX * PS];
   __shared__ __attribute__((aligned(16))) bf16_t lds_kn[DH];
+  __shared__ uint4 lds_q[2][T][64];
   __shared__ float s_ml[NW][GMAX][2];
   __shared__ float s_o[NW][GMAX][DH];
   const int r = blockIdx.y;
@@ -214,26 +220,26 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
   bf16_t* __restrict__ Kc = (bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   bf16_t* __restrict__ Vc = (bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   const int n_steps = (slot + 32 * NW) / (32 * NW);             // blocks 0 .. slot / 32, NW per step
-  // Register buffers: two for the key fragments (a block's keys are requested a whole step ahead), one for the value
-  // tiles (requested as soon as the previous block's P V is issued).  Addresses are clamped into the cache.
-  struct KBuf { u32x4 k[2][T]; };
-  auto fetch_k = [&](KBuf& B, int kb) {
+  // Two register buffers: a block's key fragments and value tiles are requested a whole step ahead (the query
+  // operand lives in LDS to make room for them).  Addresses are clamped into the cache.
+  // A block beyond the row's last one is read at the last one's address (scalar clamp) and fully masked; inside a
+  // block nothing is clamped: the caches hold a multiple of 32 slots per (row, KV head), so every key of a block
+  // that exists lies inside the cache.  Per-lane base addresses once, block offsets are scalars.
+  struct Blk { u32x4 k[2][T]; u32x4 v[CT]; };
+  const bf16_t* const k_lane = Kc + (size_t)l16 * DH + lq * 8;
+  const bf16_t* const v_lane = Vc + lane * 8;
+  const int kb_last = slot & ~31;
+  auto fetch = [&](Blk& B, int kb) {
+    const size_t off = (size_t)min(kb, kb_last) * DH;            // elements; the same for keys and value tiles
 #pragma unroll
-    for (int tile = 0; tile < 2; ++tile) {
-      const bf16_t* kr = Kc + (size_t)min(kb + tile * 16 + l16, slot) * DH + lq * 8;
+    for (int tile = 0; tile < 2; ++tile)
 #pragma unroll
-      for (int t = 0; t < T; ++t) B.k[tile][t] = *reinterpret_cast<const u32x4*>(kr + t * 32);
-    }
+      for (int t = 0; t < T; ++t) B.k[tile][t] = *reinterpret_cast<const u32x4*>(k_lane + off + tile * 16 * DH + t * 32);
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) B.v[ct] = *reinterpret_cast<const u32x4*>(v_lane + off + ct * 512);
   };
-  u32x4 V[CT];
-  auto fetch_v = [&](int kb) {
-    const bf16_t* vb = Vc + (size_t)(min(kb, slot & ~31) >> 5) * (32 * DH) + lane * 8;
-#pragma unroll
-    for (int ct = 0; ct < CT; ++ct) V[ct] = *reinterpret_cast<const u32x4*>(vb + ct * 512);
-  };
-  KBuf A, B;
-  fetch_k(A, w * 32);
-  fetch_v(w * 32);
+  Blk A, B;
+  fetch(A, w * 32);
   // The query heads as one operand (row l16 = head min(l16, G - 1): rows beyond G repeat the last head and are
   // ignored), the new key as operand pieces, the new value per column: unconditional loads first, then arithmetic.
   const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
@@ -244,8 +250,9 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
   float vraw[CT];
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) vraw[ct] = yv[ct * 16 + l16];
-  uint4 qh[T], ql[T];
+  if (w == 0) {                                                  // (scalar) one wave prepares the query operand and the new key
   u32x4 knew[T];
+  uint4 qh[T], ql[T];
 #pragma unroll
   for (int t = 0; t < T; ++t) {
     const int d0 = t * 32 + lq * 8, p0 = d0 ^ HALF;
@@ -281,12 +288,15 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
     knew[t].z = (unsigned)f2bf(kn[4]) | ((unsigned)f2bf(kn[5]) << 16);
     knew[t].w = (unsigned)f2bf(kn[6]) | ((unsigned)f2bf(kn[7]) << 16);
   }
-  if (w == 0 && l16 == 0) {                                      // the new key: into LDS for the row's last block, and into the cache
+#pragma unroll
+  for (int t = 0; t < T; ++t) { lds_q[0][t][lane] = qh[t]; lds_q[1][t][lane] = ql[t]; }   // hi, lo planes, for every wave
+  if (l16 == 0) {                                      // the new key: into LDS for the row's last block, and into the cache
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       *reinterpret_cast<u32x4*>(lds_kn + t * 32 + lq * 8) = knew[t];
       if (a.phase != 2) *reinterpret_cast<u32x4*>(Kc + (size_t)slot * DH + t * 32 + lq * 8) = knew[t];
     }
+  }
   }
   unsigned vnew[CT / 2];                                         // the new value of columns ct * 16 + l16 as bf16 bits, two per register
 #pragma unroll
@@ -296,14 +306,13 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
     if (ct & 1) vnew[ct >> 1] |= h << 16; else vnew[ct >> 1] = h;
   }
   if (a.phase == 1) return;
-  __syncthreads();                                               // the new key is in LDS for every wave
+  lds_barrier();                                                 // the query operand and the new key are in LDS for every wave
   f32x4 O[CT];
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) O[ct] = (f32x4){0.f, 0.f, 0.f, 0.f};
   float m_run[4] = {NEG, NEG, NEG, NEG}, l_run[4] = {0.f, 0.f, 0.f, 0.f};
   float* myp = lds_p[w];
-  // step(keys of block kb, block kb, next block whose value tiles are requested once this block's are consumed)
-  auto step = [&](KBuf& Bk, int kb, int kb_next) {
+  auto step = [&](Blk& Bk, int kb) {
     if (kb + 31 >= slot) {                                       // (scalar) the row's last block or beyond: patch the new key in
 #pragma unroll
       for (int tile = 0; tile < 2; ++tile)
@@ -320,8 +329,8 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
       for (int t = 0; t < T; ++t) {
         const u32x4 kk = Bk.k[tile][t];
         const uint4 kf = make_uint4(kk.x, kk.y, kk.z, kk.w);
-        sc[tile] = mfma_bf16(qh[t], kf, sc[tile]);
-        sc[tile] = mfma_bf16(ql[t], kf, sc[tile]);
+        sc[tile] = mfma_bf16(lds_q[0][t][lane], kf, sc[tile]);
+        sc[tile] = mfma_bf16(lds_q[1][t][lane], kf, sc[tile]);
       }
     }
     // accumulator register v of lane (lq, l16) is head lq * 4 + v, key kb + tile * 16 + l16
@@ -357,29 +366,27 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
         const unsigned own = (ct & 1) ? (vnew[ct >> 1] >> 16) : (vnew[ct >> 1] & 0xffffu);
-        const uint4 f = vt_fix(make_uint4(V[ct].x, V[ct].y, V[ct].z, V[ct].w), kb + lq * 8, slot, own);
-        V[ct].x = f.x; V[ct].y = f.y; V[ct].z = f.z; V[ct].w = f.w;
+        const uint4 f = vt_fix(make_uint4(Bk.v[ct].x, Bk.v[ct].y, Bk.v[ct].z, Bk.v[ct].w), kb + lq * 8, slot, own);
+        Bk.v[ct].x = f.x; Bk.v[ct].y = f.y; Bk.v[ct].z = f.z; Bk.v[ct].w = f.w;
       }
     }
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
-      const uint4 vf = make_uint4(V[ct].x, V[ct].y, V[ct].z, V[ct].w);
+      const uint4 vf = make_uint4(Bk.v[ct].x, Bk.v[ct].y, Bk.v[ct].z, Bk.v[ct].w);
       O[ct] = mfma_bf16(ph, vf, O[ct]);
       O[ct] = mfma_bf16(pl, vf, O[ct]);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    fetch_v(kb_next);
   };
   for (int i = 0; i < n_steps; i += 2) {
     const int kb = (i * NW + w) * 32;
-    fetch_k(B, kb + 32 * NW);
+    fetch(B, kb + 32 * NW);
     __builtin_amdgcn_sched_barrier(0);
-    step(A, kb, kb + 32 * NW);
+    step(A, kb);
     __builtin_amdgcn_sched_barrier(0);
     if (i + 1 < n_steps) {                                       // (scalar condition)
-      fetch_k(A, kb + 64 * NW);
+      fetch(A, kb + 64 * NW);
       __builtin_amdgcn_sched_barrier(0);
-      step(B, kb + 32 * NW, kb + 64 * NW);
+      step(B, kb + 32 * NW);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -393,7 +400,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_dec_bf16(AttnArgs a) {
       for (int ct = 0; ct < CT; ++ct) s_o[w][g][ct * 16 + l16] = O[ct][v];
     }
   }
-  __syncthreads();
+  lds_barrier();
   bf16_t* __restrict__ ao = (bf16_t*)a.ao;
   for (int idx = tid; idx < G * DH; idx += NW * 64) {
     const int g = idx / DH, i = idx % DH;

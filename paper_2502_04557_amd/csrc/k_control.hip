@@ -14,13 +14,28 @@ __global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
   __shared__ int s_tok[1024];
   __shared__ int s_wave_cnt[16];
   __shared__ int s_rej[1024];
+  __shared__ u64 s_key[16][64];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int B = a.B;
-  for (int m = w; m < B; m += 16) {
-    u64 k = merge_partials(a.am_part, a.n_lm_wg, a.Mpad, m, lane);
-    if (lane == 0) s_tok[m] = key_index(k);
+  // Arg-max merge over the LM head's per-workgroup partials part[workgroup][row]: a lane takes one row of a block
+  // of 64, a wave every 16th workgroup, so that a load covers 64 consecutive rows of one workgroup (512 contiguous
+  // bytes; with a lane per workgroup every 8-byte load hit its own cache line: 37 us at 64 rows and 512 workgroups),
+  // then the 16 waves' results meet in LDS.
+  for (int rb = 0; rb < B; rb += 64) {
+    const int m = rb + lane;
+    u64 k = 0;
+    if (m < B)
+      for (int i = w; i < a.n_lm_wg; i += 16) k = umax64(k, a.am_part[(size_t)i * a.Mpad + m]);
+    s_key[w][lane] = k;
+    __syncthreads();
+    if (w == 0 && m < B) {
+      u64 kk = s_key[0][lane];
+#pragma unroll
+      for (int q = 1; q < 16; ++q) kk = umax64(kk, s_key[q][lane]);
+      s_tok[m] = key_index(kk);
+    }
+    __syncthreads();
   }
-  __syncthreads();
   bool active = tid < B;
   float score = 0.f;
   bool acc = true;

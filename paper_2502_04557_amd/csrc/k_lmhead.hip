@@ -199,9 +199,10 @@ void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, cons
 }
 
 // =============================================================== verifier
-// Hidden layer of the verifier MLP, spread over workgroups of 8 waves (one hidden
-// unit per wave); each workgroup leaves its share of the output logit per row.
+// Hidden layer of the verifier MLP, spread over workgroups of 8 waves (VU hidden
+// units per wave); each workgroup leaves its share of the output logit per row.
 // d_hidden == 0: the logit is w2 . hf (a single chunk).
+constexpr int VU = 4;
 __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__ hf, int d, int d_hidden,
                                                        const float* __restrict__ w1, const float* __restrict__ b1,
                                                        const float* __restrict__ w2, const int* __restrict__ n_rows_p,
@@ -218,31 +219,51 @@ __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__
     }
     return;
   }
-  // one hidden unit per wave: its weight row stays in registers (2048 columns at a time), the rows of the
-  // batch go four at a time so that their loads and reductions overlap
-  const int j = blockIdx.x * 8 + w;
-  const bool unit = j < d_hidden;
-  const float bj = unit ? b1[j] : 0.f, w2j = unit ? w2[j] : 0.f;
-  for (int m0 = 0; m0 < n_rows; m0 += 4) {
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int kc = 0; kc < d; kc += 2048) {
-      float wreg[32];
+  // VU hidden units per wave: their weight rows stay in registers (2048 columns at a time), the rows of the batch
+  // go four at a time so that their loads and reductions overlap.  Every wave reads the whole hidden-state matrix
+  // (from L2), so the units per wave set that traffic: with one unit per wave 512 waves re-read 0.5 MB each at
+  // d = 2048 and 64 rows (81 us); with four it is a quarter of that.
+  const int j0 = (blockIdx.x * 8 + w) * VU;
+  float bj[VU], w2j[VU];
 #pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        const int k = kc + lane + 64 * i;
-        wreg[i] = (unit && k < d) ? w1[(size_t)j * d + k] : 0.f;
-      }
+  for (int u = 0; u < VU; ++u) {
+    const bool unit = j0 + u < d_hidden;
+    bj[u] = unit ? b1[j0 + u] : 0.f;
+    w2j[u] = unit ? w2[j0 + u] : 0.f;              // (a unit beyond the layer contributes relu(0) * 0)
+  }
+  for (int m0 = 0; m0 < n_rows; m0 += 4) {
+    float acc[VU][4];
+#pragma unroll
+    for (int u = 0; u < VU; ++u)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[u][r] = 0.f;
+    for (int kc = 0; kc < d; kc += 2048) {
+      float wreg[VU][32];
+#pragma unroll
+      for (int u = 0; u < VU; ++u)
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+          const int k = kc + lane + 64 * i;
+          wreg[u][i] = (j0 + u < d_hidden && k < d) ? w1[(size_t)(j0 + u) * d + k] : 0.f;
+        }
 #pragma unroll
       for (int i = 0; i < 32; ++i) {
         const int k = min(kc + lane + 64 * i, d - 1);
+        float h[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc[r] += wreg[i] * hf[(size_t)min(m0 + r, n_rows - 1) * d + k];
+        for (int r = 0; r < 4; ++r) h[r] = hf[(size_t)min(m0 + r, n_rows - 1) * d + k];
+#pragma unroll
+        for (int u = 0; u < VU; ++u)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[u][r] += wreg[u][i] * h[r];
       }
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const float t = wave_sum(acc[r]) + bj;
-      if (lane == 0 && m0 + r < n_rows) contrib[w * max_rows + m0 + r] = unit ? fmaxf(t, 0.f) * w2j : 0.f;
+      float t = 0.f;
+#pragma unroll
+      for (int u = 0; u < VU; ++u) t += fmaxf(wave_sum(acc[u][r]) + bj[u], 0.f) * w2j[u];
+      if (lane == 0 && m0 + r < n_rows) contrib[w * max_rows + m0 + r] = t;
     }
   }
   __syncthreads();
@@ -253,7 +274,7 @@ __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__
     part[(size_t)blockIdx.x * max_rows + m] = sacc;
   }
 }
-int verifier_num_chunks(int d_hidden) { return d_hidden > 0 ? (d_hidden + 7) / 8 : 1; }
+int verifier_num_chunks(int d_hidden) { return d_hidden > 0 ? (d_hidden + 8 * VU - 1) / (8 * VU) : 1; }
 void launch_verifier_part(const float* hf, int d, int d_hidden, const float* w1, const float* b1, const float* w2,
                           const int* n_rows, float* part, int max_rows, hipStream_t s) {
   int chunks = verifier_num_chunks(d_hidden);
