@@ -463,7 +463,7 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
             for rho in (0.05, 0.25, 0.60):
                 x = summarise(timed(tau, rho, 4, n_x), n_x, tau)
                 sw.append({"tau": tau, "reject_rate_asked": rho, "reject_rate_achieved": x["target_calls_per_token"],
-                           "value": x["value"], "ms_per_step": x["ms_per_step"], "hbm_frac": x["roofline"]["frac"],
+                           "value": x["value"], "ms_per_step": x["ms_per_step"], "hbm_frac": float(x["roofline"]["frac"]),
                            "mfma_frac_of_ceiling": x["roofline"].get("mfma", {}).get("frac_of_ceiling")})
                 note(f"sweep {sw[-1]}")
         out["sweep"] = sw
