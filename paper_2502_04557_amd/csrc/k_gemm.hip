@@ -388,9 +388,13 @@ __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
 }
 
 // Launches k_gemm_wide if the row count calls for it and the activation buffer holds every row tile of the grid.
+// min_rows: 128 for outputs that need the whole K in one workgroup; 97 for partial products, where K shares bring the
+// workgroup count back up (c4's shapes at 100 rows: FFN-down 4096 x 11008 50.8 -> 42.2 us, O-proj 25.5 -> 18.3 us with one
+// 128-row group, while FFN-up and QKV, left with 86 - 96 workgroups, lose: 95 -> 115 us and 56 -> 77 us; at 72 - 88 rows
+// FFN-down loses too, 42 -> 46 us, against two passes of 3 row tiles).
 template <int EPI>
-static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s) {
-  if (max_rows < 128) return false;
+static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s, int min_rows = 128) {
+  if (max_rows < min_rows) return false;
   const int row_groups = (max_rows + 127) / 128;
   if ((size_t)row_groups * 128 * a.Kt * 32 > a.x_plane) return false;
   constexpr bool DUAL = EPI == EPI_SWIGLU;
@@ -626,7 +630,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
   // 17+ rows: the workgroup's activation traffic (2 KiB per k tile and 16 rows) is what costs, so a wave takes
   // four column tiles (two if that leaves too few workgroups) and K is split until about 256 workgroups exist,
   // with at least two k tiles per wave and share
-  if (max_rows >= 128) {           // 128+ rows: column-split workgroups, K shares until about 256 of them exist
+  if (max_rows >= 97) {            // 97+ rows: column-split workgroups, K shares until about 256 of them exist
     const int row_groups = (max_rows + 127) / 128, s_lim = std::max(1, std::min(max_shares, a.Kt / 16));
     // first with four column tiles per wave (the shares make up for the fewer column groups), then with two
     for (int per_group : {32, 16}) {
@@ -634,7 +638,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
       const int sk = std::max(1, std::min(s_lim, (256 + groups - 1) / groups));
       if (per_group == 32 && groups * sk < 160) continue;
       a.SK = sk;
-      if (try_gemm_wide<EPI_PART>(a, max_rows, sk, s)) return sk;
+      if (try_gemm_wide<EPI_PART>(a, max_rows, sk, s, 97)) return sk;
     }
   }
   const int row_tiles = (max_rows + 15) / 16;

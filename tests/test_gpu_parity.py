@@ -347,6 +347,34 @@ def test_prefill_matrix_core_kernels_mid_size(chunk_rows):
     p.close()
 
 
+def test_hundred_target_rows_column_split_partial_products():
+    """100 rows, all rejected (threshold above 1), through a target wide enough (d 2048, FFN 8192) that the partial-product
+    GEMMs of 97 - 127 rows take the column-split kernel with a single, partly filled 128-row group (FFN-down: 16 column
+    groups x 8 K shares), while QKV and FFN-up stay on the K-split kernels (two passes of 4 and 3 row tiles).  Target
+    logits and hidden states of every row against the oracle, two steps."""
+    from parity_util import compare_replay, close_enough, eps_of
+    draft = W.ModelCfg(W.ARCH_LLAMA, 1, 256, 4, 2, 512, 1201, 64, 1e-5, 10000.0)
+    target = W.ModelCfg(W.ARCH_LLAMA, 2, 2048, 16, 4, 8192, 1201, 64, 1e-5, 10000.0)
+    cfg = W.SprinterCfg(draft, target, 16, W.DT_BF16, 100, 16, tau=1.5, seed=91, name="hundred-rows", batch=100, prompt_len=6,
+                        prompt_len_min=2, n_gen=2, prompt_dist="zipf", weight_seed=601, prompt_seed=602)
+    p = _pair(cfg)
+    outs, st = p.gpu_steps(cfg.n_gen, debug=True)
+    g = {k: np.stack([o[k2] for o in outs], axis=1) for k, k2 in
+         (("tok", "committed_tok"), ("accept", "accept"), ("score", "score"), ("draft_tok", "draft_tok"))}
+    assert not g["accept"].any() and st["sum_rejected"] == 100 * cfg.n_gen
+    rec = p.oracle(cfg.n_gen, forced=dict(tok=g["tok"], accept=g["accept"]), keep_logits=True, whole_prompt_prefill=True)
+    rep = compare_replay(cfg, g, rec)
+    eps = eps_of(cfg)
+    worst = 0.0
+    for t, o in enumerate(outs):
+        assert rec["rejected"][t] == list(range(100))
+        assert close_enough(o["target_logits"][:100], rec["target_logits"][t], eps).all(), t
+        assert close_enough(o["target_hidden"][:100], rec["target_hidden"][t], eps).all(), t
+        worst = max(worst, float(np.abs(o["target_logits"][:100] - rec["target_logits"][t]).max()))
+    print("hundred rows", rep, "max target logit difference", worst, flush=True)
+    p.close()
+
+
 @pytest.mark.parametrize("ctx", [0, 1])
 def test_long_context_few_rows(ctx):
     """Contexts of 770-900 keys with 3 rows: the attention launch takes its 8-wave variant (few workgroups, long
