@@ -114,3 +114,18 @@ def test_algorithmic_flops_match_a_brute_force_count():
         want.append(float(total))
     got = bench.algorithmic_flops(cfg, plen, accept, first, seen.copy())
     assert np.allclose(got, want, rtol=1e-12)
+
+
+def test_shifted_bias_reaches_the_asked_reject_rate():
+    """The calibration moves the verifier's output bias so that the asked share of the calibration scores falls below
+    the threshold: recomputing the scores with the new bias must reject that share (up to the quantile's granularity)."""
+    rng = np.random.default_rng(3)
+    z = rng.normal(0.3, 0.8, size=(64, 32))                  # pre-bias logits of 32 calibration steps
+    b2_0 = -0.2
+    scores = (1.0 / (1.0 + np.exp(-(z + b2_0)))).astype(np.float32)
+    for tau in (0.3, 0.5, 0.7):
+        for rho in (0.05, 0.09, 0.25, 0.60):
+            b2 = W.shifted_bias(scores, b2_0, tau, rho)
+            new = 1.0 / (1.0 + np.exp(-(z + b2)))
+            assert abs((new < tau).mean() - rho) < 2e-3, (tau, rho)
+    assert abs(W.logit(0.5)) < 1e-12 and abs(W.logit(0.7) - np.log(0.7 / 0.3)) < 1e-12
