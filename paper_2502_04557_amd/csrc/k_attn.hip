@@ -213,15 +213,46 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_dec_bf16(AttnArgs a) {
   __shared__ float s_ml[NW][GMAX][2];
   __shared__ float s_o[NW][GMAX][DH];
   const int r = blockIdx.y;
-  if (r >= *a.rd.n_rows) return;
   const int kvh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = wave_index();
   const int l16 = lane & 15, lq = lane >> 4, G = a.H / a.KVH;
+  // What depends on the row index alone is requested first, before the row count and the row's descriptor are
+  // known (the projection buffer holds every row the grid covers): the new value per column (every wave), and for
+  // wave t < T the 32-column piece t of the query heads and of the new key with their rotary partners and angles.
+  // The G query heads form one operand (row l16 = head min(l16, G - 1): rows beyond G repeat the last head and are
+  // ignored).  Spread over T waves the preparation is a quarter of the arithmetic per wave and its loads overlap
+  // the descriptor's round trips (one wave doing all of it after the descriptor took 3.4 of c2's 7.4 us).
+  const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
+  const float* __restrict__ rp = a.rope + (size_t)r * DH;
+  const float* __restrict__ yq = y + (size_t)(kvh * G + min(l16, G - 1)) * DH;
+  const float* __restrict__ yk = y + (size_t)(a.H + kvh) * DH;
+  const float* __restrict__ yv = y + (size_t)(a.H + a.KVH + kvh) * DH;
+  float vraw[CT];
+#pragma unroll
+  for (int ct = 0; ct < CT; ++ct) vraw[ct] = yv[ct * 16 + l16];
+  const int tq = min(w, T - 1);                                  // this wave's piece (waves beyond T repeat the last one and drop it)
+  const int d0 = tq * 32 + lq * 8, p0 = d0 ^ HALF;
+  float x[8], xp[8], kx[8], kp[8], cs[16];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const float4 u = reinterpret_cast<const float4*>(yq + d0)[i], v = reinterpret_cast<const float4*>(yq + p0)[i];
+    const float4 ku = reinterpret_cast<const float4*>(yk + d0)[i], kv = reinterpret_cast<const float4*>(yk + p0)[i];
+    x[4 * i] = u.x; x[4 * i + 1] = u.y; x[4 * i + 2] = u.z; x[4 * i + 3] = u.w;
+    xp[4 * i] = v.x; xp[4 * i + 1] = v.y; xp[4 * i + 2] = v.z; xp[4 * i + 3] = v.w;
+    kx[4 * i] = ku.x; kx[4 * i + 1] = ku.y; kx[4 * i + 2] = ku.z; kx[4 * i + 3] = ku.w;
+    kp[4 * i] = kv.x; kp[4 * i + 1] = kv.y; kp[4 * i + 2] = kv.z; kp[4 * i + 3] = kv.w;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float4 u = reinterpret_cast<const float4*>(rp + 2 * (d0 % HALF))[i];
+    cs[4 * i] = u.x; cs[4 * i + 1] = u.y; cs[4 * i + 2] = u.z; cs[4 * i + 3] = u.w;
+  }
+  if (r >= *a.rd.n_rows) return;
   const int b = a.rd.b[r], slot = a.rd.slot[r], S = a.max_seq;
   bf16_t* __restrict__ Kc = (bf16_t*)a.kcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   bf16_t* __restrict__ Vc = (bf16_t*)a.vcache + a.layer_off + ((size_t)b * a.KVH + kvh) * (size_t)S * DH;
   const int n_steps = (slot + 32 * NW) / (32 * NW);             // blocks 0 .. slot / 32, NW per step
   // Two register buffers: a block's key fragments and value tiles are requested a whole step ahead (the query
-  // operand lives in LDS to make room for them).  Addresses are clamped into the cache.
+  // operand lives in LDS to make room for them).
   // A block beyond the row's last one is read at the last one's address (scalar clamp) and fully masked; inside a
   // block nothing is clamped: the caches hold a multiple of 32 slots per (row, KV head), so every key of a block
   // that exists lies inside the cache.  Per-lane base addresses once, block offsets are scalars.
@@ -240,38 +271,8 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_dec_bf16(AttnArgs a) {
   };
   Blk A, B;
   fetch(A, w * 32);
-  // The query heads as one operand (row l16 = head min(l16, G - 1): rows beyond G repeat the last head and are
-  // ignored), the new key as operand pieces, the new value per column: unconditional loads first, then arithmetic.
-  const float* __restrict__ y = a.y + (size_t)r * a.dqkv;
-  const float* __restrict__ rp = a.rope + (size_t)r * DH;
-  const float* __restrict__ yq = y + (size_t)(kvh * G + min(l16, G - 1)) * DH;
-  const float* __restrict__ yk = y + (size_t)(a.H + kvh) * DH;
-  const float* __restrict__ yv = y + (size_t)(a.H + a.KVH + kvh) * DH;
-  float vraw[CT];
-#pragma unroll
-  for (int ct = 0; ct < CT; ++ct) vraw[ct] = yv[ct * 16 + l16];
-  if (w == 0) {                                                  // (scalar) one wave prepares the query operand and the new key
-  u32x4 knew[T];
-  uint4 qh[T], ql[T];
-#pragma unroll
-  for (int t = 0; t < T; ++t) {
-    const int d0 = t * 32 + lq * 8, p0 = d0 ^ HALF;
+  {
     const bool upper = d0 >= HALF;
-    float x[8], xp[8], kx[8], kp[8], cs[16];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const float4 u = reinterpret_cast<const float4*>(yq + d0)[i], v = reinterpret_cast<const float4*>(yq + p0)[i];
-      const float4 ku = reinterpret_cast<const float4*>(yk + d0)[i], kv = reinterpret_cast<const float4*>(yk + p0)[i];
-      x[4 * i] = u.x; x[4 * i + 1] = u.y; x[4 * i + 2] = u.z; x[4 * i + 3] = u.w;
-      xp[4 * i] = v.x; xp[4 * i + 1] = v.y; xp[4 * i + 2] = v.z; xp[4 * i + 3] = v.w;
-      kx[4 * i] = ku.x; kx[4 * i + 1] = ku.y; kx[4 * i + 2] = ku.z; kx[4 * i + 3] = ku.w;
-      kp[4 * i] = kv.x; kp[4 * i + 1] = kv.y; kp[4 * i + 2] = kv.z; kp[4 * i + 3] = kv.w;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float4 u = reinterpret_cast<const float4*>(rp + 2 * (d0 % HALF))[i];
-      cs[4 * i] = u.x; cs[4 * i + 1] = u.y; cs[4 * i + 2] = u.z; cs[4 * i + 3] = u.w;
-    }
     float qv[8], kn[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -279,24 +280,24 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_dec_bf16(AttnArgs a) {
       qv[i] = (upper ? x[i] * c + xp[i] * sn : x[i] * c - xp[i] * sn) * a.scale;
       kn[i] = upper ? kx[i] * c + kp[i] * sn : kx[i] * c - kp[i] * sn;
     }
-    split2(qv[0], qv[1], qh[t].x, ql[t].x);
-    split2(qv[2], qv[3], qh[t].y, ql[t].y);
-    split2(qv[4], qv[5], qh[t].z, ql[t].z);
-    split2(qv[6], qv[7], qh[t].w, ql[t].w);
-    knew[t].x = (unsigned)f2bf(kn[0]) | ((unsigned)f2bf(kn[1]) << 16);
-    knew[t].y = (unsigned)f2bf(kn[2]) | ((unsigned)f2bf(kn[3]) << 16);
-    knew[t].z = (unsigned)f2bf(kn[4]) | ((unsigned)f2bf(kn[5]) << 16);
-    knew[t].w = (unsigned)f2bf(kn[6]) | ((unsigned)f2bf(kn[7]) << 16);
-  }
-#pragma unroll
-  for (int t = 0; t < T; ++t) { lds_q[0][t][lane] = qh[t]; lds_q[1][t][lane] = ql[t]; }   // hi, lo planes, for every wave
-  if (l16 == 0) {                                      // the new key: into LDS for the row's last block, and into the cache
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-      *reinterpret_cast<u32x4*>(lds_kn + t * 32 + lq * 8) = knew[t];
-      if (a.phase != 2) *reinterpret_cast<u32x4*>(Kc + (size_t)slot * DH + t * 32 + lq * 8) = knew[t];
+    uint4 qh, ql;
+    u32x4 knew;
+    split2(qv[0], qv[1], qh.x, ql.x);
+    split2(qv[2], qv[3], qh.y, ql.y);
+    split2(qv[4], qv[5], qh.z, ql.z);
+    split2(qv[6], qv[7], qh.w, ql.w);
+    knew.x = (unsigned)f2bf(kn[0]) | ((unsigned)f2bf(kn[1]) << 16);
+    knew.y = (unsigned)f2bf(kn[2]) | ((unsigned)f2bf(kn[3]) << 16);
+    knew.z = (unsigned)f2bf(kn[4]) | ((unsigned)f2bf(kn[5]) << 16);
+    knew.w = (unsigned)f2bf(kn[6]) | ((unsigned)f2bf(kn[7]) << 16);
+    if (w < T) {                                                 // (scalar)
+      lds_q[0][tq][lane] = qh;                                   // hi, lo planes of the query operand, for every wave
+      lds_q[1][tq][lane] = ql;
+      if (l16 == 0) {                                            // the new key: into LDS for the row's last block, and into the cache
+        *reinterpret_cast<u32x4*>(lds_kn + d0) = knew;
+        if (a.phase != 2) *reinterpret_cast<u32x4*>(Kc + (size_t)slot * DH + d0) = knew;
+      }
     }
-  }
   }
   unsigned vnew[CT / 2];                                         // the new value of columns ct * 16 + l16 as bf16 bits, two per register
 #pragma unroll
