@@ -204,7 +204,8 @@ int sprinter_create_static(const sprinter_cfg* cfg, void* hip_stream, sprinter_c
  * (enqueued on the stream; the originals may be freed once the stream has passed
  * this point), except the embedding tables, which are read in place; every other
  * tensor is BORROWED and must stay valid for the life of the context.  The call
- * fails if a name is unknown, a shape is wrong, or a tensor of the model is absent. */
+ * fails if a name is unknown, a shape is wrong, a pointer is not 16-byte aligned,
+ * or a tensor of the model is absent. */
 int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names,
                           const void* const* dev_ptrs, const int64_t* shapes, int n);
 

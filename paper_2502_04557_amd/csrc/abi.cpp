@@ -710,6 +710,8 @@ int sprinter_load_weights(sprinter_ctx* ctx, int which, const char* const* names
       return fail(ctx, SPRINTER_E_WEIGHTS, "%s: tensor '%s' has shape [%lld,%lld,%lld,%lld], expected [%lld,%lld]", who,
                   names[i], (long long)sh[0], (long long)sh[1], (long long)sh[2], (long long)sh[3], (long long)e.rows,
                   (long long)e.cols);
+    if (((uintptr_t)dev_ptrs[i]) & 15)   // the kernels read borrowed tensors with 16-byte loads
+      return fail(ctx, SPRINTER_E_WEIGHTS, "%s: tensor '%s' is not 16-byte aligned", who, names[i]);
     if (seen[it->second]) return fail(ctx, SPRINTER_E_WEIGHTS, "%s: tensor '%s' given twice", who, names[i]);
     seen[it->second] = 1;
     hit[i] = it->second;

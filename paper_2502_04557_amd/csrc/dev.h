@@ -106,10 +106,11 @@ __device__ __forceinline__ float block_max256(float v, float* s4) {
 
 // ------------------------------------------------- Philox4x32-10 + Gumbel
 // Counter-based generator of Salmon et al. (SC'11).  key = seed, counter =
-// (vocab index / 4, position, row, stream); word (vocab index % 4) of the block.
-__device__ __forceinline__ unsigned philox_word(unsigned k0, unsigned k1, unsigned stream, unsigned b,
-                                                unsigned t, unsigned v) {
-  unsigned c0 = v >> 2, c1 = t, c2 = b, c3 = stream;
+// (vocab index / 4, position, row, stream); word (vocab index % 4) of the block.  philox_block: the whole block of
+// four words (vocabulary indices 4 c0 .. 4 c0 + 3 of one row and position).
+__device__ __forceinline__ uint4 philox_block(unsigned k0, unsigned k1, unsigned stream, unsigned b, unsigned t,
+                                              unsigned c0) {
+  unsigned c1 = t, c2 = b, c3 = stream;
 #pragma unroll
   for (int r = 0; r < 10; ++r) {
     unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
@@ -118,8 +119,13 @@ __device__ __forceinline__ unsigned philox_word(unsigned k0, unsigned k1, unsign
     c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
     k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
   }
-  unsigned sel = v & 3u;
-  return sel == 0 ? c0 : sel == 1 ? c1 : sel == 2 ? c2 : c3;
+  return make_uint4(c0, c1, c2, c3);
+}
+__device__ __forceinline__ unsigned philox_word(unsigned k0, unsigned k1, unsigned stream, unsigned b,
+                                                unsigned t, unsigned v) {
+  const uint4 c = philox_block(k0, k1, stream, b, t, v >> 2);
+  const unsigned sel = v & 3u;
+  return sel == 0 ? c.x : sel == 1 ? c.y : sel == 2 ? c.z : c.w;
 }
 // u = ((word >> 9) + 0.5) * 2^-23 is exact in float32 and inside (0,1).
 __device__ __forceinline__ float gumbel_from_word(unsigned w) {
@@ -151,6 +157,36 @@ __device__ __forceinline__ u64 sample_key(float logit, const SamplerArgs& sa, in
   return pack_key(y, (unsigned)n);
 }
 
+// Sampling keys of a matrix-core accumulator: register v of the lane is the logit of (row v of four, column n), and
+// the four lanes of a quad hold four consecutive columns 4 c .. 4 c + 3 of the same four rows, i.e. words 0 .. 3 of
+// the same four random blocks.  Lane q of the quad computes the block of row q (whose batch row and position the
+// caller passes as b_q, t_q) and the quad exchanges words through DPP broadcasts: one block per lane instead of
+// four - the integer multiplies of the generator are most of the sampling arithmetic.  Same words as sample_key.
+// All 64 lanes must be active.
+__device__ __forceinline__ void sample_keys_quad(f32x4 logit, const SamplerArgs& sa, int b_q, int t_q, int n, u64 (&key)[4]) {
+  if (!(sa.inv_temperature > 0.0f)) {                 // (uniform)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) key[v] = pack_key(logit[v], (unsigned)n);
+    return;
+  }
+  const uint4 blk = philox_block(sa.seed_lo, sa.seed_hi, sa.stream, (unsigned)b_q, (unsigned)t_q, (unsigned)n >> 2);
+  const int sel = n & 3;
+#define SPRINTER_QUAD_ROW(V, CTRL)                                                                     \
+  {                                                                                                    \
+    const unsigned x = (unsigned)__builtin_amdgcn_update_dpp(0, (int)blk.x, CTRL, 0xF, 0xF, true);     \
+    const unsigned y = (unsigned)__builtin_amdgcn_update_dpp(0, (int)blk.y, CTRL, 0xF, 0xF, true);     \
+    const unsigned z = (unsigned)__builtin_amdgcn_update_dpp(0, (int)blk.z, CTRL, 0xF, 0xF, true);     \
+    const unsigned w = (unsigned)__builtin_amdgcn_update_dpp(0, (int)blk.w, CTRL, 0xF, 0xF, true);     \
+    const unsigned word = sel == 0 ? x : sel == 1 ? y : sel == 2 ? z : w;                              \
+    key[V] = pack_key(logit[V] * sa.inv_temperature + gumbel_from_word(word), (unsigned)n);            \
+  }
+  SPRINTER_QUAD_ROW(0, 0x00)   // quad_perm [0,0,0,0]: the block lane 0 of the quad computed (row 0)
+  SPRINTER_QUAD_ROW(1, 0x55)   // [1,1,1,1]
+  SPRINTER_QUAD_ROW(2, 0xAA)   // [2,2,2,2]
+  SPRINTER_QUAD_ROW(3, 0xFF)   // [3,3,3,3]
+#undef SPRINTER_QUAD_ROW
+}
+
 // Sum over an aligned group of 8 or 16 consecutive lanes, the total in every lane of the group, through DPP
 // (quad permutes, then the half-row and row mirrors: after the quad steps every lane of a quad holds the quad's
 // sum, so any lane of the other half is a valid partner).  A ds_bpermute butterfly costs about 100 cycles per
@@ -172,6 +208,22 @@ __device__ __forceinline__ float group_max16(float v) {
   v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true)));
   v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true)));
   return v;
+}
+
+// Maximum of 64-bit keys over an aligned group of 16 consecutive lanes, in every lane of the group.
+__device__ __forceinline__ u64 group_umax64_16(u64 k) {
+#define SPRINTER_DPP_STEP(CTRL)                                                                              \
+  {                                                                                                          \
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)k, CTRL, 0xF, 0xF, true);    \
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(k >> 32), CTRL, 0xF, 0xF, true); \
+    k = umax64(k, ((u64)hi << 32) | lo);                                                                     \
+  }
+  SPRINTER_DPP_STEP(0xB1)    // quad_perm [1,0,3,2]
+  SPRINTER_DPP_STEP(0x4E)    // quad_perm [2,3,0,1]
+  SPRINTER_DPP_STEP(0x141)   // row_half_mirror
+  SPRINTER_DPP_STEP(0x140)   // row_mirror
+#undef SPRINTER_DPP_STEP
+  return k;
 }
 
 __device__ __forceinline__ f32x4 mfma_bf16(uint4 x, uint4 w, f32x4 c) {

@@ -21,6 +21,12 @@ __global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
   // of 64, a wave every 16th workgroup, so that a load covers 64 consecutive rows of one workgroup (512 contiguous
   // bytes; with a lane per workgroup every 8-byte load hit its own cache line: 37 us at 64 rows and 512 workgroups),
   // then the 16 waves' results meet in LDS.
+  float z = 0.f;                                     // the verifier's output logit: offset + the hidden chunks' shares, in order
+  if (tid < B) {                                     // (requested ahead of the merge below)
+    z = a.b2[0];
+#pragma unroll 8
+    for (int c = 0; c < a.n_chunks; ++c) z += a.ver_part[(size_t)c * B + tid];
+  }
   for (int rb = 0; rb < B; rb += 64) {
     const int m = rb + lane;
     u64 k = 0;
@@ -40,8 +46,6 @@ __global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
   float score = 0.f;
   bool acc = true;
   if (active) {
-    float z = a.b2[0];
-    for (int c = 0; c < a.n_chunks; ++c) z += a.ver_part[(size_t)c * B + tid];
     score = 1.0f / (1.0f + expf(-z));
     acc = score >= *a.tau_ptr;
   }

@@ -9,15 +9,14 @@ namespace sprinter {
 // ======================================================= LM head + sample
 struct LmArgs {
   const void* W; const void* X; RowDesc rd; int V, K, Kt, n_tiles;
-  SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_plane;
+  SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_plane; int m_tiles;
 };
 
-// bf16: each workgroup owns a contiguous range of column tiles; its 8 waves take pairs of adjacent tiles
-// round-robin (the two tiles share the activation fragments: at 16+ rows the activations, 2 KiB per k tile and
-// row tile from L2, outweigh the 1 KiB of weights), keep a running (value, index) maximum per row, and the
-// workgroup writes one partial per row.  The k loop has no branches: two register buffers, tiles and k tiles
-// beyond the end are clamped on load; columns beyond the vocabulary and rows beyond the row count are dropped
-// when the logits are sampled.  More than 16 MT rows take further passes over the workgroup's tiles.
+// bf16, at most 16 rows (launched with MT = 1): each workgroup owns a contiguous range of column tiles; its 8 waves
+// take pairs of adjacent tiles round-robin (the two tiles share the activation fragments), keep a running
+// (value, index) maximum per row, and the workgroup writes one partial per row.  The k loop has no branches: two
+// register buffers, tiles and k tiles beyond the end are clamped on load; columns beyond the vocabulary and rows
+// beyond the row count are dropped when the logits are sampled.
 template <int MT>
 __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
   __shared__ u64 sbest[8][MT * 16];
@@ -87,19 +86,24 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const int n = (nt + j) * 16 + (lane & 15);
-        if (nt + j < t1 && n < a.V) {
+        const bool col = nt + j < t1 && n < a.V;             // (no branches below: the quad exchange needs every lane)
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
+          if (a.logits_out) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-              int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
-              if (m < n_rows) {
-                float logit = acc[j][mt][v];
-                if (a.logits_out) a.logits_out[(size_t)m * a.V + n] = logit;
-                const int mi = mt * 16 + (lane >> 4) * 4 + v;
-                best[mt][v] = umax64(best[mt][v], sample_key(logit, a.sa, s_rb[mi], s_rt[mi], n));
-              }
+              const int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
+              if (col && m < n_rows) a.logits_out[(size_t)m * a.V + n] = acc[j][mt][v];
             }
+          }
+          const int mq = mt * 16 + (lane >> 4) * 4 + (lane & 3);   // the row whose random block this lane computes for its quad
+          u64 kj[4];
+          sample_keys_quad(acc[j][mt], a.sa, s_rb[mq], s_rt[mq], n, kj);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
+            best[mt][v] = umax64(best[mt][v], col && m < n_rows ? kj[v] : 0);
+          }
         }
       }
     }
@@ -112,6 +116,162 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
         for (int o = 1; o < 16; o <<= 1) k = umax64(k, shfl_xor_u64(k, o));
         if ((lane & 15) == 0) sbest[w][mt * 16 + (lane >> 4) * 4 + v] = k;
       }
+    __syncthreads();
+    for (int i = threadIdx.x; i < MT * 16; i += 512) {
+      u64 k = sbest[0][i];
+#pragma unroll
+      for (int q = 1; q < 8; ++q) k = umax64(k, sbest[q][i]);
+      if (m0 + i < a.Mpad) a.part[(size_t)blockIdx.x * a.Mpad + m0 + i] = k;
+    }
+    __syncthreads();
+  }
+}
+
+// bf16, 17+ rows: the 8 waves of a workgroup take different column tiles (NTW each, 8 NTW tiles per round over the
+// workgroup's tile range) and share the activations of MT row tiles through LDS, so a k tile costs the workgroup
+// MT * 2 KiB of activations once instead of once per wave - at 64 rows the per-wave reads above pull five times the
+// weight bytes through L2.  KS k tiles per stage, two LDS stages: the loads of stage c + 1 (the wave's weight tiles
+// and its share of the activation fragments, into registers) are in flight while the MFMAs of stage c run; one
+// barrier per stage.  NTW = 2 where the workgroup's range has more than 8 tiles (large vocabularies), else 1 so
+// that every wave has a tile.  Fragment f of a stage = (k tile f / (2 MT), plane (f / MT) % 2, row tile f % MT); wave w
+// stages fragments w, w + 8, ...  Tiles and k tiles beyond the end are clamped on load and dropped afterwards; row
+// tiles are clamped to the m_tiles the activation buffer holds.  More than 16 MT rows take further passes.
+template <int MT, int NTW, int KS>
+__global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) {
+  constexpr int NF = KS * 2 * MT, F = NF / 8;
+  static_assert(NF % 8 == 0, "every wave stages the same number of fragments");
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  __shared__ u32x4 xs[2][NF][64];
+  __shared__ u64 sbest[8][MT * 16];
+  __shared__ int s_rb[MT * 16], s_rt[MT * 16];
+  const int lane = threadIdx.x & 63, w = wave_index();
+  const int tpw = (a.n_tiles + gridDim.x - 1) / gridDim.x;
+  const int t0 = blockIdx.x * tpw, t1 = min(t0 + tpw, a.n_tiles);
+  const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
+  const int Kt = a.Kt;
+  const int n_rows = *a.rd.n_rows;
+  struct Regs { u32x4 x[F]; uint4 w[KS][NTW]; };
+  for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
+    const int mtile0 = m0 >> 4;
+    // running maximum per row: accumulator (row tile mt, register v) of DPP row lq is row mt * 16 + lq * 4 + v; after
+    // each round its 16 lanes (columns) are merged and lane l16 = (mt * 4 + v) % 16 keeps the result in slot
+    // (mt * 4 + v) / 16 - one or two keys per lane instead of 4 MT
+    constexpr int NB = (MT * 4 + 15) / 16;
+    u64 best[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) best[q] = 0;
+    for (int i = threadIdx.x; i < MT * 16; i += 512) {     // the rows' random streams: batch row, position being generated
+      s_rb[i] = m0 + i < n_rows ? a.rd.b[m0 + i] : 0;
+      s_rt[i] = m0 + i < n_rows ? a.rd.pos[m0 + i] + 1 : 0;
+    }
+    const u32x4* xsrc[F];                                    // this wave's fragments of a stage, at k tile 0
+    int xu[F];
+#pragma unroll
+    for (int i = 0; i < F; ++i) {
+      const int f = w + 8 * i, mt = f % MT, pl = (f / MT) & 1;
+      xu[i] = f / (2 * MT);
+      xsrc[i] = (const u32x4*)a.X + (size_t)pl * (a.x_plane / 8) + (size_t)min(mtile0 + mt, a.m_tiles - 1) * Kt * 64 + lane;
+    }
+    for (int c0 = t0; c0 < t1; c0 += 8 * NTW) {
+      const int nt = c0 + NTW * w;
+      size_t wrow[NTW];
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt + j, t1 - 1) * Kt * 64;
+      auto gload = [&](Regs& r, int kt) {
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
+          const int kc = min(kt + u, Kt - 1);
+#pragma unroll
+          for (int j = 0; j < NTW; ++j) r.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
+        }
+#pragma unroll
+        for (int i = 0; i < F; ++i) r.x[i] = xsrc[i][(size_t)min(kt + xu[i], Kt - 1) * 64];
+      };
+      auto sstore = [&](int stage, const Regs& r) {
+#pragma unroll
+        for (int i = 0; i < F; ++i) xs[stage][w + 8 * i][lane] = r.x[i];
+      };
+      f32x4 acc[NTW][MT];
+#pragma unroll
+      for (int j = 0; j < NTW; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      auto compute = [&](int stage, const Regs& r, int kt) {
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
+          const bool in_k = kt + u < Kt;
+          uint4 wv[NTW];
+#pragma unroll
+          for (int j = 0; j < NTW; ++j) wv[j] = in_k ? r.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 h = xs[stage][(u * 2) * MT + mt][lane], l = xs[stage][(u * 2 + 1) * MT + mt][lane];
+            const uint4 xh = make_uint4(h.x, h.y, h.z, h.w), xl = make_uint4(l.x, l.y, l.z, l.w);
+#pragma unroll
+            for (int j = 0; j < NTW; ++j) {
+              acc[j][mt] = mfma_bf16(xh, wv[j], acc[j][mt]);
+              acc[j][mt] = mfma_bf16(xl, wv[j], acc[j][mt]);
+            }
+          }
+        }
+      };
+      Regs A, B;
+      gload(A, 0);
+      sstore(0, A);                                          // (nobody reads stage 0 any more: the last barrier of the previous round)
+      __syncthreads();                                       // also orders s_rb / s_rt before the sampling below
+      for (int kt = 0; kt < Kt; kt += 2 * KS) {
+        gload(B, kt + KS);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(0, A, kt);
+        sstore(1, B);
+        __syncthreads();
+        gload(A, kt + 2 * KS);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(1, B, kt + KS);
+        sstore(0, A);
+        __syncthreads();
+      }
+      const int n0 = nt * 16 + (lane & 15);                  // tile j's column: n0 + 16 j
+      bool col[NTW];
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) col[j] = nt + j < t1 && n0 + 16 * j < a.V;
+      if (a.logits_out) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int m = m0 + mt * 16 + (lane >> 4) * 4 + v;
+#pragma unroll
+            for (int j = 0; j < NTW; ++j)
+              if (m < n_rows && col[j]) a.logits_out[(size_t)m * a.V + n0 + 16 * j] = acc[j][mt][v];
+          }
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int mq = mt * 16 + (lane >> 4) * 4 + (lane & 3);   // the row whose random block this lane computes for its quad
+        const int rb = s_rb[mq], rt = s_rt[mq];
+        u64 kv[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) {
+          u64 kj[4];
+          sample_keys_quad(acc[j][mt], a.sa, rb, rt, n0 + 16 * j, kj);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) kv[v] = umax64(kv[v], col[j] ? kj[v] : 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int mi = mt * 16 + (lane >> 4) * 4 + v, idx = mt * 4 + v;
+          const u64 k = group_umax64_16(m0 + mi < n_rows ? kv[v] : 0);
+          if ((lane & 15) == (idx & 15)) best[idx >> 4] = umax64(best[idx >> 4], k);
+        }
+        __builtin_amdgcn_sched_barrier(0);                   // one row tile's random streams at a time (registers)
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      const int idx = q * 16 + (lane & 15);                  // (row tile, register) this lane kept
+      if (idx < MT * 4) sbest[w][(idx >> 2) * 16 + (lane >> 4) * 4 + (idx & 3)] = best[q];
+    }
     __syncthreads();
     for (int i = threadIdx.x; i < MT * 16; i += 512) {
       u64 k = sbest[0][i];
@@ -184,33 +344,44 @@ void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, cons
   LmArgs a;
   a.x_plane = x_plane;
   a.W = W; a.X = X; a.rd = rd; a.V = V; a.K = K; a.Kt = (K + 31) / 32; a.n_tiles = (V + 15) / 16;
-  a.sa = sa; a.part = part; a.Mpad = Mpad; a.logits_out = logits_out;
+  a.sa = sa; a.part = part; a.Mpad = Mpad; a.logits_out = logits_out; a.m_tiles = 0;
   if (dtype == 0) {
     hipLaunchKernelGGL(k_lmhead_f32, dim3(n_wg), dim3(256), 0, s, a);
   } else if (max_rows <= 16) {
     hipLaunchKernelGGL(k_lmhead_bf16<1>, dim3(n_wg), dim3(512), 0, s, a);
-  } else if (max_rows <= 32) {
-    hipLaunchKernelGGL(k_lmhead_bf16<2>, dim3(n_wg), dim3(512), 0, s, a);
-  } else if (max_rows <= 48) {
-    hipLaunchKernelGGL(k_lmhead_bf16<3>, dim3(n_wg), dim3(512), 0, s, a);
-  } else {                                   // 4 row tiles per pass; more rows take further passes inside the kernel
-    hipLaunchKernelGGL(k_lmhead_bf16<4>, dim3(n_wg), dim3(512), 0, s, a);
+  } else {
+    a.m_tiles = (int)(x_plane / ((size_t)a.Kt * 512));      // row tiles the activation buffer holds
+    const int tpw = (a.n_tiles + n_wg - 1) / n_wg;           // tiles per workgroup
+#define SPRINTER_LM(MT, KS1, KS2)                                                                       \
+  do {                                                                                                  \
+    if (tpw <= 8) hipLaunchKernelGGL((k_lmhead_wide<MT, 1, KS1>), dim3(n_wg), dim3(512), 0, s, a);      \
+    else hipLaunchKernelGGL((k_lmhead_wide<MT, 2, KS2>), dim3(n_wg), dim3(512), 0, s, a);               \
+  } while (0)
+    if (max_rows <= 32) SPRINTER_LM(2, 2, 2);
+    else if (max_rows <= 64) SPRINTER_LM(4, 2, 2);
+    else SPRINTER_LM(8, 2, 1);                               // more than 128 rows: further passes inside the kernel
+#undef SPRINTER_LM
   }
 }
 
 // =============================================================== verifier
-// Hidden layer of the verifier MLP, spread over workgroups of 8 waves (VU hidden
-// units per wave); each workgroup leaves its share of the output logit per row.
-// d_hidden == 0: the logit is w2 . hf (a single chunk).
-constexpr int VU = 4;
+// Hidden layer of the verifier MLP (Sec. 3.2; the paper's single linear layer when d_hidden == 0) in float32.
+// With a hidden layer it is a small matrix product, hidden = relu(hf W1^T + b1), done on the float32 matrix
+// pipes: a workgroup owns 16 rows x 16 hidden units, its 8 waves split K; lane (l16, lq) holds four consecutive k of
+// row l16 and of unit l16 per 16-byte load, and the four 16x16x4 products of a load take k = 4 lq + 0 .. 3 (any
+// assignment of k to products is a valid order of the sum as long as both operands use the same one).  The waves'
+// accumulators are added in fixed order through LDS, then relu(. + b1) * w2 is summed over the 16 units and the
+// workgroup leaves its share of each row's output logit in part[chunk][row]; the consumer adds the chunks in order.
+// (One wave per hidden unit re-read the whole hidden-state matrix per wave - 268 MB through L2 at d = 2048,
+// 512 units and 64 rows, 81 us; this form reads 32 MB.)
 __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__ hf, int d, int d_hidden,
                                                        const float* __restrict__ w1, const float* __restrict__ b1,
                                                        const float* __restrict__ w2, const int* __restrict__ n_rows_p,
                                                        float* __restrict__ part, int max_rows) {
-  extern __shared__ float contrib[];   // [8][max_rows]
+  __shared__ float red[8][4][64];
   const int n_rows = *n_rows_p;
   const int lane = threadIdx.x & 63, w = wave_index();
-  if (d_hidden == 0) {
+  if (d_hidden == 0) {                               // (one workgroup)
     for (int m = w; m < n_rows; m += 8) {
       float acc = 0.f;
       for (int k = lane; k < d; k += 64) acc += w2[k] * hf[(size_t)m * d + k];
@@ -219,67 +390,51 @@ __global__ __launch_bounds__(512) void k_verifier_part(const float* __restrict__
     }
     return;
   }
-  // VU hidden units per wave: their weight rows stay in registers (2048 columns at a time), the rows of the batch
-  // go four at a time so that their loads and reductions overlap.  Every wave reads the whole hidden-state matrix
-  // (from L2), so the units per wave set that traffic: with one unit per wave 512 waves re-read 0.5 MB each at
-  // d = 2048 and 64 rows (81 us); with four it is a quarter of that.
-  const int j0 = (blockIdx.x * 8 + w) * VU;
-  float bj[VU], w2j[VU];
+  const int m0 = blockIdx.y * 16;
+  if (m0 >= n_rows) return;
+  const int l16 = lane & 15, lq = lane >> 4, j = blockIdx.x * 16 + l16;
+  // rows beyond the row count and units beyond the layer are read at the last valid one and dropped below
+  const float4* __restrict__ hrow = reinterpret_cast<const float4*>(hf + (size_t)min(m0 + l16, n_rows - 1) * d) + lq;
+  const float4* __restrict__ wrow = reinterpret_cast<const float4*>(w1 + (size_t)min(j, d_hidden - 1) * d) + lq;
+  const int n16 = d >> 4, g0 = n16 * w / 8, g1 = n16 * (w + 1) / 8;   // this wave's groups of 16 k (d is a multiple of 16)
+  f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int g = g0; g < g1; g += 8) {
+    float4 av[8], bv[8];
 #pragma unroll
-  for (int u = 0; u < VU; ++u) {
-    const bool unit = j0 + u < d_hidden;
-    bj[u] = unit ? b1[j0 + u] : 0.f;
-    w2j[u] = unit ? w2[j0 + u] : 0.f;              // (a unit beyond the layer contributes relu(0) * 0)
-  }
-  for (int m0 = 0; m0 < n_rows; m0 += 4) {
-    float acc[VU][4];
-#pragma unroll
-    for (int u = 0; u < VU; ++u)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[u][r] = 0.f;
-    for (int kc = 0; kc < d; kc += 2048) {
-      float wreg[VU][32];
-#pragma unroll
-      for (int u = 0; u < VU; ++u)
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-          const int k = kc + lane + 64 * i;
-          wreg[u][i] = (j0 + u < d_hidden && k < d) ? w1[(size_t)(j0 + u) * d + k] : 0.f;
-        }
-#pragma unroll
-      for (int i = 0; i < 32; ++i) {
-        const int k = min(kc + lane + 64 * i, d - 1);
-        float h[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) h[r] = hf[(size_t)min(m0 + r, n_rows - 1) * d + k];
-#pragma unroll
-        for (int u = 0; u < VU; ++u)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) acc[u][r] += wreg[u][i] * h[r];
-      }
+    for (int i = 0; i < 8; ++i) {
+      const int gi = min(g + i, g1 - 1);
+      av[i] = hrow[gi * 4];
+      bv[i] = wrow[gi * 4];
     }
+    __builtin_amdgcn_sched_barrier(0);               // all sixteen loads go out before the first product waits
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float t = 0.f;
-#pragma unroll
-      for (int u = 0; u < VU; ++u) t += fmaxf(wave_sum(acc[u][r]) + bj[u], 0.f) * w2j[u];
-      if (lane == 0 && m0 + r < n_rows) contrib[w * max_rows + m0 + r] = t;
+    for (int i = 0; i < 8; ++i) {
+      const bool on = g + i < g1;                    // (scalar) a group beyond the share contributes zeros
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i].x, on ? bv[i].x : 0.f, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i].y, on ? bv[i].y : 0.f, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i].z, on ? bv[i].z : 0.f, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i].w, on ? bv[i].w : 0.f, acc, 0, 0, 0);
     }
   }
+#pragma unroll
+  for (int v = 0; v < 4; ++v) red[w][v][lane] = acc[v];
   __syncthreads();
-  for (int m = threadIdx.x; m < n_rows; m += 512) {
-    float sacc = 0.f;
+  if (w < 4) {                                       // wave v finishes accumulator register v: row m0 + lq * 4 + v, unit j
+    float sum = 0.f;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) sacc += contrib[q * max_rows + m];
-    part[(size_t)blockIdx.x * max_rows + m] = sacc;
+    for (int q = 0; q < 8; ++q) sum += red[q][w][lane];
+    const bool unit = j < d_hidden;
+    const float t = unit ? fmaxf(sum + b1[min(j, d_hidden - 1)], 0.f) * w2[min(j, d_hidden - 1)] : 0.f;
+    const float tot = group_sum<16>(t);
+    const int m = m0 + lq * 4 + w;
+    if (l16 == 0 && m < n_rows) part[(size_t)blockIdx.x * max_rows + m] = tot;
   }
 }
-int verifier_num_chunks(int d_hidden) { return d_hidden > 0 ? (d_hidden + 8 * VU - 1) / (8 * VU) : 1; }
+int verifier_num_chunks(int d_hidden) { return d_hidden > 0 ? (d_hidden + 15) / 16 : 1; }
 void launch_verifier_part(const float* hf, int d, int d_hidden, const float* w1, const float* b1, const float* w2,
                           const int* n_rows, float* part, int max_rows, hipStream_t s) {
-  int chunks = verifier_num_chunks(d_hidden);
-  hipLaunchKernelGGL(k_verifier_part, dim3(chunks), dim3(512), (size_t)8 * max_rows * sizeof(float), s, hf, d,
-                     d_hidden, w1, b1, w2, n_rows, part, max_rows);
+  const dim3 grid = d_hidden > 0 ? dim3(verifier_num_chunks(d_hidden), (max_rows + 15) / 16) : dim3(1);
+  hipLaunchKernelGGL(k_verifier_part, grid, dim3(512), 0, s, hf, d, d_hidden, w1, b1, w2, n_rows, part, max_rows);
 }
 
 }  // namespace sprinter

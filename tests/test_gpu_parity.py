@@ -236,6 +236,13 @@ def test_error_paths():
     bad = dict(dw); bad["nonsense"] = bad["l0.wo"]
     with pytest.raises(binding.SprinterError):
         s.load_weights(binding.DRAFT, bad)
+    import torch
+    k1 = next(k for k, v in dw.items() if v.ndim == 1)       # a device tensor that starts 4 bytes into its allocation
+    flat = torch.zeros(dw[k1].size + 1, dtype=torch.float32, device=s.device)
+    bad = dict(dw); bad[k1] = flat[1:]
+    with pytest.raises(binding.SprinterError) as e:
+        s.load_weights(binding.DRAFT, bad)
+    assert e.value.code == -4 and "aligned" in str(e.value)
     s.load_weights(binding.DRAFT, dw); s.load_weights(binding.TARGET, tw); s.load_weights(binding.VERIFIER, vw)
     with pytest.raises(binding.SprinterError) as e:          # step before prefill
         s.step()
