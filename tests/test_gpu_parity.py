@@ -319,6 +319,26 @@ def test_random_shapes(seed):
     p.close()
 
 
+def test_large_vocabulary_many_rows():
+    """A vocabulary of more than 65536 entries (over 8 column tiles per LM-head workgroup, a pair per wave, last
+    tile ragged) with 80 rows: the LM head variant with 8 row tiles and two column tiles per wave, which the five
+    benchmark shapes never reach (c5 has the vocabulary but 64 rows, c4 the rows but 32000 entries); the target
+    pass takes the 2- and 4-row-tile variants on the same vocabulary.  Every row replayed."""
+    from parity_util import compare_replay
+    V, B, G = 66003, 80, 4
+    cfg = W.SprinterCfg(W.ModelCfg(W.ARCH_LLAMA, 1, 128, 2, 1, 192, V, 32, 1e-5, 10000.0),
+                        W.ModelCfg(W.ARCH_GPT, 1, 64, 1, 1, 128, V, 32), 24, W.DT_BF16, B, 32, seed=91,
+                        name="large-vocab", batch=B, prompt_len=6, prompt_len_min=2, n_gen=G, prompt_dist="uniform",
+                        weight_seed=92, prompt_seed=93)
+    p = _pair(cfg, ver_scale=8.0)
+    g, st = p.gpu_generate(G)
+    rej = (g["accept"] == 0).sum(0)
+    assert rej.max() > 16, rej                                # the target pass leaves the 16-row LM head too
+    rec = p.oracle(G, forced=dict(tok=g["tok"], accept=g["accept"], draft_tok=g["draft_tok"]))
+    print("large vocabulary", rej, compare_replay(cfg, g, rec), flush=True)
+    p.close()
+
+
 @pytest.mark.parametrize("chunk_rows", [0, 256])
 def test_prefill_matrix_core_kernels_mid_size(chunk_rows):
     """A prompt set large enough (9 ragged prompts, about 600 tokens) and models wide enough that prefill takes the
