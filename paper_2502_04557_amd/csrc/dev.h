@@ -144,7 +144,16 @@ __device__ __forceinline__ int key_index(u64 k) { return (int)(0xFFFFFFFFu - (un
 // Largest key of row m over the per-workgroup partial results part[n_wg][Mpad] (all 64 lanes get it).
 __device__ __forceinline__ u64 merge_partials(const u64* part, int n_wg, int Mpad, int m, int lane) {
   u64 k = 0;
-  for (int i = lane; i < n_wg; i += 64) k = umax64(k, part[(size_t)i * Mpad + m]);
+  for (int i0 = lane; i0 < n_wg; i0 += 256) {                  // four loads in flight per lane
+    u64 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + 64 * u;
+      v[u] = i < n_wg ? part[(size_t)i * Mpad + m] : 0;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) k = umax64(k, v[u]);
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) k = umax64(k, shfl_xor_u64(k, o));
   return k;

@@ -31,7 +31,16 @@ __global__ __launch_bounds__(1024) void k_draft_decide(DecideArgs a) {
     const int m = rb + lane;
     u64 k = 0;
     if (m < B)
-      for (int i = w; i < a.n_lm_wg; i += 16) k = umax64(k, a.am_part[(size_t)i * a.Mpad + m]);
+      for (int i0 = w; i0 < a.n_lm_wg; i0 += 128) {            // eight loads in flight per lane, not a chain of single ones
+        u64 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int i = i0 + 16 * u;
+          v[u] = i < a.n_lm_wg ? a.am_part[(size_t)i * a.Mpad + m] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) k = umax64(k, v[u]);
+      }
     s_key[w][lane] = k;
     __syncthreads();
     if (w == 0 && m < B) {
