@@ -465,7 +465,7 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
                 sw.append({"tau": tau, "reject_rate_asked": rho, "reject_rate_achieved": x["target_calls_per_token"],
                            "value": x["value"], "ms_per_step": x["ms_per_step"], "hbm_frac": float(x["roofline"]["frac"]),
                            "mfma_frac_of_ceiling": x["roofline"].get("mfma", {}).get("frac_of_ceiling")})
-                note(f"sweep {sw[-1]}")
+                note("sweep " + json.dumps({k: (round(float(v), 4) if v is not None else None) for k, v in sw[-1].items()}))
         out["sweep"] = sw
     s.close()
     del s
