@@ -14,6 +14,7 @@ struct GemmArgs {
   size_t x_plane;     // elements between the hi and lo planes of X (bf16 mode)
   size_t out_plane;   // same for out_act
   int SK; float* part; size_t part_stride;   // k_gemm16_part: K shares, partial outputs [SK][rows][N], floats per share
+  int rows_live;      // the host's bound on the row count: rows from here on exist in no launch, their activations are not fetched
 };
 
 // bias: the column's bias (0 if none); res: the current value of the output element (residual epilogue only)
@@ -64,13 +65,21 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
       }
     }
   };
+  // A lane holds 8 k of row lane % 16: lanes of rows the host knows not to exist skip their loads (a step with 3
+  // rejected rows then pulls 3/16 of the activation bytes through the compute unit's memory pipeline, which carries
+  // them next to the weight stream); what their registers hold only reaches output rows that are dropped.
+  const bool row_live = (lane & 15) < a.rows_live;
   uint4 xv[U], xl[U];
-  auto load_x = [&](int kt) {                               // row tile 0 always exists: no dependence on the row count
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kc = min(kt + u * 8, Kt - 1);
-      xv[u] = Xp[(size_t)kc * 64 + lane];
-      xl[u] = Xl[(size_t)kc * 64 + lane];
+  for (int u = 0; u < U; ++u) xv[u] = xl[u] = make_uint4(0u, 0u, 0u, 0u);
+  auto load_x = [&](int kt) {                               // no dependence on the (device-side) row count
+    if (row_live) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int kc = min(kt + u * 8, Kt - 1);
+        xv[u] = Xp[(size_t)kc * 64 + lane];
+        xl[u] = Xl[(size_t)kc * 64 + lane];
+      }
     }
   };
   load_weights(min(kw, Kt - 1));
@@ -161,6 +170,11 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
 #pragma unroll
   for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt0 + j, a.n_tiles - 1) * Kt * 64;
   struct Buf { uint4 w[U][NWT], xh[U][MT], xl[U][MT]; };
+  // (as in k_gemm16: a lane whose row exists in no launch - the host's bound - skips its activation loads; with 18
+  // rows the second row tile costs an eighth of its bytes)
+  bool row_live[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) row_live[mt] = (mtile0 + mt) * 16 + (lane & 15) < a.rows_live;
   auto load = [&](Buf& b, int kt) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -170,10 +184,16 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
         b.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
         if (DUAL) b.w[u][NTW + j] = W2p[wrow[j] + (size_t)kc * 64];
       }
+    }
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        b.xh[u][mt] = Xp[((size_t)mt * Kt + kc) * 64];
-        b.xl[u][mt] = Xl[((size_t)mt * Kt + kc) * 64];
+    for (int mt = 0; mt < MT; ++mt) {
+      if (row_live[mt]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int kc = min(kt + u * 8, k1 - 1);
+          b.xh[u][mt] = Xp[((size_t)mt * Kt + kc) * 64];
+          b.xl[u][mt] = Xl[((size_t)mt * Kt + kc) * 64];
+        }
       }
     }
   };
@@ -198,6 +218,10 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
     }
   };
   Buf A, B;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) A.xh[u][mt] = A.xl[u][mt] = B.xh[u][mt] = B.xl[u][mt] = make_uint4(0u, 0u, 0u, 0u);
   load(A, min(k0 + kw, k1 - 1));
   const int n_rows = *a.n_rows;                               // only the epilogue needs it (passes are sized by the host)
   // (the scheduling barriers keep the compiler from sinking a buffer's loads down to their first use)
@@ -451,13 +475,18 @@ __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
       for (int j = 0; j < NTW; ++j) wv[u][j] = Wp[((size_t)min(nt0 + j, a.n_tiles - 1) * Kt + kc) * 64 + lane];
     }
   };
+  const bool row_live = (lane & 15) < a.rows_live;            // (as in k_gemm16: rows that exist in no launch are not fetched)
   uint4 xv[U], xl[U];
-  auto load_x = [&](int kt) {                                 // row tile 0 always exists
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kc = min(kt + u * 8, k1 - 1);
-      xv[u] = Xp[(size_t)kc * 64 + lane];
-      xl[u] = Xl[(size_t)kc * 64 + lane];
+  for (int u = 0; u < U; ++u) xv[u] = xl[u] = make_uint4(0u, 0u, 0u, 0u);
+  auto load_x = [&](int kt) {
+    if (row_live) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int kc = min(kt + u * 8, k1 - 1);
+        xv[u] = Xp[(size_t)kc * 64 + lane];
+        xl[u] = Xl[(size_t)kc * 64 + lane];
+      }
     }
   };
   load_weights(min(k0 + kw, k1 - 1));
@@ -588,7 +617,7 @@ void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* 
   a.x_plane = x_plane; a.out_plane = out_plane;
   a.W = W; a.W2 = W2; a.X = X; a.n_rows = n_rows; a.N = N; a.K = K;
   a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16;
-  a.bias = bias; a.out_f32 = out_f32; a.ldo = ldo; a.out_act = out_act; a.out_K = out_K;
+  a.bias = bias; a.out_f32 = out_f32; a.ldo = ldo; a.out_act = out_act; a.out_K = out_K; a.rows_live = max_rows;
   if (dtype == 0) {
     dim3 grid((N + 3) / 4), block(256);
     switch (epi) {
@@ -613,7 +642,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_
   memset(&a, 0, sizeof a);
   a.W = W; a.X = X; a.x_plane = x_plane; a.n_rows = n_rows; a.N = N; a.K = K;
   a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16; a.ldo = N;
-  a.part = part; a.part_stride = part_stride;
+  a.part = part; a.part_stride = part_stride; a.rows_live = max_rows;
   if (max_rows <= 16) {
     // shares: fill the 256 compute units, at least 12 k tiles per share; long K takes two column tiles per wave
     const bool two = a.Kt >= 192 && a.n_tiles >= 64;   // (4096x4096: 8.2 us with one tile, 10.5 with two; 4096x11008: 24.1 / 19.8)

@@ -10,6 +10,7 @@ namespace sprinter {
 struct LmArgs {
   const void* W; const void* X; RowDesc rd; int V, K, Kt, n_tiles;
   SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_plane; int m_tiles;
+  int rows_live;   // the host's bound on the row count: lanes of rows from here on skip their activation loads
 };
 
 // bf16, at most 16 rows (launched with MT = 1): each workgroup owns a contiguous range of column tiles; its 8 waves
@@ -49,9 +50,11 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
         b.w[0] = Wp[wrow0 + (size_t)kc * 64];
         b.w[1] = Wp[wrow1 + (size_t)kc * 64];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {                 // (row tiles beyond the rows hold old data: dropped below)
-          b.xh[mt] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64];
-          b.xl[mt] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64];
+        for (int mt = 0; mt < MT; ++mt) {                 // (a lane holds 8 k of one row: rows that exist in no launch are not fetched,
+          if (m0 + mt * 16 + (lane & 15) < a.rows_live) { //  what the registers hold for them only reaches logits that are dropped)
+            b.xh[mt] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64];
+            b.xl[mt] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64];
+          }
         }
       };
       f32x4 acc[2][MT];
@@ -72,6 +75,8 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
         }
       };
       Buf A, B;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) A.xh[mt] = A.xl[mt] = B.xh[mt] = B.xl[mt] = make_uint4(0u, 0u, 0u, 0u);
       load(A, 0);
       for (int kt = 0; kt < Kt; kt += 2) {
         load(B, kt + 1);
@@ -166,10 +171,12 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
     }
     const u32x4* xsrc[F];                                    // this wave's fragments of a stage, at k tile 0
     int xu[F];
+    bool xlive[F];                                           // (a lane stages 8 k of one row: rows that exist in no launch are not fetched)
 #pragma unroll
     for (int i = 0; i < F; ++i) {
       const int f = w + 8 * i, mt = f % MT, pl = (f / MT) & 1;
       xu[i] = f / (2 * MT);
+      xlive[i] = m0 + mt * 16 + (lane & 15) < a.rows_live;
       xsrc[i] = (const u32x4*)a.X + (size_t)pl * (a.x_plane / 8) + (size_t)min(mtile0 + mt, a.m_tiles - 1) * Kt * 64 + lane;
     }
     for (int c0 = t0; c0 < t1; c0 += 8 * NTW) {
@@ -185,7 +192,8 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
           for (int j = 0; j < NTW; ++j) r.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
         }
 #pragma unroll
-        for (int i = 0; i < F; ++i) r.x[i] = xsrc[i][(size_t)min(kt + xu[i], Kt - 1) * 64];
+        for (int i = 0; i < F; ++i)
+          if (xlive[i]) r.x[i] = xsrc[i][(size_t)min(kt + xu[i], Kt - 1) * 64];
       };
       auto sstore = [&](int stage, const Regs& r) {
 #pragma unroll
@@ -216,6 +224,8 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
         }
       };
       Regs A, B;
+#pragma unroll
+      for (int i = 0; i < F; ++i) A.x[i] = B.x[i] = (u32x4){0u, 0u, 0u, 0u};
       gload(A, 0);
       sstore(0, A);                                          // (nobody reads stage 0 any more: the last barrier of the previous round)
       __syncthreads();                                       // also orders s_rb / s_rt before the sampling below
@@ -344,7 +354,7 @@ void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, cons
   LmArgs a;
   a.x_plane = x_plane;
   a.W = W; a.X = X; a.rd = rd; a.V = V; a.K = K; a.Kt = (K + 31) / 32; a.n_tiles = (V + 15) / 16;
-  a.sa = sa; a.part = part; a.Mpad = Mpad; a.logits_out = logits_out; a.m_tiles = 0;
+  a.sa = sa; a.part = part; a.Mpad = Mpad; a.logits_out = logits_out; a.m_tiles = 0; a.rows_live = max_rows;
   if (dtype == 0) {
     hipLaunchKernelGGL(k_lmhead_f32, dim3(n_wg), dim3(256), 0, s, a);
   } else if (max_rows <= 16) {
