@@ -297,7 +297,8 @@ def bench_sd(args, base):
         "config": {"workload": f"{cfg.name}: standard speculative decoding, gamma {G}; batch {B}, prompt {pmax}, "
                                f"T {cfg.temperature}; draft L{cfg.draft.n_layer} d{cfg.draft.d_model}, target "
                                f"L{cfg.target.n_layer} d{cfg.target.d_model}, vocab {cfg.draft.vocab}; random-init "
-                               f"weights, Zipf(1.1) prompts", "batch": B, "prompt_len": pmax, "gamma": G},
+                               f"weights, Zipf(1.1) prompts", "batch": B, "prompt_len": pmax, "gamma": G,
+                   "arithmetic": ("bf16 weights and KV caches, float16 matrix operands, float32 accumulation" if cfg.dtype == 1 else "float32")},
         "tokens_per_round": tokens / (B * K),
         "target_calls_per_token": B * K / tokens,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -430,7 +431,8 @@ def run_decode(base, args, K, Wm, reject_rate=None, extras=True, want_cpu=True):
            "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": res["ms_per_step"],
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16" if cfg.dtype == 1 else "f32", "data": "synthetic",
-           "config": {"workload": label, "batch": B, "prompt_len": pmax},
+           "config": {"workload": label, "batch": B, "prompt_len": pmax,
+                      "arithmetic": ("bf16 weights and KV caches, float16 matrix operands, float32 accumulation" if cfg.dtype == 1 else "float32")},
            "target_calls_per_token": res["target_calls_per_token"],
            "steps_with_target_frac": res["steps_with_target_frac"], "avg_accepted_run": res["avg_accepted_run"],
            "roofline": res["roofline"]}

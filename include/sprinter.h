@@ -34,6 +34,13 @@
  *   - matrices are row-major [out, in] ("y = W x"), in the element type chosen
  *     by sprinter_cfg.dtype; every 1-D parameter (bias, norm gain/offset) and
  *     the whole verifier are float32.
+ *   - arithmetic of SPRINTER_BF16: weights and both KV caches hold bfloat16
+ *     values; the matrix products take float16 operands - the weights converted
+ *     once when they are packed (exact above 2^-14, rounded to the float16
+ *     subnormal grid below), the activations rounded to float16 (11 significant
+ *     bits; magnitudes above 65504 become infinities) - and accumulate in
+ *     float32; the residual stream, projections, attention scores and logits
+ *     are float32.  SPRINTER_F32: float32 throughout.
  */
 #ifndef SPRINTER_H
 #define SPRINTER_H

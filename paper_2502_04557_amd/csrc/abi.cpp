@@ -133,10 +133,8 @@ int rows_alloc_for(int max_batch) {
 }
 
 size_t esize(int dtype) { return dtype == SPRINTER_F32 ? 4 : 2; }
-// elements of an activation buffer [rows, K] in the activation layout
-size_t act_plane(int dtype, int rows, int K) { return (size_t)rows * (dtype == SPRINTER_F32 ? K : round_up(K, 32)); }
-// bf16 mode keeps every activation as hi + lo in two planes
-size_t act_elems(int dtype, int rows, int K) { return act_plane(dtype, rows, K) * (dtype == SPRINTER_F32 ? 1 : 2); }
+// elements of an activation buffer [rows, K] in the activation layout (bf16 mode: float16 operand tiles)
+size_t act_elems(int dtype, int rows, int K) { return (size_t)rows * (dtype == SPRINTER_F32 ? K : round_up(K, 32)); }
 size_t packed_elems(int N, int K) { return (size_t)round_up(N, 16) * round_up(K, 32); }
 
 constexpr int DEFAULT_CHUNK_ROWS = 4096;
@@ -373,7 +371,8 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
   hipStream_t s = ctx->stream;
   ModelScratch& sc = m.sc;
   const int rows = ctx->rows_alloc;
-  const size_t pl_d = act_plane(dt, rows, md.d), pl_a = act_plane(dt, rows, md.H * md.dh), pl_f = act_plane(dt, rows, md.ff);
+  // elements the activation buffers hold (their row tiles bound what a kernel may fetch)
+  const size_t pl_d = act_elems(dt, rows, md.d), pl_a = act_elems(dt, rows, md.H * md.dh), pl_f = act_elems(dt, rows, md.ff);
   launch_embed(dt, md, m.tok_emb, m.pos_emb, rd, sc.h, sc.rope, max_rows, s);
   // bf16: O-proj and FFN-down split K over workgroups and leave partial products; the norm that follows folds
   // them (and the bias) into the residual stream before it normalises the row.
@@ -385,11 +384,11 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
       pend.shares = launch_gemm_part(W, X, plane, rd.n_rows, md.d, K, sc.part, part_stride, PART_SHARES, max_rows, s);
       pend.bias = bias;
     } else {
-      launch_gemm(dt, EPI_RESID, W, nullptr, X, plane, rd.n_rows, md.d, K, bias, sc.h, md.d, nullptr, 0, 0, max_rows, s);
+      launch_gemm(dt, EPI_RESID, W, nullptr, X, plane, rd.n_rows, md.d, K, bias, sc.h, md.d, nullptr, 0, max_rows, s);
     }
   };
   auto norm = [&](const float* g, const float* b, void* out, float* f32_out) {
-    launch_norm(dt, md.arch, sc.h, g, b, md.eps, md.d, rd.n_rows, out, pl_d, f32_out, max_rows, s,
+    launch_norm(dt, md.arch, sc.h, g, b, md.eps, md.d, rd.n_rows, out, f32_out, max_rows, s,
                 pend.shares > 0 ? &pend : nullptr);
     pend.shares = 0;
   };
@@ -397,25 +396,25 @@ void forward(sprinter_ctx* ctx, Model& m, const RowDesc& rd, int max_rows, bool 
     const LayerW& L = m.layers[i];
     norm(L.n1g, L.n1b, sc.xn, nullptr);
     launch_gemm(dt, EPI_F32, L.wqkv, nullptr, sc.xn, pl_d, rd.n_rows, md.dqkv, md.d, L.bqkv, sc.y, md.dqkv, nullptr, 0,
-                0, max_rows, s);
+                max_rows, s);
     if (shared_caches) {
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       kv_slots(ctx->cfg), sc.ao, pl_a, max_rows, s, 1);
+                       kv_slots(ctx->cfg), sc.ao, max_rows, s, 1);
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       kv_slots(ctx->cfg), sc.ao, pl_a, max_rows, s, long_runs ? 3 : 2);
+                       kv_slots(ctx->cfg), sc.ao, max_rows, s, long_runs ? 3 : 2);
     } else {
       launch_attention(dt, md, sc.y, sc.rope, rd, m.kcache, m.vcache, m.layer_stride * i, ctx->max_prompt_len + (int)ctx->steps_done,
-                       kv_slots(ctx->cfg), sc.ao, pl_a, max_rows, s);
+                       kv_slots(ctx->cfg), sc.ao, max_rows, s);
     }
     if (!want_head && i + 1 == md.n_layer) break;   // a prefill position only has to fill the caches
     resid_gemm(L.wo, sc.ao, pl_a, md.H * md.dh, L.bo);
     norm(L.n2g, L.n2b, sc.xn, nullptr);
     if (md.arch == SPRINTER_ARCH_GPT)
       launch_gemm(dt, EPI_GELU, L.w1, nullptr, sc.xn, pl_d, rd.n_rows, md.ff, md.d, L.b1, nullptr, 0, sc.mid, md.ff,
-                  pl_f, max_rows, s);
+                  max_rows, s);
     else
       launch_gemm(dt, EPI_SWIGLU, L.wg, L.wu, sc.xn, pl_d, rd.n_rows, md.ff, md.d, nullptr, nullptr, 0, sc.mid, md.ff,
-                  pl_f, max_rows, s);
+                  max_rows, s);
     resid_gemm(L.w2, sc.mid, pl_f, md.ff, L.b2);
   }
   if (!want_head) return;

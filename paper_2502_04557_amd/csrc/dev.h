@@ -6,8 +6,10 @@
 
 namespace sprinter {
 
-typedef unsigned short bf16_t;   // raw bfloat16 bits
+typedef unsigned short bf16_t;   // raw bfloat16 bits (weights as given, KV caches); also the 16-bit element type of an
+                                 // activation operand, whose bits are float16 (below)
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef unsigned long long u64;
 
@@ -34,18 +36,20 @@ template <> __device__ __forceinline__ size_t act_idx<bf16_t>(int m, int k, int 
   return ((size_t)(m >> 4) * Kt + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7);
 }
 
-// Store one activation.  In bf16 mode a value is kept as the sum of two bf16 numbers
-// (hi = RNE(v), lo = RNE(v - hi)) in two planes of operand tiles, so that the GEMM input
-// carries ~16 mantissa bits while the weights stay plain bf16; each plane is one MFMA operand.
-template <typename T> __device__ __forceinline__ void act_store(T* base, size_t plane, int m, int k, int K, float v);
-template <> __device__ __forceinline__ void act_store<float>(float* base, size_t, int m, int k, int K, float v) {
+// Store one activation.  In bf16 mode the GEMM operands are float16: the weights (bf16 values, converted once when
+// they are packed - exact above 2^-14) and the activations, rounded to nearest even with 11 significant bits, so
+// that one matrix instruction per product carries eight times the precision of a bf16 activation; the products
+// accumulate in float32.  Values beyond the float16 range (65504) become infinities and show as such downstream.
+__device__ __forceinline__ unsigned short f2h(float v) {
+  const _Float16 h = (_Float16)v;
+  return __builtin_bit_cast(unsigned short, h);
+}
+template <typename T> __device__ __forceinline__ void act_store(T* base, int m, int k, int K, float v);
+template <> __device__ __forceinline__ void act_store<float>(float* base, int m, int k, int K, float v) {
   base[act_idx<float>(m, k, K)] = v;
 }
-template <> __device__ __forceinline__ void act_store<bf16_t>(bf16_t* base, size_t plane, int m, int k, int K, float v) {
-  size_t i = act_idx<bf16_t>(m, k, K);
-  bf16_t hi = f2bf(v);
-  base[i] = hi;
-  base[plane + i] = f2bf(v - bf2f(hi));
+template <> __device__ __forceinline__ void act_store<bf16_t>(bf16_t* base, int m, int k, int K, float v) {
+  base[act_idx<bf16_t>(m, k, K)] = f2h(v);
 }
 
 // Two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even), and the hi + lo split of a pair.
@@ -54,6 +58,13 @@ typedef __bf16 b2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pk_bf16(float a, float b) {
   f2v v = {a, b};
   b2v h = __builtin_convertvector(v, b2v);   // v_cvt_pk_bf16_f32, round to nearest even
+  return __builtin_bit_cast(unsigned, h);
+}
+// Two floats -> packed float16 pair of an activation operand (round to nearest even).
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pk_f16(float a, float b) {
+  f2v v = {a, b};
+  h2v h = __builtin_convertvector(v, h2v);
   return __builtin_bit_cast(unsigned, h);
 }
 __device__ __forceinline__ void split2(float a, float b, unsigned& hi, unsigned& lo) {
@@ -235,6 +246,10 @@ __device__ __forceinline__ u64 group_umax64_16(u64 k) {
   return k;
 }
 
+// D += X W^T for a 16 x 32 activation tile and a 16 x 32 weight tile, both float16 operands.
+__device__ __forceinline__ f32x4 mfma_f16(uint4 x, uint4 w, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(*reinterpret_cast<f16x8*>(&x), *reinterpret_cast<f16x8*>(&w), c, 0, 0, 0);
+}
 __device__ __forceinline__ f32x4 mfma_bf16(uint4 x, uint4 w, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8*>(&x), *reinterpret_cast<bf16x8*>(&w), c, 0,
                                                  0, 0);

@@ -67,29 +67,29 @@ struct NormPending {
 };
 // pend is honoured by the bf16 kernel only (d a multiple of 8, at most 8192): see norm_takes_pending().
 void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
-                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s,
+                 const int* n_rows, void* act_out, float* f32_out, int max_rows, hipStream_t s,
                  const NormPending* pend = nullptr);
 inline bool norm_takes_pending(int dtype, int d) { return dtype == 1 && d % 8 == 0 && d <= 8192; }
 // bf16: part[s] = X[:, K share s] W[:, K share s]^T for s < returned share count (<= max_shares)
-int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_rows, int N, int K, float* part,
+int launch_gemm_part(const void* W, const void* X, size_t x_elems, const int* n_rows, int N, int K, float* part,
                      size_t part_stride, int max_shares, int max_rows, hipStream_t s);
 
 enum { EPI_F32 = 0, EPI_RESID = 1, EPI_GELU = 2, EPI_SWIGLU = 3, EPI_PART = 4 /* partial product of one K share */ };
 // Y[M,N] = X[M,K] W[N,K]^T (+bias) with epilogue; X in activation layout, W in weight layout.
-// x_plane / out_plane: element distance between the hi and lo planes of a bf16 activation buffer.
-void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane,
+// x_elems: elements the activation buffer X holds (its row tiles bound what a kernel may fetch).
+void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_elems,
                  const int* n_rows, int N, int K, const float* bias, float* out_f32, int ldo, void* out_act,
-                 int out_K, size_t out_plane, int max_rows, hipStream_t s);
+                 int out_K, int max_rows, hipStream_t s);
 
 void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
                       void* kcache, void* vcache, size_t layer_off, int ctx_bound /* upper bound of the rows' cache lengths */,
                       int max_seq /* slots per (row, KV head) of the caches; bf16: a multiple of 32 */,
-                      void* ao, size_t ao_plane, int max_rows, hipStream_t s, int phase = 0);
+                      void* ao, int max_rows, hipStream_t s, int phase = 0);
 // phase 0: append the row's new key / value to the cache and attend (rows of one launch own different caches);
 // phase 1: append only; phase 2: attend only (the pair serves launches where several rows share a cache).
 
 int lmhead_num_wg(int dtype, int V);
-void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, const RowDesc& rd, int V, int K,
+void launch_lmhead(int dtype, const void* W, const void* X, size_t x_elems, const RowDesc& rd, int V, int K,
                    const SamplerArgs& sa, unsigned long long* part, int n_wg, int Mpad,
                    float* logits_out, int max_rows, hipStream_t s);
 

@@ -13,7 +13,7 @@ struct AttnArgs {
   const float* y; const float* rope; RowDesc rd;
   void* kcache; void* vcache; size_t layer_off;
   int H, KVH, dqkv, max_seq, use_rope; float scale;
-  void* ao; int ao_K; size_t ao_plane;
+  void* ao; int ao_K;
   int phase;   // 0 append + attend, 1 append only, 2 attend only, 3 attend only over long runs of one row (launcher only)
 };
 
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     int g = idx / DH;
     float o = ((red[idx] + red[G * DH + idx]) + red[2 * G * DH + idx]) + red[3 * G * DH + idx];
     o *= s_inv[g];
-    act_store<T>(ao, a.ao_plane, r, kvh * G * DH + idx, a.ao_K, o);
+    act_store<T>(ao, r, kvh * G * DH + idx, a.ao_K, o);
   }
 }
 
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(NW * 64, 2) void k_attn_dec_bf16(AttnArgs a) {
       den += c * s_ml[q][g][1];
       num += c * s_o[q][g][i];
     }
-    act_store<bf16_t>(ao, a.ao_plane, r, kvh * G * DH + idx, a.ao_K, num / den);
+    act_store<bf16_t>(ao, r, kvh * G * DH + idx, a.ao_K, num / den);
   }
 }
 
@@ -625,7 +625,7 @@ __global__ __launch_bounds__(64) void k_attn_mfma_bf16(AttnArgs a) {
       if (e < s0 || e >= s1) continue;
       const float inv = 1.0f / l_run[v];
 #pragma unroll
-      for (int ct = 0; ct < CT; ++ct) act_store<bf16_t>(ao, a.ao_plane, r0 + e, h * DH + ct * 16 + l16, a.ao_K, O[ct][v] * inv);
+      for (int ct = 0; ct < CT; ++ct) act_store<bf16_t>(ao, r0 + e, h * DH + ct * 16 + l16, a.ao_K, O[ct][v] * inv);
     }
     s0 = s1;
   }
@@ -667,13 +667,13 @@ static void launch_attn_g(const AttnArgs& a, int G, int max_rows, hipStream_t s)
 
 void launch_attention(int dtype, const ModelDims& md, const float* y, const float* rope, const RowDesc& rd,
                       void* kcache, void* vcache, size_t layer_off, int ctx_bound, int max_seq, void* ao,
-                      size_t ao_plane, int max_rows, hipStream_t s, int phase) {
+                      int max_rows, hipStream_t s, int phase) {
   AttnArgs a;
   a.phase = (phase == 3 && dtype == 0) ? 2 : phase;      // the run-sharing kernel exists for bf16 only
   a.y = y; a.rope = rope; a.rd = rd; a.kcache = kcache; a.vcache = vcache; a.layer_off = layer_off;
   a.H = md.H; a.KVH = md.KVH; a.dqkv = md.dqkv; a.max_seq = max_seq; a.use_rope = md.arch == 1;
   a.scale = 1.0f / sqrtf((float)md.dh);
-  a.ao = ao; a.ao_K = md.H * md.dh; a.ao_plane = ao_plane;
+  a.ao = ao; a.ao_K = md.H * md.dh;
   int G = md.H / md.KVH;
   if (dtype == 0) {
     if (md.dh == 64) launch_attn_g<float, 64>(a, G, max_rows, s); else launch_attn_g<float, 128>(a, G, max_rows, s);

@@ -11,8 +11,7 @@ struct GemmArgs {
   const void* W; const void* W2; const void* X; const int* n_rows;
   int N, K, Kt, n_tiles;
   const float* bias; float* out_f32; int ldo; void* out_act; int out_K;
-  size_t x_plane;     // elements between the hi and lo planes of X (bf16 mode)
-  size_t out_plane;   // same for out_act
+  size_t x_elems;     // elements the activation buffer X holds (bf16 mode)
   int SK; float* part; size_t part_stride;   // k_gemm16_part: K shares, partial outputs [SK][rows][N], floats per share
   int rows_live;      // the host's bound on the row count: rows from here on exist in no launch, their activations are not fetched
 };
@@ -23,8 +22,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int
   if (m >= n_rows || n >= a.N) return;
   if (EPI == EPI_F32) a.out_f32[(size_t)m * a.ldo + n] = v + bias;
   else if (EPI == EPI_RESID) a.out_f32[(size_t)m * a.ldo + n] = res + (v + bias);
-  else if (EPI == EPI_GELU) act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, gelu_tanh(v + bias));
-  else act_store<AT>((AT*)a.out_act, a.out_plane, m, n, a.out_K, silu(v) * v2);
+  else if (EPI == EPI_GELU) act_store<AT>((AT*)a.out_act, m, n, a.out_K, gelu_tanh(v + bias));
+  else act_store<AT>((AT*)a.out_act, m, n, a.out_K, silu(v) * v2);
 }
 
 
@@ -32,7 +31,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int
 // (16 columns each): D[m][n] += X[m][k] W[n][k].
 // All 8 waves leave their partial sums in LDS and every thread then finishes ONE output element: it adds the 8
 // partials in fixed order, applies bias / residual / GELU / SwiGLU and stores.  With the element order chosen per
-// output layout the 256 x NTW stores of the workgroup are contiguous: one 32-column operand tile (two planes) for
+// output layout the 256 x NTW stores of the workgroup are contiguous: one 32-column operand tile for
 // the activation outputs, 64-128 byte runs for float32 rows.  (When wave 0 alone ran the epilogue - 8 tanh and 16
 // scattered 2-byte stores per lane for FFN-up - it took 2.2 of the kernel's 7.1 us.)
 // Accumulator layout of v_mfma_f32_16x16x32: lane l, register v hold n = l % 16, m = (l / 16) * 4 + v.
@@ -48,7 +47,6 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
   const uint4* __restrict__ Wp = (const uint4*)a.W;
   const uint4* __restrict__ W2p = (const uint4*)a.W2;
   const uint4* __restrict__ Xp = (const uint4*)a.X;
-  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   const int Kt = a.Kt;
   // Requests that depend on nothing are issued before the row count is even read: this wave's first weight
   // tiles and this thread's bias and (residual epilogue) current output value.
@@ -69,16 +67,15 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
   // rejected rows then pulls 3/16 of the activation bytes through the compute unit's memory pipeline, which carries
   // them next to the weight stream); what their registers hold only reaches output rows that are dropped.
   const bool row_live = (lane & 15) < a.rows_live;
-  uint4 xv[U], xl[U];
+  uint4 xv[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) xv[u] = xl[u] = make_uint4(0u, 0u, 0u, 0u);
+  for (int u = 0; u < U; ++u) xv[u] = make_uint4(0u, 0u, 0u, 0u);
   auto load_x = [&](int kt) {                               // no dependence on the (device-side) row count
     if (row_live) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int kc = min(kt + u * 8, Kt - 1);
         xv[u] = Xp[(size_t)kc * 64 + lane];
-        xl[u] = Xl[(size_t)kc * 64 + lane];
       }
     }
   };
@@ -109,14 +106,12 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool in_k = kt + u * 8 < Kt;
-      const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
+      const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
       for (int j = 0; j < NTW; ++j) {
-        acc[j] = mfma_bf16(ah, wv[u][j], acc[j]);
-        acc[j] = mfma_bf16(al, wv[u][j], acc[j]);
+        acc[j] = mfma_f16(ah, wv[u][j], acc[j]);
         if (DUAL) {
-          acc2[j] = mfma_bf16(ah, wv2[u][j], acc2[j]);
-          acc2[j] = mfma_bf16(al, wv2[u][j], acc2[j]);
+          acc2[j] = mfma_f16(ah, wv2[u][j], acc2[j]);
         }
       }
     }
@@ -144,9 +139,9 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
 }
 
 // bf16 GEMM for 17 .. 64 rows per pass (MT row tiles of 16), one column tile per workgroup, K split over
-// the 8 waves.  At these row counts a workgroup pulls the whole activation matrix (MT x 2 KiB per k tile,
+// the 8 waves.  At these row counts a workgroup pulls the whole activation matrix (MT x 1 KiB per k tile,
 // from L2) for 1 KiB of weights per k tile, so the kernel lives on memory-level parallelism: two register
-// buffers, the loads of chunk c + 1 (weights and all MT row tiles, both planes) are in flight while the
+// buffers, the loads of chunk c + 1 (weights and all MT row tiles) are in flight while the
 // MFMAs of chunk c run, and there is no branch inside the loop.  Row tiles beyond the row count are
 // computed on whatever the buffers hold and dropped by the epilogue; k tiles beyond K are clamped on load
 // and their weight operand zeroed.  blockIdx.y = pass over 16 * MT rows.
@@ -165,11 +160,10 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
   const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
   const uint4* __restrict__ W2p = DUAL ? (const uint4*)a.W2 + lane : nullptr;
   const uint4* __restrict__ Xp = (const uint4*)a.X + (size_t)mtile0 * Kt * 64 + lane;
-  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   size_t wrow[NTW];
 #pragma unroll
   for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt0 + j, a.n_tiles - 1) * Kt * 64;
-  struct Buf { uint4 w[U][NWT], xh[U][MT], xl[U][MT]; };
+  struct Buf { uint4 w[U][NWT], xh[U][MT]; };
   // (as in k_gemm16: a lane whose row exists in no launch - the host's bound - skips its activation loads; with 18
   // rows the second row tile costs an eighth of its bytes)
   bool row_live[MT];
@@ -192,7 +186,6 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
         for (int u = 0; u < U; ++u) {
           const int kc = min(kt + u * 8, k1 - 1);
           b.xh[u][mt] = Xp[((size_t)mt * Kt + kc) * 64];
-          b.xl[u][mt] = Xl[((size_t)mt * Kt + kc) * 64];
         }
       }
     }
@@ -211,8 +204,7 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
         const uint4 w1 = in_k ? b.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          acc[j][mt] = mfma_bf16(b.xh[u][mt], w1, acc[j][mt]);
-          acc[j][mt] = mfma_bf16(b.xl[u][mt], w1, acc[j][mt]);
+          acc[j][mt] = mfma_f16(b.xh[u][mt], w1, acc[j][mt]);
         }
       }
     }
@@ -221,7 +213,7 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) A.xh[u][mt] = A.xl[u][mt] = B.xh[u][mt] = B.xl[u][mt] = make_uint4(0u, 0u, 0u, 0u);
+    for (int mt = 0; mt < MT; ++mt) A.xh[u][mt] = B.xh[u][mt] = make_uint4(0u, 0u, 0u, 0u);
   load(A, min(k0 + kw, k1 - 1));
   const int n_rows = *a.n_rows;                               // only the epilogue needs it (passes are sized by the host)
   // (the scheduling barriers keep the compiler from sinking a buffer's loads down to their first use)
@@ -302,38 +294,36 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
 
 // bf16 GEMM for 128+ rows (prefill chunks, long work lists): the 8 waves of a workgroup split the COLUMNS (NTW
 // column tiles each; SwiGLU: one gate + one up tile) and share the activations of 8 row tiles (128 rows) through LDS,
-// so a k tile costs the workgroup 16 KiB of activations (both planes, once) + 8 * NWT KiB of weights for
-// 8 * NWT * 16 MFMAs - a third of the bytes per MFMA of the K-split kernel above, which reads every operand per wave.
-// Two k tiles per stage (one with four weight tiles per wave), two LDS stages: the global loads of stage c + 1 (4 activation fragments per thread into
-// registers, the wave's own weight tiles) are in flight while the MFMAs of stage c run; one barrier per stage.
+// so a k tile costs the workgroup 8 KiB of activations (once) + 8 * NWT KiB of weights for
+// 8 * NWT * 8 MFMAs - far fewer bytes per MFMA than the K-split kernel above, which reads every operand per wave.
+// Two k tiles per stage (one with four weight tiles per wave), two LDS stages: the global loads of stage c + 1 (the activation fragments a thread stages, into
+// registers, and the wave's own weight tiles) are in flight while the MFMAs of stage c run; one barrier per stage.
 // blockIdx.y = group of 128 rows, blockIdx.z = K share (EPI_PART).  The activation buffer must hold every row
-// tile the grid covers (the launcher checks it against the plane size).
+// tile the grid covers (the launcher checks it against the buffer's size).
 template <int NTW, int EPI>
 __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
   constexpr bool DUAL = (EPI == EPI_SWIGLU);
   constexpr int NWT = NTW * (DUAL ? 2 : 1), MT = 8;
   constexpr int KU = NWT >= 4 ? 1 : 2;                 // k tiles per stage (four weight tiles per wave leave registers for one)
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  __shared__ u32x4 xs[2][KU * 2][MT][64];               // [stage][k tile, plane][row tile][lane]: 64 KiB
+  __shared__ u32x4 xs[2][KU][MT][64];                   // [stage][k tile][row tile][lane]: 16 KiB per k tile of a stage
   const int lane = threadIdx.x & 63, w = wave_index();
   const int Kt = a.Kt, mtile0 = blockIdx.y * MT, nt0 = (blockIdx.x * 8 + w) * NTW;
   const int sk = (EPI == EPI_PART) ? blockIdx.z : 0, SK = (EPI == EPI_PART) ? gridDim.z : 1;
   const int k0 = (int)((long long)Kt * sk / SK), k1 = (int)((long long)Kt * (sk + 1) / SK);
   const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
   const uint4* __restrict__ W2p = DUAL ? (const uint4*)a.W2 + lane : nullptr;
-  // staging: wave w fetches row tile w of every (k tile, plane) of the stage
+  // staging: wave w fetches row tile w of every k tile of the stage
   const u32x4* __restrict__ Xh = (const u32x4*)a.X + (size_t)(mtile0 + w) * Kt * 64 + lane;
-  const u32x4* __restrict__ Xl = Xh + a.x_plane / 8;
   size_t wrow[NTW];
 #pragma unroll
   for (int j = 0; j < NTW; ++j) wrow[j] = (size_t)min(nt0 + j, a.n_tiles - 1) * Kt * 64;
-  struct Regs { u32x4 x[KU * 2]; uint4 w[KU][NWT]; };
+  struct Regs { u32x4 x[KU]; uint4 w[KU][NWT]; };
   auto gload = [&](Regs& r, int kt) {
 #pragma unroll
     for (int u = 0; u < KU; ++u) {
       const int kc = min(kt + u, k1 - 1);                // clamped: always a tile of this share
-      r.x[u * 2] = Xh[(size_t)kc * 64];
-      r.x[u * 2 + 1] = Xl[(size_t)kc * 64];
+      r.x[u] = Xh[(size_t)kc * 64];
 #pragma unroll
       for (int j = 0; j < NTW; ++j) {
         r.w[u][j] = Wp[wrow[j] + (size_t)kc * 64];
@@ -343,7 +333,7 @@ __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
   };
   auto sstore = [&](int stage, const Regs& r) {
 #pragma unroll
-    for (int i = 0; i < KU * 2; ++i) xs[stage][i][w][lane] = r.x[i];
+    for (int i = 0; i < KU; ++i) xs[stage][i][w][lane] = r.x[i];
   };
   f32x4 acc[NWT][MT];
 #pragma unroll
@@ -359,12 +349,11 @@ __global__ __launch_bounds__(512) void k_gemm_wide(GemmArgs a) {
       for (int j = 0; j < NWT; ++j) wv[j] = in_k ? r.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const u32x4 h = xs[stage][u * 2][mt][lane], l = xs[stage][u * 2 + 1][mt][lane];
-        const uint4 xh = make_uint4(h.x, h.y, h.z, h.w), xl = make_uint4(l.x, l.y, l.z, l.w);
+        const u32x4 h = xs[stage][u][mt][lane];
+        const uint4 xh = make_uint4(h.x, h.y, h.z, h.w);
 #pragma unroll
         for (int j = 0; j < NWT; ++j) {
-          acc[j][mt] = mfma_bf16(xh, wv[j], acc[j][mt]);
-          acc[j][mt] = mfma_bf16(xl, wv[j], acc[j][mt]);
+          acc[j][mt] = mfma_f16(xh, wv[j], acc[j][mt]);
         }
       }
     }
@@ -420,7 +409,7 @@ template <int EPI>
 static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s, int min_rows = 128) {
   if (max_rows < min_rows) return false;
   const int row_groups = (max_rows + 127) / 128;
-  if ((size_t)row_groups * 128 * a.Kt * 32 > a.x_plane) return false;
+  if ((size_t)row_groups * 128 * a.Kt * 32 > a.x_elems) return false;
   constexpr bool DUAL = EPI == EPI_SWIGLU;
   const int g2 = (a.n_tiles + 15) / 16, g1 = (a.n_tiles + 7) / 8;
   // too few workgroups for the chip (a 128-row decode batch on a narrow model: 18 column groups): the K-split
@@ -465,7 +454,6 @@ __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
   const int k0 = (int)((long long)Kt * sk / a.SK), k1 = (int)((long long)Kt * (sk + 1) / a.SK);
   const uint4* __restrict__ Wp = (const uint4*)a.W;
   const uint4* __restrict__ Xp = (const uint4*)a.X;
-  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   uint4 wv[U][NTW];
   auto load_weights = [&](int kt) {
 #pragma unroll
@@ -476,16 +464,15 @@ __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
     }
   };
   const bool row_live = (lane & 15) < a.rows_live;            // (as in k_gemm16: rows that exist in no launch are not fetched)
-  uint4 xv[U], xl[U];
+  uint4 xv[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) xv[u] = xl[u] = make_uint4(0u, 0u, 0u, 0u);
+  for (int u = 0; u < U; ++u) xv[u] = make_uint4(0u, 0u, 0u, 0u);
   auto load_x = [&](int kt) {
     if (row_live) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int kc = min(kt + u * 8, k1 - 1);
         xv[u] = Xp[(size_t)kc * 64 + lane];
-        xl[u] = Xl[(size_t)kc * 64 + lane];
       }
     }
   };
@@ -500,11 +487,10 @@ __global__ __launch_bounds__(512) void k_gemm16_part(GemmArgs a) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bool in_k = kt + u * 8 < k1;
-      const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u), al = in_k ? xl[u] : make_uint4(0u, 0u, 0u, 0u);
+      const uint4 ah = in_k ? xv[u] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
       for (int j = 0; j < NTW; ++j) {
-        acc[j] = mfma_bf16(ah, wv[u][j], acc[j]);
-        acc[j] = mfma_bf16(al, wv[u][j], acc[j]);
+        acc[j] = mfma_f16(ah, wv[u][j], acc[j]);
       }
     }
   }
@@ -609,12 +595,12 @@ static void launch_gemm_bf16(const GemmArgs& a, int max_rows, hipStream_t s) {
   }
 }
 
-void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_plane, const int* n_rows,
-                 int N, int K, const float* bias, float* out_f32, int ldo, void* out_act, int out_K, size_t out_plane,
+void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* X, size_t x_elems, const int* n_rows,
+                 int N, int K, const float* bias, float* out_f32, int ldo, void* out_act, int out_K,
                  int max_rows, hipStream_t s) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.x_plane = x_plane; a.out_plane = out_plane;
+  a.x_elems = x_elems;
   a.W = W; a.W2 = W2; a.X = X; a.n_rows = n_rows; a.N = N; a.K = K;
   a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16;
   a.bias = bias; a.out_f32 = out_f32; a.ldo = ldo; a.out_act = out_act; a.out_K = out_K; a.rows_live = max_rows;
@@ -636,11 +622,11 @@ void launch_gemm(int dtype, int epi, const void* W, const void* W2, const void* 
   }
 }
 
-int launch_gemm_part(const void* W, const void* X, size_t x_plane, const int* n_rows, int N, int K, float* part,
+int launch_gemm_part(const void* W, const void* X, size_t x_elems, const int* n_rows, int N, int K, float* part,
                      size_t part_stride, int max_shares, int max_rows, hipStream_t s) {
   GemmArgs a;
   memset(&a, 0, sizeof a);
-  a.W = W; a.X = X; a.x_plane = x_plane; a.n_rows = n_rows; a.N = N; a.K = K;
+  a.W = W; a.X = X; a.x_elems = x_elems; a.n_rows = n_rows; a.N = N; a.K = K;
   a.Kt = (K + 31) / 32; a.n_tiles = (N + 15) / 16; a.ldo = N;
   a.part = part; a.part_stride = part_stride; a.rows_live = max_rows;
   if (max_rows <= 16) {

@@ -9,7 +9,7 @@ namespace sprinter {
 // ======================================================= LM head + sample
 struct LmArgs {
   const void* W; const void* X; RowDesc rd; int V, K, Kt, n_tiles;
-  SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_plane; int m_tiles;
+  SamplerArgs sa; u64* part; int Mpad; float* logits_out; size_t x_elems; int m_tiles;
   int rows_live;   // the host's bound on the row count: lanes of rows from here on skip their activation loads
 };
 
@@ -27,10 +27,9 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
   const int t0 = blockIdx.x * tpw, t1 = min(t0 + tpw, a.n_tiles);
   const uint4* __restrict__ Wp = (const uint4*)a.W + lane;
   const uint4* __restrict__ Xp = (const uint4*)a.X + lane;
-  const uint4* __restrict__ Xl = Xp + a.x_plane / 8;
   const int Kt = a.Kt;
   const int n_rows = *a.rd.n_rows;
-  struct Buf { uint4 w[2], xh[MT], xl[MT]; };
+  struct Buf { uint4 w[2], xh[MT]; };
   for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
     const int mtile0 = m0 >> 4;
     u64 best[MT][4];
@@ -53,7 +52,6 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
         for (int mt = 0; mt < MT; ++mt) {                 // (a lane holds 8 k of one row: rows that exist in no launch are not fetched,
           if (m0 + mt * 16 + (lane & 15) < a.rows_live) { //  what the registers hold for them only reaches logits that are dropped)
             b.xh[mt] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64];
-            b.xl[mt] = Xl[((size_t)(mtile0 + mt) * Kt + kc) * 64];
           }
         }
       };
@@ -69,14 +67,13 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
           const uint4 wj = in_k ? b.w[j] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
-            acc[j][mt] = mfma_bf16(b.xh[mt], wj, acc[j][mt]);
-            acc[j][mt] = mfma_bf16(b.xl[mt], wj, acc[j][mt]);
+            acc[j][mt] = mfma_f16(b.xh[mt], wj, acc[j][mt]);
           }
         }
       };
       Buf A, B;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) A.xh[mt] = A.xl[mt] = B.xh[mt] = B.xl[mt] = make_uint4(0u, 0u, 0u, 0u);
+      for (int mt = 0; mt < MT; ++mt) A.xh[mt] = B.xh[mt] = make_uint4(0u, 0u, 0u, 0u);
       load(A, 0);
       for (int kt = 0; kt < Kt; kt += 2) {
         load(B, kt + 1);
@@ -134,16 +131,16 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
 
 // bf16, 17+ rows: the 8 waves of a workgroup take different column tiles (NTW each, 8 NTW tiles per round over the
 // workgroup's tile range) and share the activations of MT row tiles through LDS, so a k tile costs the workgroup
-// MT * 2 KiB of activations once instead of once per wave - at 64 rows the per-wave reads above pull five times the
+// MT KiB of activations once instead of once per wave - at 64 rows per-wave reads would pull three times the
 // weight bytes through L2.  KS k tiles per stage, two LDS stages: the loads of stage c + 1 (the wave's weight tiles
 // and its share of the activation fragments, into registers) are in flight while the MFMAs of stage c run; one
 // barrier per stage.  NTW = 2 where the workgroup's range has more than 8 tiles (large vocabularies), else 1 so
-// that every wave has a tile.  Fragment f of a stage = (k tile f / (2 MT), plane (f / MT) % 2, row tile f % MT); wave w
+// that every wave has a tile.  Fragment f of a stage = (k tile f / MT, row tile f % MT); wave w
 // stages fragments w, w + 8, ...  Tiles and k tiles beyond the end are clamped on load and dropped afterwards; row
 // tiles are clamped to the m_tiles the activation buffer holds.  More than 16 MT rows take further passes.
 template <int MT, int NTW, int KS>
 __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) {
-  constexpr int NF = KS * 2 * MT, F = NF / 8;
+  constexpr int NF = KS * MT, F = NF / 8;
   static_assert(NF % 8 == 0, "every wave stages the same number of fragments");
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   __shared__ u32x4 xs[2][NF][64];
@@ -174,10 +171,10 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
     bool xlive[F];                                           // (a lane stages 8 k of one row: rows that exist in no launch are not fetched)
 #pragma unroll
     for (int i = 0; i < F; ++i) {
-      const int f = w + 8 * i, mt = f % MT, pl = (f / MT) & 1;
-      xu[i] = f / (2 * MT);
+      const int f = w + 8 * i, mt = f % MT;
+      xu[i] = f / MT;
       xlive[i] = m0 + mt * 16 + (lane & 15) < a.rows_live;
-      xsrc[i] = (const u32x4*)a.X + (size_t)pl * (a.x_plane / 8) + (size_t)min(mtile0 + mt, a.m_tiles - 1) * Kt * 64 + lane;
+      xsrc[i] = (const u32x4*)a.X + (size_t)min(mtile0 + mt, a.m_tiles - 1) * Kt * 64 + lane;
     }
     for (int c0 = t0; c0 < t1; c0 += 8 * NTW) {
       const int nt = c0 + NTW * w;
@@ -213,12 +210,11 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
           for (int j = 0; j < NTW; ++j) wv[j] = in_k ? r.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
-            const u32x4 h = xs[stage][(u * 2) * MT + mt][lane], l = xs[stage][(u * 2 + 1) * MT + mt][lane];
-            const uint4 xh = make_uint4(h.x, h.y, h.z, h.w), xl = make_uint4(l.x, l.y, l.z, l.w);
+            const u32x4 h = xs[stage][u * MT + mt][lane];
+            const uint4 xh = make_uint4(h.x, h.y, h.z, h.w);
 #pragma unroll
             for (int j = 0; j < NTW; ++j) {
-              acc[j][mt] = mfma_bf16(xh, wv[j], acc[j][mt]);
-              acc[j][mt] = mfma_bf16(xl, wv[j], acc[j][mt]);
+              acc[j][mt] = mfma_f16(xh, wv[j], acc[j][mt]);
             }
           }
         }
@@ -348,11 +344,11 @@ int lmhead_num_wg(int dtype, int V) {
   return n < 512 ? n : 512;
 }
 
-void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, const RowDesc& rd, int V, int K,
+void launch_lmhead(int dtype, const void* W, const void* X, size_t x_elems, const RowDesc& rd, int V, int K,
                    const SamplerArgs& sa, unsigned long long* part, int n_wg, int Mpad, float* logits_out, int max_rows,
                    hipStream_t s) {
   LmArgs a;
-  a.x_plane = x_plane;
+  a.x_elems = x_elems;
   a.W = W; a.X = X; a.rd = rd; a.V = V; a.K = K; a.Kt = (K + 31) / 32; a.n_tiles = (V + 15) / 16;
   a.sa = sa; a.part = part; a.Mpad = Mpad; a.logits_out = logits_out; a.m_tiles = 0; a.rows_live = max_rows;
   if (dtype == 0) {
@@ -360,14 +356,14 @@ void launch_lmhead(int dtype, const void* W, const void* X, size_t x_plane, cons
   } else if (max_rows <= 16) {
     hipLaunchKernelGGL(k_lmhead_bf16<1>, dim3(n_wg), dim3(512), 0, s, a);
   } else {
-    a.m_tiles = (int)(x_plane / ((size_t)a.Kt * 512));      // row tiles the activation buffer holds
+    a.m_tiles = (int)(x_elems / ((size_t)a.Kt * 512));      // row tiles the activation buffer holds
     const int tpw = (a.n_tiles + n_wg - 1) / n_wg;           // tiles per workgroup
 #define SPRINTER_LM(MT, KS1, KS2)                                                                       \
   do {                                                                                                  \
     if (tpw <= 8) hipLaunchKernelGGL((k_lmhead_wide<MT, 1, KS1>), dim3(n_wg), dim3(512), 0, s, a);      \
     else hipLaunchKernelGGL((k_lmhead_wide<MT, 2, KS2>), dim3(n_wg), dim3(512), 0, s, a);               \
   } while (0)
-    if (max_rows <= 32) SPRINTER_LM(2, 2, 2);
+    if (max_rows <= 32) SPRINTER_LM(2, 4, 4);                // (k tiles per stage: at least 8 fragments, one per wave)
     else if (max_rows <= 64) SPRINTER_LM(4, 2, 2);
     else SPRINTER_LM(8, 2, 1);                               // more than 128 rows: further passes inside the kernel
 #undef SPRINTER_LM

@@ -11,7 +11,8 @@
 namespace sprinter {
 
 // ================================================================ packing
-// [N, K] row-major bf16 -> operand tiles (zero padded to 16 rows x 32 k).
+// [N, K] row-major bf16 -> operand tiles of float16 (zero padded to 16 rows x 32 k).  A bf16 value has 8 significant
+// bits and converts exactly above 2^-14; smaller ones round to the float16 subnormal grid (2^-24 apart).
 __global__ __launch_bounds__(256) void k_pack_bf16(const bf16_t* __restrict__ w, uint4* __restrict__ out, int N, int K,
                                                    int Kt, size_t total) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -32,7 +33,11 @@ __global__ __launch_bounds__(256) void k_pack_bf16(const bf16_t* __restrict__ w,
       v = *reinterpret_cast<uint4*>(t);
     }
   }
-  out[i] = v;
+  const unsigned wd[4] = {v.x, v.y, v.z, v.w};
+  unsigned o[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = pk_f16(__uint_as_float(wd[e] << 16), __uint_as_float(wd[e] & 0xffff0000u));
+  out[i] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 void launch_pack_bf16(const void* w, void* out, int N, int K, hipStream_t s) {
   int Kt = (K + 31) / 32, Nt = (N + 15) / 16;
@@ -96,7 +101,7 @@ template <typename AT, int ARCH>
 __global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const float* __restrict__ g,
                                               const float* __restrict__ b, float eps, int d,
                                               const int* __restrict__ n_rows, AT* __restrict__ act_out,
-                                              size_t plane, float* __restrict__ f32_out) {
+                                              float* __restrict__ f32_out) {
   __shared__ float s4[4];
   int r = blockIdx.x;
   if (r >= *n_rows) return;
@@ -126,14 +131,14 @@ __global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const
     if (k < d) {
       float o = (v[i] - mean) * rstd * g[k];
       if (ARCH == 0) o += b[k];
-      act_store<AT>(act_out, plane, r, k, d, o);
+      act_store<AT>(act_out, r, k, d, o);
       if (f32_out) f32_out[(size_t)r * d + k] = o;
     }
   }
 }
 // bf16 output: one row per workgroup, one thread per 8 consecutive columns (= one 16-byte slot of an
-// operand tile per plane), so the row, gain and offset are requested with six 16-byte loads per thread
-// before anything is waited for and the result leaves as two 16-byte stores.  d <= 8192.
+// operand tile), so the row, gain and offset are requested with six 16-byte loads per thread
+// before anything is waited for and the result leaves as one 16-byte store of float16.  d <= 8192.
 // NI = 2048-column blocks per row (1, 2 or 4); SH = 0, or the most partial products a pending update of the
 // residual stream may consist of (4 or 8): the row is then h + bias + share 0 + share 1 + ..., added in that
 // order, written back and normalised.  The partial loads are issued with the others, before the row count
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(256) void k_norm(const float* __restrict__ h, const
 template <int ARCH, int NI, int SH>
 __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, const float* __restrict__ g,
                                                    const float* __restrict__ b, float eps, int d,
-                                                   const int* __restrict__ n_rows, bf16_t* __restrict__ act_out, size_t plane,
+                                                   const int* __restrict__ n_rows, bf16_t* __restrict__ act_out,
                                                    float* __restrict__ f32_out, NormPending pend) {
   __shared__ float s4[4];
   const int r = blockIdx.x, tid = threadIdx.x;
@@ -219,15 +224,10 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
         o[e] = (x[i][e] - mean) * rstd * gg[i][e];
         if (ARCH == 0) o[e] += bb[i][e];
       }
-      uint4 hi, lo;
-      split2(o[0], o[1], hi.x, lo.x);
-      split2(o[2], o[3], hi.y, lo.y);
-      split2(o[4], o[5], hi.z, lo.z);
-      split2(o[6], o[7], hi.w, lo.w);
+      const uint4 ov = make_uint4(pk_f16(o[0], o[1]), pk_f16(o[2], o[3]), pk_f16(o[4], o[5]), pk_f16(o[6], o[7]));
       const int k = c * 8;
       const size_t slot = ((size_t)(r >> 4) * Kt + (k >> 5)) * 512 + ((((k & 31) >> 3) << 4) + (r & 15)) * 8;
-      *reinterpret_cast<uint4*>(act_out + slot) = hi;
-      *reinterpret_cast<uint4*>(act_out + plane + slot) = lo;
+      *reinterpret_cast<uint4*>(act_out + slot) = ov;
       if (f32_out) {
         *reinterpret_cast<float4*>(f32_out + (size_t)r * d + k) = make_float4(o[0], o[1], o[2], o[3]);
         *reinterpret_cast<float4*>(f32_out + (size_t)r * d + k + 4) = make_float4(o[4], o[5], o[6], o[7]);
@@ -238,8 +238,8 @@ __global__ __launch_bounds__(256) void k_norm_bf16(const float* __restrict__ h, 
 
 template <int ARCH, int NI>
 static void launch_norm_bf16(const float* h, const float* g, const float* b, float eps, int d, const int* n_rows,
-                             bf16_t* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s, const NormPending& np) {
-#define SPRINTER_NORM(SH) hipLaunchKernelGGL((k_norm_bf16<ARCH, NI, SH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, act_out, plane, f32_out, np)
+                             bf16_t* act_out, float* f32_out, int max_rows, hipStream_t s, const NormPending& np) {
+#define SPRINTER_NORM(SH) hipLaunchKernelGGL((k_norm_bf16<ARCH, NI, SH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, act_out, f32_out, np)
   if (np.shares <= 0) SPRINTER_NORM(0);
   else if (np.shares <= 4) SPRINTER_NORM(4);
   else SPRINTER_NORM(8);
@@ -247,24 +247,24 @@ static void launch_norm_bf16(const float* h, const float* g, const float* b, flo
 }
 
 void launch_norm(int dtype, int arch, const float* h, const float* g, const float* b, float eps, int d,
-                 const int* n_rows, void* act_out, size_t plane, float* f32_out, int max_rows, hipStream_t s,
+                 const int* n_rows, void* act_out, float* f32_out, int max_rows, hipStream_t s,
                  const NormPending* pend) {
   NormPending np;
   memset(&np, 0, sizeof np);
   if (pend) np = *pend;
 #define NORM_CASE(AT, ARCH) \
-  hipLaunchKernelGGL((k_norm<AT, ARCH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (AT*)act_out, plane, f32_out)
+  hipLaunchKernelGGL((k_norm<AT, ARCH>), dim3(max_rows), dim3(256), 0, s, h, g, b, eps, d, n_rows, (AT*)act_out, f32_out)
   if (dtype == 0) { if (arch == 0) NORM_CASE(float, 0); else NORM_CASE(float, 1); }
   else if (d % 8 == 0 && d <= 8192) {
     bf16_t* out = (bf16_t*)act_out;
     if (arch == 0) {
-      if (d <= 2048) launch_norm_bf16<0, 1>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
-      else if (d <= 4096) launch_norm_bf16<0, 2>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
-      else launch_norm_bf16<0, 4>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+      if (d <= 2048) launch_norm_bf16<0, 1>(h, g, b, eps, d, n_rows, out, f32_out, max_rows, s, np);
+      else if (d <= 4096) launch_norm_bf16<0, 2>(h, g, b, eps, d, n_rows, out, f32_out, max_rows, s, np);
+      else launch_norm_bf16<0, 4>(h, g, b, eps, d, n_rows, out, f32_out, max_rows, s, np);
     } else {
-      if (d <= 2048) launch_norm_bf16<1, 1>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
-      else if (d <= 4096) launch_norm_bf16<1, 2>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
-      else launch_norm_bf16<1, 4>(h, g, b, eps, d, n_rows, out, plane, f32_out, max_rows, s, np);
+      if (d <= 2048) launch_norm_bf16<1, 1>(h, g, b, eps, d, n_rows, out, f32_out, max_rows, s, np);
+      else if (d <= 4096) launch_norm_bf16<1, 2>(h, g, b, eps, d, n_rows, out, f32_out, max_rows, s, np);
+      else launch_norm_bf16<1, 4>(h, g, b, eps, d, n_rows, out, f32_out, max_rows, s, np);
     }
   }
   else            { if (arch == 0) NORM_CASE(bf16_t, 0); else NORM_CASE(bf16_t, 1); }
