@@ -669,7 +669,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_elems, const int* n_
   const int passes = (row_tiles + 3) / 4;
   const int mt = std::max(2, (row_tiles + passes - 1) / passes);
   int ntw = 4, groups = (a.n_tiles + 3) / 4, sk = std::min(s_max, std::max(1, 256 / groups));
-  if (groups * sk < 192) { ntw = 2; groups = (a.n_tiles + 1) / 2; sk = std::min(s_max, std::max(1, 256 / groups)); }
+  if (groups * sk < 192 || mt == 4) { ntw = 2; groups = (a.n_tiles + 1) / 2; sk = std::min(s_max, std::max(1, 256 / groups)); }
   a.SK = sk;
   const dim3 grid(groups, passes, sk);
   if (ntw == 4) { if (mt == 2) SPRINTER_PART(2, 4); else if (mt == 3) SPRINTER_PART(3, 4); else SPRINTER_PART(4, 4); }

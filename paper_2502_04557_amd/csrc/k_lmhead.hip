@@ -140,8 +140,7 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
 // tiles are clamped to the m_tiles the activation buffer holds.  More than 16 MT rows take further passes.
 template <int MT, int NTW, int KS>
 __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) {
-  constexpr int NF = KS * MT, F = NF / 8;
-  static_assert(NF % 8 == 0, "every wave stages the same number of fragments");
+  constexpr int NF = KS * MT, F = (NF + 7) / 8;             // fragments per stage, per wave (with fewer than 8 the last waves stage none)
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   __shared__ u32x4 xs[2][NF][64];
   __shared__ u64 sbest[8][MT * 16];
@@ -173,7 +172,7 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
     for (int i = 0; i < F; ++i) {
       const int f = w + 8 * i, mt = f % MT;
       xu[i] = f / MT;
-      xlive[i] = m0 + mt * 16 + (lane & 15) < a.rows_live;
+      xlive[i] = f < NF && m0 + mt * 16 + (lane & 15) < a.rows_live;
       xsrc[i] = (const u32x4*)a.X + (size_t)min(mtile0 + mt, a.m_tiles - 1) * Kt * 64 + lane;
     }
     for (int c0 = t0; c0 < t1; c0 += 8 * NTW) {
@@ -194,7 +193,8 @@ __global__ __launch_bounds__(512, MT <= 4 ? 4 : 2) void k_lmhead_wide(LmArgs a) 
       };
       auto sstore = [&](int stage, const Regs& r) {
 #pragma unroll
-        for (int i = 0; i < F; ++i) xs[stage][w + 8 * i][lane] = r.x[i];
+        for (int i = 0; i < F; ++i)
+          if (w + 8 * i < NF) xs[stage][w + 8 * i][lane] = r.x[i];
       };
       f32x4 acc[NTW][MT];
 #pragma unroll
@@ -363,7 +363,7 @@ void launch_lmhead(int dtype, const void* W, const void* X, size_t x_elems, cons
     if (tpw <= 8) hipLaunchKernelGGL((k_lmhead_wide<MT, 1, KS1>), dim3(n_wg), dim3(512), 0, s, a);      \
     else hipLaunchKernelGGL((k_lmhead_wide<MT, 2, KS2>), dim3(n_wg), dim3(512), 0, s, a);               \
   } while (0)
-    if (max_rows <= 32) SPRINTER_LM(2, 4, 4);                // (k tiles per stage: at least 8 fragments, one per wave)
+    if (max_rows <= 32) SPRINTER_LM(2, 2, 2);
     else if (max_rows <= 64) SPRINTER_LM(4, 2, 2);
     else SPRINTER_LM(8, 2, 1);                               // more than 128 rows: further passes inside the kernel
 #undef SPRINTER_LM
