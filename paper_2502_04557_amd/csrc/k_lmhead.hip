@@ -29,7 +29,8 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
   const uint4* __restrict__ Xp = (const uint4*)a.X + lane;
   const int Kt = a.Kt;
   const int n_rows = *a.rd.n_rows;
-  struct Buf { uint4 w[2], xh[MT]; };
+  constexpr int U = 2;                                    // k tiles per register buffer
+  struct Buf { uint4 w[U][2], xh[U][MT]; };
   for (int m0 = 0; m0 < n_rows; m0 += MT * 16) {
     const int mtile0 = m0 >> 4;
     u64 best[MT][4];
@@ -45,13 +46,17 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
     for (int nt = t0 + 2 * w; nt < t1; nt += 16) {
       const size_t wrow0 = (size_t)nt * Kt * 64, wrow1 = (size_t)min(nt + 1, t1 - 1) * Kt * 64;
       auto load = [&](Buf& b, int kt) {
-        const int kc = min(kt, Kt - 1);
-        b.w[0] = Wp[wrow0 + (size_t)kc * 64];
-        b.w[1] = Wp[wrow1 + (size_t)kc * 64];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int kc = min(kt + u, Kt - 1);
+          b.w[u][0] = Wp[wrow0 + (size_t)kc * 64];
+          b.w[u][1] = Wp[wrow1 + (size_t)kc * 64];
+        }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {                 // (a lane holds 8 k of one row: rows that exist in no launch are not fetched,
           if (m0 + mt * 16 + (lane & 15) < a.rows_live) { //  what the registers hold for them only reaches logits that are dropped)
-            b.xh[mt] = Xp[((size_t)(mtile0 + mt) * Kt + kc) * 64];
+#pragma unroll
+            for (int u = 0; u < U; ++u) b.xh[u][mt] = Xp[((size_t)(mtile0 + mt) * Kt + min(kt + u, Kt - 1)) * 64];
           }
         }
       };
@@ -61,28 +66,31 @@ __global__ __launch_bounds__(512) void k_lmhead_bf16(LmArgs a) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[j][mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
       auto compute = [&](const Buf& b, int kt) {
-        const bool in_k = kt < Kt;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const uint4 wj = in_k ? b.w[j] : make_uint4(0u, 0u, 0u, 0u);
+        for (int u = 0; u < U; ++u) {
+          const bool in_k = kt + u < Kt;
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            acc[j][mt] = mfma_f16(b.xh[mt], wj, acc[j][mt]);
+          for (int j = 0; j < 2; ++j) {
+            const uint4 wj = in_k ? b.w[u][j] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[j][mt] = mfma_f16(b.xh[u][mt], wj, acc[j][mt]);
           }
         }
       };
       Buf A, B;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) A.xh[mt] = B.xh[mt] = make_uint4(0u, 0u, 0u, 0u);
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) A.xh[u][mt] = B.xh[u][mt] = make_uint4(0u, 0u, 0u, 0u);
       load(A, 0);
-      for (int kt = 0; kt < Kt; kt += 2) {
-        load(B, kt + 1);
+      for (int kt = 0; kt < Kt; kt += 2 * U) {
+        load(B, kt + U);
         __builtin_amdgcn_sched_barrier(0);
         compute(A, kt);
         __builtin_amdgcn_sched_barrier(0);
-        load(A, kt + 2);
+        load(A, kt + 2 * U);
         __builtin_amdgcn_sched_barrier(0);
-        compute(B, kt + 1);
+        compute(B, kt + U);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
