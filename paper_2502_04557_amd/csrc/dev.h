@@ -52,7 +52,8 @@ template <> __device__ __forceinline__ void act_store<bf16_t>(bf16_t* base, int 
   base[act_idx<bf16_t>(m, k, K)] = f2h(v);
 }
 
-// Two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even), and the hi + lo split of a pair.
+// Two floats -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even), and the hi + lo split of a pair (the
+// attention kernels keep the query and the probabilities as two bf16 operands next to the bf16 keys / values).
 typedef float f2v __attribute__((ext_vector_type(2)));
 typedef __bf16 b2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned pk_bf16(float a, float b) {

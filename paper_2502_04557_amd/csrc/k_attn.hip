@@ -192,7 +192,7 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // bf16 single-query attention on the matrix cores: one workgroup of NW waves per (row, KV head); the G query heads
 // that share the KV head are rows of one 16-row operand, so a cached key costs the same whatever G is and the
 // kernel is left with streaming the cache.  Wave w takes the 32-key blocks w, w + NW, ...; per block
-// S = Q K^T (Q rotated, scaled and split into hi + lo bf16 planes in registers, so it enters at float32
+// S = Q K^T (Q rotated, scaled and split into hi + lo bf16 planes in LDS, so it enters at float32
 // precision; K fragments straight from the cache), online softmax in float32 on the accumulator layout (the 16 keys
 // of a tile sit in one DPP row), P through a wave-private piece of LDS into operand layout (hi + lo), V^T tiles
 // straight from the cache, O += P V.  A block's keys and value tiles are requested a whole step ahead (two register

@@ -27,7 +27,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int n_rows, int
 }
 
 
-// bf16 GEMM on MFMA for at most 16 rows.  512 threads = 8 waves that split K; each wave owns NTW column tiles
+// bf16-mode GEMM (float16 operands) on MFMA for at most 16 rows.  512 threads = 8 waves that split K; each wave owns NTW column tiles
 // (16 columns each): D[m][n] += X[m][k] W[n][k].
 // All 8 waves leave their partial sums in LDS and every thread then finishes ONE output element: it adds the 8
 // partials in fixed order, applies bias / residual / GELU / SwiGLU and stores.  With the element order chosen per
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(512) void k_gemm16(GemmArgs a) {
   gemm_epilogue<EPI, bf16_t>(a, n_rows, m, n, s1, s2, pbias, pres);
 }
 
-// bf16 GEMM for 17 .. 64 rows per pass (MT row tiles of 16), one column tile per workgroup, K split over
+// bf16-mode GEMM for 17 .. 64 rows per pass (MT row tiles of 16), one column tile per workgroup, K split over
 // the 8 waves.  At these row counts a workgroup pulls the whole activation matrix (MT x 1 KiB per k tile,
 // from L2) for 1 KiB of weights per k tile, so the kernel lives on memory-level parallelism: two register
 // buffers, the loads of chunk c + 1 (weights and all MT row tiles) are in flight while the
@@ -292,7 +292,7 @@ __global__ __launch_bounds__(512) void k_gemm_rows(GemmArgs a) {
   }
 }
 
-// bf16 GEMM for 128+ rows (prefill chunks, long work lists): the 8 waves of a workgroup split the COLUMNS (NTW
+// bf16-mode GEMM for 128+ rows (prefill chunks, long work lists): the 8 waves of a workgroup split the COLUMNS (NTW
 // column tiles each; SwiGLU: one gate + one up tile) and share the activations of 8 row tiles (128 rows) through LDS,
 // so a k tile costs the workgroup 8 KiB of activations (once) + 8 * NWT KiB of weights for
 // 8 * NWT * 8 MFMAs - far fewer bytes per MFMA than the K-split kernel above, which reads every operand per wave.
@@ -437,7 +437,7 @@ static bool try_gemm_wide(const GemmArgs& a, int max_rows, int sk, hipStream_t s
   return true;
 }
 
-// bf16 GEMM for at most 16 rows whose output only has to exist as a sum: O-proj and FFN-down add into the
+// bf16-mode GEMM for at most 16 rows whose output only has to exist as a sum: O-proj and FFN-down add into the
 // residual stream, and the layer norm that follows reads the whole row anyway.  K is split into SK shares
 // over workgroups (workgroup = NTW column tiles x one share), each share leaves its partial product in
 // part[s] and the norm kernel adds residual + bias + the shares in fixed order.  No reduction step, no
@@ -642,7 +642,7 @@ int launch_gemm_part(const void* W, const void* X, size_t x_elems, const int* n_
     else hipLaunchKernelGGL((k_gemm16_part<1>), dim3(groups * sk), dim3(512), 0, s, a);
     return sk;
   }
-  // 17+ rows: the workgroup's activation traffic (2 KiB per k tile and 16 rows) is what costs, so a wave takes
+  // 17+ rows: the workgroup's activation traffic (1 KiB per k tile and 16 rows) is what costs, so a wave takes
   // four column tiles (two if that leaves too few workgroups) and K is split until about 256 workgroups exist,
   // with at least two k tiles per wave and share
   if (max_rows >= 97) {            // 97+ rows: column-split workgroups, K shares until about 256 of them exist
