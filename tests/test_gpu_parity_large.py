@@ -204,7 +204,8 @@ def test_c3_full_size_sampled_rows(llama7b, ctx, rej):
     if rej == W.REJECT_SD:
         assert st["coin_kept"] == int(((g["accept"] == 0) & (g["tok"] == g["draft_tok"])).sum())
     rng = np.random.default_rng(3)
-    rows = sorted({0, cfg.batch - 1, int(rng.integers(1, cfg.batch - 1))})
+    n_seeded = 4 if (ctx, rej) == (0, 0) else 1               # default modes: first, last and four seeded rows
+    rows = sorted({0, cfg.batch - 1, *rng.choice(np.arange(1, cfg.batch - 1), n_seeded, replace=False).tolist()})
     tot = _replay_segments(s, g, rows, [(cfg.tau, b2_0)] * n1 + [(cfg.tau, b2)] * n2)
     assert tot["rejected"] > 0
     s.close()
